@@ -1,0 +1,256 @@
+/*
+ * flexshard.h -- C ABI of libflexshard_hip.so
+ *
+ * The tiered sequence-embedding lookup behind FlexShard's per-row sharding
+ * (arXiv 2301.02959), taken at one GPU's share of the work:
+ *
+ *   jagged ids -> per-row placement (tier, owner) -> stable bucketize by owner
+ *   -> unpooled sequence gather -> duplicate-row gradient accumulation,
+ *   plus the row-frequency histogram and top-k-under-budget choice of the
+ *   rows to replicate.
+ *
+ * The paper describes the placement (Sections 3.1, 4.3-4.6) and the cost of
+ * each stage (Section 3.2, the six per-GPU metrics and the two cost tables);
+ * it describes no kernel.  The operations below are the stages those metrics
+ * name, written as plain array operations.
+ *
+ * Conventions for every entry point
+ *   - Every pointer is DEVICE memory owned by the caller unless the comment
+ *     says "host".  The library allocates nothing, frees nothing and keeps no
+ *     state between calls (the opt-in profiling hooks at the end excepted).
+ *   - All work is enqueued on `stream` (a hipStream_t passed as void*; NULL is
+ *     the default stream).  No entry point synchronises with the host.
+ *   - `workspace == NULL`: the required scratch size is written to
+ *     `*workspace_bytes` (host), nothing is launched, FS_OK is returned.
+ *     Otherwise `*workspace_bytes` is the size of the buffer passed in and
+ *     must be at least the required size (else FS_ERR_WORKSPACE).  The
+ *     workspace must be 256-byte aligned.
+ *   - Faults the host can see return an fs_status at once and launch nothing.
+ *     Faults only the data shows OR a bit into `*dev_status` (a caller-owned
+ *     int32 in device memory that the library never clears) and keep every
+ *     access in bounds.  `dev_status` may be NULL: then nothing is reported.
+ *   - n == 0 (or an empty [j0, j1) range) is legal everywhere.
+ *   - 0 <= n < 2^31, 0 < R < 2^32 - 1.
+ */
+#ifndef FLEXSHARD_H
+#define FLEXSHARD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    FS_OK = 0,
+    FS_ERR_NULL = 1,      /* a required pointer is NULL */
+    FS_ERR_SIZE = 2,      /* negative / overflowing / inconsistent size */
+    FS_ERR_DTYPE = 3,     /* unknown fs_dtype */
+    FS_ERR_ALIGN = 4,     /* row bytes not a multiple of 16, or base not 16-B aligned */
+    FS_ERR_WORKSPACE = 5, /* workspace too small or misaligned */
+    FS_ERR_CONFIG = 6,    /* U, W, self, flags, variant out of range */
+    FS_ERR_DEVICE = 7     /* a HIP call failed */
+} fs_status;
+
+typedef enum { FS_F32 = 0, FS_F16 = 1, FS_BF16 = 2 } fs_dtype;
+
+/* Bits OR-ed into *dev_status. */
+enum {
+    FS_DEV_BAD_ID = 1,         /* id outside its table / row or pos outside range */
+    FS_DEV_BAD_OFFSETS = 2,    /* offsets[0] != 0, decreasing, or offsets[T*B] != n */
+    FS_DEV_BAD_PLACEMENT = 4,  /* tier 3, or owner outside its range */
+    FS_DEV_COUNT_OVERFLOW = 8, /* a histogram count saturated at 2^32 - 1 */
+    FS_DEV_UNIQUE_OVERFLOW = 16, /* more distinct rows than cap_unique */
+    FS_DEV_POS_ORDER = 32      /* bwd: equal rows whose pos is not ascending in j */
+};
+
+/*
+ * Placement entry, one uint32 per global row g (Sections 4.3-4.5: every row
+ * is in exactly one of three tiers):
+ *   bits 31..30  tier   0 replicated on every GPU        ("DP")
+ *                       1 replicated once per group      ("Flex": sharded
+ *                         over the W GPUs of a group, each shard replicated
+ *                         across the U/W groups)
+ *                       2 sharded over all U GPUs        ("RW")
+ *                       3 invalid
+ *   bits 29..0   owner  tier 2: bucket in [0, U); tier 1: index in [0, W)
+ *                       inside the requester's group; tier 0: ignored.
+ */
+#define FS_TIER_SHIFT 30
+#define FS_OWNER_MASK 0x3FFFFFFFu
+#define FS_TIER_GLOBAL 0u
+#define FS_TIER_GROUP 1u
+#define FS_TIER_SHARDED 2u
+
+/* Number of sorted lookups per partial sum in the backward's canonical
+ * summation order (see fs_seq_grad_bwd). */
+#define FS_BWD_TILE 256
+
+#define FS_MAX_BUCKETS 4096
+
+/*
+ * fs_route_bucketize -- input-ID distribution (Section 3.2, metric 2 "input
+ * data distribution": the ids that must reach their owners before any lookup;
+ * tier semantics from Sections 3.1, 4.4, 4.5).
+ *
+ *   ids[n], offsets[T*B + 1]   jagged batch, table-major: segment t*B + b holds
+ *                              sample b of table t; ids are table-local.
+ *   row_base[T + 1]            row_base[t] = first global row of table t,
+ *                              row_base[T] = R.
+ *   placement[R]               see above.
+ *   n                          host copy of offsets[T*B].
+ *   U, W, self                 buckets, group width (U % W == 0), own bucket.
+ *
+ * For lookup i in table t:  g = row_base[t] + ids[i];
+ *   dest = self                     (tier 0: served from the local replica)
+ *        = (self / W) * W + owner   (tier 1: served inside the own group)
+ *        = owner                    (tier 2)
+ * Outputs: bucket_offsets[U + 1] (exclusive scan of per-bucket counts,
+ * bucket_offsets[U] = n); out_rows[n] = g and out_pos[n] = i, bucket-major and
+ * in ascending i inside a bucket (a stable counting sort by dest);
+ * tier_counts[3] (may be NULL) = lookups per tier, overwritten.
+ *
+ * Data faults: an id outside [0, E_t) is routed as row row_base[t]
+ * (FS_DEV_BAD_ID); tier 3, owner >= U (tier 2) or owner >= W (tier 1) is
+ * routed to `self` (FS_DEV_BAD_PLACEMENT; tier 3 is counted under tier 0);
+ * bad offsets set FS_DEV_BAD_OFFSETS and leave the outputs unspecified but
+ * written in bounds.
+ * Host faults: NULL -> FS_ERR_NULL; n < 0, n >= 2^31, T < 1, B < 1,
+ * T*B >= 2^31 -> FS_ERR_SIZE; U < 1, U > FS_MAX_BUCKETS, W < 1, U % W != 0,
+ * self outside [0, U) -> FS_ERR_CONFIG.
+ */
+fs_status fs_route_bucketize(
+    const int64_t* ids, const int64_t* offsets, int32_t T, int32_t B,
+    const int64_t* row_base, const uint32_t* placement,
+    int64_t n, int32_t U, int32_t W, int32_t self,
+    int64_t* bucket_offsets, int64_t* out_rows, int32_t* out_pos,
+    int64_t* tier_counts,
+    void* workspace, size_t* workspace_bytes /* host */,
+    void* stream, int32_t* dev_status);
+
+/*
+ * fs_seq_gather_fwd -- unpooled sequence lookup (Section 2, "Embedding
+ * Pooling": every looked-up row is materialised; Section 3.2 metrics 3 and 4,
+ * "rows accessed" and "dynamic memory").
+ *
+ *   weights[R, D] row-major, `dtype`; rows[*], pos[*] as written by
+ *   fs_route_bucketize; for j in [j0, j1): out[pos[j], :] = weights[rows[j], :]
+ *   (a bit copy).  out is [n, D]; rows of out whose index is not in
+ *   pos[j0..j1) are left untouched.
+ *
+ * Data faults: rows[j] outside [0, R) or pos[j] outside [0, n): that j is
+ * skipped (FS_DEV_BAD_ID).
+ * Host faults: NULL; R < 1, n < 0, D < 1, j0 < 0, j0 > j1 (FS_ERR_SIZE);
+ * D * sizeof(dtype) not a multiple of 16 or weights/out not 16-byte aligned
+ * (FS_ERR_ALIGN).
+ */
+fs_status fs_seq_gather_fwd(
+    const void* weights, int64_t R, int32_t D, fs_dtype dtype,
+    const int64_t* rows, const int32_t* pos, int64_t j0, int64_t j1,
+    void* out, int64_t n, void* stream, int32_t* dev_status);
+
+/*
+ * fs_seq_grad_bwd -- backward of the sequence lookup (Section 3.2 metrics 4-6:
+ * the gradient of every materialised row flows back to the row's owner, where
+ * duplicates of one row are summed before the update).
+ *
+ *   grad_out[n, D] in `dtype`; for every distinct row r among rows[j0..j1):
+ *       row_grads[u(r), :] = sum over {j : rows[j] == r} of f32(grad_out[pos[j], :])
+ *   uniq_rows[u] ascending, u(r) its rank; *num_unique = number of distinct
+ *   rows.  uniq_rows and row_grads hold cap_unique rows; if there are more
+ *   distinct rows, the first cap_unique are written, *num_unique is still the
+ *   true count and FS_DEV_UNIQUE_OVERFLOW is set.
+ *
+ * Summation order (fp32, round-to-nearest-even, no fused multiply-add,
+ * subnormals kept).  Sort the lookups by (row asc, pos asc), k = 0 .. m-1 the
+ * sorted index, m = j1 - j0.  A partial sum starts at the first k of each
+ * row's run and at every k that is a multiple of FS_BWD_TILE; a partial is
+ * accumulated left to right starting from its first term; the row's gradient
+ * is the left-to-right sum of its partials.
+ *   variant 0: exactly that order, bit for bit, on every run.
+ *   variant 1: partials as above, combined with fp32 atomic adds in arbitrary
+ *              order: within 1e-5 of the fp64 sum, relative to
+ *              max(|sum|, 2-norm of the terms), per element.
+ *
+ * Precondition (true of every fs_route_bucketize output and any [j0, j1) of
+ * it): lookups of one row appear with ascending pos in j order.  A violation
+ * sets FS_DEV_POS_ORDER and the sums of that row follow j order instead.
+ *
+ * Data faults: rows[j] outside [0, R) or pos[j] outside [0, n) is replaced by
+ * row 0 / pos 0 (FS_DEV_BAD_ID), result unspecified but in bounds.
+ * Host faults: as fs_seq_gather_fwd; R >= 2^32 - 1, cap_unique < 0
+ * (FS_ERR_SIZE); variant not 0/1 (FS_ERR_CONFIG).
+ */
+fs_status fs_seq_grad_bwd(
+    const void* grad_out, int64_t n, int32_t D, fs_dtype dtype,
+    const int64_t* rows, const int32_t* pos, int64_t j0, int64_t j1, int64_t R,
+    int32_t variant,
+    int64_t* uniq_rows, float* row_grads, int64_t cap_unique, int64_t* num_unique,
+    void* workspace, size_t* workspace_bytes /* host */,
+    void* stream, int32_t* dev_status);
+
+/*
+ * fs_plan_replication -- profile and choose the rows to replicate
+ * (Section 4.1: per-row appearance counts; Section 4.3: rows are taken in
+ * descending frequency order and, for a given amount of extra memory, the
+ * best hybrid is the prefix that fits; Section 4.6: several tables are merged
+ * into one distribution).
+ *
+ *   flags & FS_PLAN_ACCUMULATE  counts[row_base[t] + ids[i]] += 1 for every
+ *                               lookup of the jagged sample (ids, offsets, T, B
+ *                               as in fs_route_bucketize; counts is in/out, so
+ *                               calls accumulate).  A count that would pass
+ *                               2^32 - 1 stays there (FS_DEV_COUNT_OVERFLOW).
+ *   flags & FS_PLAN_SELECT      order rows by (count desc, g asc); candidates
+ *                               are rows with count > 0 (all rows with
+ *                               FS_PLAN_ALLOW_ZERO);
+ *                               k = min(budget_bytes / bytes_per_row, #candidates);
+ *                               sel_rows[0..k) = the first k in that order,
+ *                               *num_selected = k.  sel_rows holds
+ *                               min(R, budget_bytes / bytes_per_row) entries.
+ *   flags & FS_PLAN_TAG         (with SELECT) the tier bits of placement[g]
+ *                               are set to 0 for the k selected rows.
+ * Pointers a flag does not use may be NULL.
+ * Host faults: NULL; n, R, T, B as above; budget_bytes < 0 or
+ * bytes_per_row < 1 (FS_ERR_SIZE); unknown flag bits, TAG without SELECT
+ * (FS_ERR_CONFIG).
+ */
+#define FS_PLAN_ACCUMULATE 1
+#define FS_PLAN_SELECT 2
+#define FS_PLAN_TAG 4
+#define FS_PLAN_ALLOW_ZERO 8
+
+fs_status fs_plan_replication(
+    const int64_t* ids, const int64_t* offsets, int32_t T, int32_t B,
+    const int64_t* row_base, int64_t n, int64_t R,
+    uint32_t* counts, int32_t flags,
+    int64_t budget_bytes, int64_t bytes_per_row,
+    int64_t* sel_rows, int64_t* num_selected,
+    uint32_t* placement,
+    void* workspace, size_t* workspace_bytes /* host */,
+    void* stream, int32_t* dev_status);
+
+/* ---- helpers ---------------------------------------------------------- */
+
+/* Library version, major * 1000 + minor. */
+int32_t fs_version(void);
+
+/* FS_BWD_TILE as compiled into the library. */
+int32_t fs_bwd_tile(void);
+
+/*
+ * Opt-in per-kernel timing.  fs_prof_begin(max_records) makes every later
+ * kernel launch of this library (on any stream) bracketed by a pair of HIP
+ * events; fs_prof_end() synchronises those events, writes up to `cap` records
+ * (kernel name, NUL-terminated, 48 bytes each, into names; milliseconds into
+ * ms; all host memory), returns the number of records taken and switches
+ * timing off.  Not thread-safe; for benchmarks only.
+ */
+fs_status fs_prof_begin(int32_t max_records);
+int32_t fs_prof_end(char* names /* host, cap*48 */, float* ms /* host */, int32_t cap);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLEXSHARD_H */
