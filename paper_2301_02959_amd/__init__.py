@@ -1,0 +1,196 @@
+"""Thin Python binding of libflexshard_hip.so (argument marshalling only).
+
+Every function has the name and the arguments of the C entry point declared in
+include/flexshard.h; tensors are torch CUDA tensors whose device pointers are
+passed through, the stream is torch's current stream.  Nothing is computed
+here, and there is no fallback: without the built library every call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Tuple
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libflexshard_hip.so")
+
+FS_F32, FS_F16, FS_BF16 = 0, 1, 2
+FS_DEV_BAD_ID, FS_DEV_BAD_OFFSETS, FS_DEV_BAD_PLACEMENT = 1, 2, 4
+FS_DEV_COUNT_OVERFLOW, FS_DEV_UNIQUE_OVERFLOW, FS_DEV_POS_ORDER = 8, 16, 32
+FS_PLAN_ACCUMULATE, FS_PLAN_SELECT, FS_PLAN_TAG, FS_PLAN_ALLOW_ZERO = 1, 2, 4, 8
+FS_BWD_TILE = 256
+FS_MAX_BUCKETS = 4096
+
+STATUS_NAMES = {0: "FS_OK", 1: "FS_ERR_NULL", 2: "FS_ERR_SIZE", 3: "FS_ERR_DTYPE", 4: "FS_ERR_ALIGN",
+                5: "FS_ERR_WORKSPACE", 6: "FS_ERR_CONFIG", 7: "FS_ERR_DEVICE"}
+
+EXPORTS = ["fs_route_bucketize", "fs_seq_gather_fwd", "fs_seq_grad_bwd", "fs_plan_replication",
+           "fs_version", "fs_bwd_tile", "fs_prof_begin", "fs_prof_end"]
+
+_DTYPES = {torch.float32: FS_F32, torch.float16: FS_F16, torch.bfloat16: FS_BF16}
+
+_lib: Optional[ctypes.CDLL] = None
+
+
+class FlexShardError(RuntimeError):
+    def __init__(self, fn: str, code: int):
+        super().__init__(f"{fn} returned {STATUS_NAMES.get(code, code)}")
+        self.code = code
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded HIP library; raises if it has not been built (no fallback exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2301_02959_amd.build` "
+                "(hipcc, gfx950); this package has no other code path")
+        _lib = ctypes.CDLL(LIB_PATH)
+        for name in ("fs_route_bucketize", "fs_seq_gather_fwd", "fs_seq_grad_bwd", "fs_plan_replication",
+                     "fs_prof_begin"):
+            getattr(_lib, name).restype = ctypes.c_int
+        _lib.fs_version.restype = ctypes.c_int32
+        _lib.fs_bwd_tile.restype = ctypes.c_int32
+        _lib.fs_prof_end.restype = ctypes.c_int32
+    return _lib
+
+
+def _ptr(t: Optional[torch.Tensor]) -> ctypes.c_void_p:
+    if t is None:
+        return ctypes.c_void_p(0)
+    assert t.is_contiguous(), "tensors must be contiguous"
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream() -> ctypes.c_void_p:
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(fn: str, code: int, raise_on_error: bool) -> int:
+    if code != 0 and raise_on_error:
+        raise FlexShardError(fn, code)
+    return code
+
+
+def _workspace(query, device) -> Tuple[torch.Tensor, ctypes.c_size_t]:
+    """Ask the entry point for its scratch size, then allocate it through torch."""
+    size = ctypes.c_size_t(0)
+    code = query(ctypes.c_void_p(0), ctypes.byref(size))
+    if code != 0:
+        return None, size, code
+    ws = torch.empty(max(int(size.value), 256), dtype=torch.uint8, device=device)
+    return ws, ctypes.c_size_t(ws.numel()), 0
+
+
+def fs_route_bucketize(ids, offsets, T: int, B: int, row_base, placement, n: int, U: int, W: int, self_: int,
+                       bucket_offsets, out_rows, out_pos, tier_counts=None, dev_status=None,
+                       workspace: Optional[torch.Tensor] = None, raise_on_error: bool = True) -> int:
+    L = lib()
+
+    def call(ws_ptr, ws_size_ref):
+        return L.fs_route_bucketize(
+            _ptr(ids), _ptr(offsets), ctypes.c_int32(T), ctypes.c_int32(B), _ptr(row_base), _ptr(placement),
+            ctypes.c_int64(n), ctypes.c_int32(U), ctypes.c_int32(W), ctypes.c_int32(self_),
+            _ptr(bucket_offsets), _ptr(out_rows), _ptr(out_pos), _ptr(tier_counts),
+            ws_ptr, ws_size_ref, _stream(), _ptr(dev_status))
+
+    if workspace is None:
+        workspace, size, code = _workspace(call, offsets.device)
+        if code != 0:
+            return _check("fs_route_bucketize", code, raise_on_error)
+    else:
+        size = ctypes.c_size_t(workspace.numel())
+    return _check("fs_route_bucketize", call(_ptr(workspace), ctypes.byref(size)), raise_on_error)
+
+
+def route_workspace_bytes(T: int, B: int, n: int, U: int, W: int, self_: int) -> int:
+    size = ctypes.c_size_t(0)
+    z = ctypes.c_void_p(0)
+    code = lib().fs_route_bucketize(z, z, ctypes.c_int32(T), ctypes.c_int32(B), z, z, ctypes.c_int64(n),
+                                    ctypes.c_int32(U), ctypes.c_int32(W), ctypes.c_int32(self_), z, z, z, z,
+                                    z, ctypes.byref(size), z, z)
+    _check("fs_route_bucketize", code, True)
+    return int(size.value)
+
+
+def fs_seq_gather_fwd(weights, rows, pos, j0: int, j1: int, out, dev_status=None,
+                      raise_on_error: bool = True, R: Optional[int] = None, D: Optional[int] = None,
+                      dtype: Optional[int] = None, n: Optional[int] = None) -> int:
+    R = weights.shape[0] if R is None else R
+    D = weights.shape[1] if D is None else D
+    n = out.shape[0] if n is None else n
+    dtype = _DTYPES[weights.dtype] if dtype is None else dtype
+    code = lib().fs_seq_gather_fwd(
+        _ptr(weights), ctypes.c_int64(R), ctypes.c_int32(D), ctypes.c_int(dtype), _ptr(rows), _ptr(pos),
+        ctypes.c_int64(j0), ctypes.c_int64(j1), _ptr(out), ctypes.c_int64(n), _stream(), _ptr(dev_status))
+    return _check("fs_seq_gather_fwd", code, raise_on_error)
+
+
+def fs_seq_grad_bwd(grad_out, rows, pos, j0: int, j1: int, R: int, variant: int,
+                    uniq_rows, row_grads, cap_unique: int, num_unique, dev_status=None,
+                    workspace: Optional[torch.Tensor] = None, raise_on_error: bool = True,
+                    n: Optional[int] = None, D: Optional[int] = None, dtype: Optional[int] = None) -> int:
+    L = lib()
+    n = grad_out.shape[0] if n is None else n
+    D = grad_out.shape[1] if D is None else D
+    dtype = _DTYPES[grad_out.dtype] if dtype is None else dtype
+
+    def call(ws_ptr, ws_size_ref):
+        return L.fs_seq_grad_bwd(
+            _ptr(grad_out), ctypes.c_int64(n), ctypes.c_int32(D), ctypes.c_int(dtype), _ptr(rows), _ptr(pos),
+            ctypes.c_int64(j0), ctypes.c_int64(j1), ctypes.c_int64(R), ctypes.c_int32(variant),
+            _ptr(uniq_rows), _ptr(row_grads), ctypes.c_int64(cap_unique), _ptr(num_unique),
+            ws_ptr, ws_size_ref, _stream(), _ptr(dev_status))
+
+    if workspace is None:
+        workspace, size, code = _workspace(call, grad_out.device)
+        if code != 0:
+            return _check("fs_seq_grad_bwd", code, raise_on_error)
+    else:
+        size = ctypes.c_size_t(workspace.numel())
+    return _check("fs_seq_grad_bwd", call(_ptr(workspace), ctypes.byref(size)), raise_on_error)
+
+
+def fs_plan_replication(ids, offsets, T: int, B: int, row_base, n: int, R: int, counts, flags: int,
+                        budget_bytes: int = 0, bytes_per_row: int = 1, sel_rows=None, num_selected=None,
+                        placement=None, dev_status=None, workspace: Optional[torch.Tensor] = None,
+                        raise_on_error: bool = True) -> int:
+    L = lib()
+
+    def call(ws_ptr, ws_size_ref):
+        return L.fs_plan_replication(
+            _ptr(ids), _ptr(offsets), ctypes.c_int32(T), ctypes.c_int32(B), _ptr(row_base), ctypes.c_int64(n),
+            ctypes.c_int64(R), _ptr(counts), ctypes.c_int32(flags), ctypes.c_int64(budget_bytes),
+            ctypes.c_int64(bytes_per_row), _ptr(sel_rows), _ptr(num_selected), _ptr(placement),
+            ws_ptr, ws_size_ref, _stream(), _ptr(dev_status))
+
+    if workspace is None:
+        workspace, size, code = _workspace(call, counts.device)
+        if code != 0:
+            return _check("fs_plan_replication", code, raise_on_error)
+    else:
+        size = ctypes.c_size_t(workspace.numel())
+    return _check("fs_plan_replication", call(_ptr(workspace), ctypes.byref(size)), raise_on_error)
+
+
+def fs_version() -> int:
+    return int(lib().fs_version())
+
+
+def fs_bwd_tile() -> int:
+    return int(lib().fs_bwd_tile())
+
+
+def fs_prof_begin(max_records: int = 4096) -> None:
+    _check("fs_prof_begin", lib().fs_prof_begin(ctypes.c_int32(max_records)), True)
+
+
+def fs_prof_end(cap: int = 4096) -> List[Tuple[str, float]]:
+    names = ctypes.create_string_buffer(cap * 48)
+    ms = (ctypes.c_float * cap)()
+    k = lib().fs_prof_end(names, ms, ctypes.c_int32(cap))
+    raw = names.raw
+    return [(raw[i * 48:(i + 1) * 48].split(b"\0")[0].decode(), float(ms[i])) for i in range(k)]

@@ -1,0 +1,76 @@
+// Version helpers and the opt-in per-kernel timing hooks.
+#include <string.h>
+
+#include <vector>
+
+#include "fs_common.h"
+
+namespace fs {
+
+bool g_prof_on = false;
+
+namespace {
+struct Record {
+    const char* name;
+    hipEvent_t start;
+    hipEvent_t stop;
+};
+std::vector<Record> g_records;
+std::vector<Record> g_pool;     // events created by fs_prof_begin, not yet used
+}  // namespace
+
+void prof_pre(const char* name, hipStream_t stream)
+{
+    if (g_pool.empty()) return;
+    Record r = g_pool.back();
+    g_pool.pop_back();
+    r.name = name;
+    (void)hipEventRecord(r.start, stream);
+    g_records.push_back(r);
+}
+
+void prof_post(hipStream_t stream)
+{
+    if (g_records.empty()) return;
+    (void)hipEventRecord(g_records.back().stop, stream);
+}
+
+}  // namespace fs
+
+extern "C" int32_t fs_version(void) { return 1000; }
+
+extern "C" int32_t fs_bwd_tile(void) { return FS_BWD_TILE; }
+
+extern "C" fs_status fs_prof_begin(int32_t max_records)
+{
+    using namespace fs;
+    if (max_records < 1 || max_records > (1 << 20)) return FS_ERR_SIZE;
+    while ((int32_t)(g_pool.size() + g_records.size()) < max_records) {
+        Record r{nullptr, nullptr, nullptr};
+        if (hipEventCreate(&r.start) != hipSuccess || hipEventCreate(&r.stop) != hipSuccess)
+            return FS_ERR_DEVICE;
+        g_pool.push_back(r);
+    }
+    g_prof_on = true;
+    return FS_OK;
+}
+
+extern "C" int32_t fs_prof_end(char* names, float* ms, int32_t cap)
+{
+    using namespace fs;
+    g_prof_on = false;
+    int32_t taken = 0;
+    for (Record& r : g_records) {
+        float t = -1.0f;
+        if (hipEventSynchronize(r.stop) == hipSuccess) (void)hipEventElapsedTime(&t, r.start, r.stop);
+        if (taken < cap && names != nullptr && ms != nullptr) {
+            strncpy(names + (size_t)taken * 48, r.name ? r.name : "?", 47);
+            names[(size_t)taken * 48 + 47] = '\0';
+            ms[taken] = t;
+            ++taken;
+        }
+        g_pool.push_back(r);
+    }
+    g_records.clear();
+    return taken;
+}

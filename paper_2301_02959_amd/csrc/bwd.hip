@@ -1,0 +1,410 @@
+// fs_seq_grad_bwd: row_grads[u(r), :] = sum of f32(grad_out[pos[j], :]) over the lookups of row r.
+//
+// Sort-by-row segmented reduction:
+//   bwd_make_keys     (row, pos) -> (u32 key, u32 value), validated
+//   radix sort        stable by row; lookups of one row keep their j order, which is
+//                     ascending pos for any fs_route_bucketize output
+//   bwd_count_heads   per 256-lookup chunk of the sorted order: number of runs that
+//                     start in it, with a block-local exclusive prefix
+//   bwd_scan_blocks   exclusive scan of the per-block sums -> index of every run,
+//                     *num_unique
+//   bwd_segreduce     a group of LG lanes (one 16-byte piece of the row per lane) walks
+//                     one chunk left to right with 8 gradient rows in flight; a run that
+//                     starts in the chunk goes to row_grads, the piece that continues a
+//                     run from the previous chunk goes to carry[chunk]
+//   bwd_fold          for every run that spills over a chunk end: row_grads += carry of
+//                     the following chunks, left to right
+// which is exactly the summation order stated in flexshard.h (chunk = FS_BWD_TILE).
+// variant 1 replaces carry + fold by fp32 atomic adds into pre-zeroed rows.
+// HBM-bound: grad_out is read once (random 16*units-byte rows), row_grads written once.
+#include "fs_common.h"
+#include "radix_sort.h"
+
+namespace fs {
+
+constexpr int kChunk = FS_BWD_TILE;
+constexpr int kChunksPerBlock = 64;          // bwd_count_heads: chunks per block
+constexpr int kBwdUnroll = 8;
+constexpr uint32_t kNoKey = 0xFFFFFFFFu;     // never a row: R < 2^32 - 1
+
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+
+__global__ __launch_bounds__(kBlock) void bwd_make_keys_kernel(
+    const int64_t* __restrict__ rows, const int32_t* __restrict__ pos, int64_t m, int64_t R, int64_t n,
+    uint32_t* __restrict__ keys, uint32_t* __restrict__ vals, int32_t* status)
+{
+    const int64_t q = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    bool bad = false;
+    if (q < m) {
+        int64_t r = load_stream(rows + q);
+        int64_t p = load_stream(pos + q);
+        if (r < 0 || r >= R) { r = 0; bad = true; }
+        if (p < 0 || p >= n) { p = 0; bad = true; }
+        keys[q] = (uint32_t)r;
+        vals[q] = (uint32_t)p;
+    }
+    if (ballot(bad) != 0 && lane_id() == 0) report(status, FS_DEV_BAD_ID);
+}
+
+// Block b covers chunks [64 b, 64 b + 64): wave w walks 16 of them.  chunk_local[c] = runs that
+// start in the block's chunks before c; block_sum[b] = runs that start in the block.
+__global__ __launch_bounds__(kBlock) void bwd_count_heads_kernel(
+    const uint32_t* __restrict__ keys, const uint32_t* __restrict__ vals, int64_t m, int64_t chunks,
+    uint32_t* __restrict__ chunk_local, uint32_t* __restrict__ block_sum, int32_t* status)
+{
+    __shared__ uint32_t heads[kChunksPerBlock];
+    const int w = wave_id();
+    const int lane = lane_id();
+    constexpr int kPerWave = kChunksPerBlock / kWavesPerBlock;
+    bool disorder = false;
+    for (int q = 0; q < kPerWave; ++q) {
+        const int slot = w * kPerWave + q;
+        const int64_t chunk = (int64_t)blockIdx.x * kChunksPerBlock + slot;
+        uint32_t count = 0;
+        if (chunk < chunks) {
+            const int64_t k0 = chunk * kChunk;
+#pragma unroll
+            for (int s = 0; s < kChunk / kWave; ++s) {
+                const int64_t k = k0 + s * kWave + lane;
+                bool head = false;
+                if (k < m) {
+                    const uint32_t key = keys[k];
+                    if (k == 0) {
+                        head = true;
+                    } else {
+                        const uint32_t prev = keys[k - 1];
+                        head = key != prev;
+                        if (!head && vals[k] < vals[k - 1]) disorder = true;
+                    }
+                }
+                count += (uint32_t)__popcll(ballot(head));
+            }
+        }
+        if (lane == 0) heads[slot] = count;
+    }
+    if (ballot(disorder) != 0 && lane == 0) report(status, FS_DEV_POS_ORDER);
+    __syncthreads();
+    if (w == 0) {
+        const uint32_t mine = heads[lane];
+        uint32_t incl = mine;
+        for (int off = 1; off < kWave; off <<= 1) {
+            const uint32_t up = __shfl_up(incl, off);
+            if (lane >= off) incl += up;
+        }
+        const int64_t chunk = (int64_t)blockIdx.x * kChunksPerBlock + lane;
+        if (chunk < chunks) chunk_local[chunk] = incl - mine;
+        if (lane == kWave - 1) block_sum[blockIdx.x] = incl;
+    }
+}
+
+// One block: block_sum[0..blocks) -> exclusive prefix in place, block_sum[blocks] = total.
+__global__ __launch_bounds__(kBlock) void bwd_scan_blocks_kernel(
+    uint32_t* __restrict__ block_sum, int64_t blocks, int64_t cap, int64_t* __restrict__ num_unique,
+    int32_t* status)
+{
+    __shared__ uint32_t part[kBlock];
+    const int64_t per = (blocks + kBlock - 1) / kBlock;
+    const int64_t lo = (int64_t)threadIdx.x * per < blocks ? (int64_t)threadIdx.x * per : blocks;
+    const int64_t hi = lo + per < blocks ? lo + per : blocks;
+    uint32_t sum = 0;
+    for (int64_t k = lo; k < hi; ++k) sum += block_sum[k];
+    part[threadIdx.x] = sum;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t run = 0;
+        for (int k = 0; k < kBlock; ++k) { const uint32_t v = part[k]; part[k] = run; run += v; }
+        block_sum[blocks] = run;
+        *num_unique = (int64_t)run;
+        if ((int64_t)run > cap) report(status, FS_DEV_UNIQUE_OVERFLOW);
+    }
+    __syncthreads();
+    uint32_t run = part[threadIdx.x];
+    for (int64_t k = lo; k < hi; ++k) { const uint32_t v = block_sum[k]; block_sum[k] = run; run += v; }
+}
+
+__device__ __forceinline__ uint32_t runs_before(const uint32_t* __restrict__ block_base,
+                                                const uint32_t* __restrict__ chunk_local, int64_t chunk, int64_t chunks)
+{
+    if (chunk >= chunks) return block_base[(chunks + kChunksPerBlock - 1) / kChunksPerBlock];
+    return block_base[chunk / kChunksPerBlock] + chunk_local[chunk];
+}
+
+template <int DT>
+struct Vec;
+template <>
+struct Vec<FS_F32> {
+    static constexpr int N = 4;
+    static __device__ __forceinline__ void load(const u32x4& x, float* f)
+    {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) f[i] = __uint_as_float(x[i]);   // (a bit_cast of a vector element miscompiles)
+    }
+};
+template <>
+struct Vec<FS_F16> {
+    static constexpr int N = 8;
+    static __device__ __forceinline__ void load(const u32x4& x, float* f)
+    {
+        const f16x8 h = __builtin_bit_cast(f16x8, x);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) f[i] = (float)h[i];
+    }
+};
+template <>
+struct Vec<FS_BF16> {
+    static constexpr int N = 8;
+    static __device__ __forceinline__ void load(const u32x4& x, float* f)
+    {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            f[2 * i] = __uint_as_float(x[i] << 16);
+            f[2 * i + 1] = __uint_as_float(x[i] & 0xFFFF0000u);
+        }
+    }
+};
+
+template <int LG, int DT>
+__global__ __launch_bounds__(kBlock) void bwd_segreduce_kernel(
+    const u32x4* __restrict__ grad, int units, int D,
+    const uint32_t* __restrict__ keys, const uint32_t* __restrict__ vals, int64_t m, int64_t chunks,
+    const uint32_t* __restrict__ block_base, const uint32_t* __restrict__ chunk_local,
+    int64_t* __restrict__ uniq_rows, float* __restrict__ row_grads, int64_t cap,
+    float* __restrict__ carry, int atomic)
+{
+    constexpr int N = Vec<DT>::N;
+    constexpr int GPB = kBlock / LG;
+    const int lig = threadIdx.x % LG;
+    const int gi = threadIdx.x / LG;
+    const int64_t chunk = (int64_t)blockIdx.x * GPB + gi;
+    const int c = blockIdx.y * LG + lig;                 // 16-byte piece of the row
+    if (chunk >= chunks || c >= units) return;
+    const int64_t k0 = chunk * kChunk;
+    const int64_t k1 = k0 + kChunk < m ? k0 + kChunk : m;
+    const int col = c * N;
+
+    bool piece_cont = k0 > 0 && keys[k0 - 1] == keys[k0];    // first piece continues the previous chunk's run
+    int64_t u = (int64_t)runs_before(block_base, chunk_local, chunk, chunks) - 1;
+    bool fresh = true;
+    float acc[N];
+
+    for (int64_t kb = k0; kb < k1; kb += kBwdUnroll) {
+        uint32_t kk[kBwdUnroll + 1];
+        uint32_t pp[kBwdUnroll];
+        u32x4 x[kBwdUnroll];
+#pragma unroll
+        for (int j = 0; j <= kBwdUnroll; ++j) kk[j] = kb + j < m ? keys[kb + j] : kNoKey;
+#pragma unroll
+        for (int j = 0; j < kBwdUnroll; ++j) pp[j] = kb + j < k1 ? vals[kb + j] : 0u;
+#pragma unroll
+        for (int j = 0; j < kBwdUnroll; ++j)
+            if (kb + j < k1) x[j] = load_stream(grad + (int64_t)pp[j] * units + c);
+#pragma unroll
+        for (int j = 0; j < kBwdUnroll; ++j) {
+            const int64_t k = kb + j;
+            if (k < k1) {
+                float f[N];
+                Vec<DT>::load(x[j], f);
+                if (fresh) {
+                    if (!piece_cont) ++u;
+#pragma unroll
+                    for (int i = 0; i < N; ++i) acc[i] = f[i];
+                } else {
+#pragma unroll
+                    for (int i = 0; i < N; ++i) acc[i] = acc[i] + f[i];
+                }
+                const bool last_in_chunk = k + 1 == k1;
+                const bool run_goes_on = kk[j + 1] == kk[j];          // kNoKey past the end
+                if (last_in_chunk || !run_goes_on) {
+                    if (piece_cont && !atomic) {
+                        float* dst = carry + chunk * D + col;
+#pragma unroll
+                        for (int i = 0; i < N; i += 4)
+                            *reinterpret_cast<f32x4*>(dst + i) = f32x4{acc[i], acc[i + 1], acc[i + 2], acc[i + 3]};
+                    } else if (u < cap) {
+                        float* dst = row_grads + u * D + col;
+                        if (atomic && (piece_cont || run_goes_on)) {
+#pragma unroll
+                            for (int i = 0; i < N; ++i) unsafeAtomicAdd(dst + i, acc[i]);
+                        } else {
+#pragma unroll
+                            for (int i = 0; i < N; i += 4)
+                                *reinterpret_cast<f32x4*>(dst + i) = f32x4{acc[i], acc[i + 1], acc[i + 2], acc[i + 3]};
+                        }
+                        if (!piece_cont && c == 0) uniq_rows[u] = (int64_t)kk[j];
+                    }
+                    fresh = true;
+                    piece_cont = false;
+                } else {
+                    fresh = false;
+                }
+            }
+        }
+    }
+}
+
+// Does a run that starts in `chunk` go on into chunk + 1?  Returns its key through *key.
+__device__ __forceinline__ bool run_spills_from(const uint32_t* __restrict__ keys, int64_t m, int64_t chunk, uint32_t* key)
+{
+    const int64_t k0 = chunk * kChunk;
+    const int64_t k1 = k0 + kChunk;
+    if (k1 >= m) return false;
+    const uint32_t last = keys[k1 - 1];
+    if (keys[k1] != last) return false;
+    // the run's first lookup must lie in this chunk
+    if (k0 > 0 && keys[k0] == last && keys[k0 - 1] == last) return false;
+    *key = last;
+    return true;
+}
+
+// One wave per chunk; a wave whose chunk starts a spilling run adds the carries of the chunks
+// the run goes on into, left to right.
+__global__ __launch_bounds__(kBlock) void bwd_fold_kernel(
+    const uint32_t* __restrict__ keys, int64_t m, int64_t chunks,
+    const uint32_t* __restrict__ block_base, const uint32_t* __restrict__ chunk_local,
+    float* __restrict__ row_grads, int D, int64_t cap, const float* __restrict__ carry)
+{
+    const int64_t chunk = (int64_t)blockIdx.x * kWavesPerBlock + wave_id();
+    if (chunk >= chunks) return;
+    uint32_t key;
+    if (!run_spills_from(keys, m, chunk, &key)) return;
+    const int64_t u = (int64_t)runs_before(block_base, chunk_local, chunk + 1, chunks) - 1;
+    if (u >= cap) return;
+    // first sorted index past the run
+    int64_t lo = (chunk + 1) * kChunk, hi = m;
+    while (lo < hi) {
+        const int64_t mid = lo + ((hi - lo) >> 1);
+        if (keys[mid] == key) lo = mid + 1; else hi = mid;
+    }
+    const int64_t last_chunk = (lo - 1) / kChunk;
+    for (int col = lane_id() * 4; col < D; col += kWave * 4) {
+        f32x4 acc = *reinterpret_cast<const f32x4*>(row_grads + u * D + col);
+        int64_t cc = chunk + 1;
+        for (; cc + kBwdUnroll <= last_chunk + 1; cc += kBwdUnroll) {
+            f32x4 part[kBwdUnroll];
+#pragma unroll
+            for (int j = 0; j < kBwdUnroll; ++j)
+                part[j] = *reinterpret_cast<const f32x4*>(carry + (cc + j) * D + col);
+#pragma unroll
+            for (int j = 0; j < kBwdUnroll; ++j) acc = acc + part[j];
+        }
+        for (; cc <= last_chunk; ++cc) acc = acc + *reinterpret_cast<const f32x4*>(carry + cc * D + col);
+        *reinterpret_cast<f32x4*>(row_grads + u * D + col) = acc;
+    }
+}
+
+// variant 1: rows that receive atomic adds start at zero.
+__global__ __launch_bounds__(kBlock) void bwd_zero_spilled_kernel(
+    const uint32_t* __restrict__ keys, int64_t m, int64_t chunks,
+    const uint32_t* __restrict__ block_base, const uint32_t* __restrict__ chunk_local,
+    float* __restrict__ row_grads, int D, int64_t cap)
+{
+    const int64_t chunk = (int64_t)blockIdx.x * kWavesPerBlock + wave_id();
+    if (chunk >= chunks || chunk == 0) return;
+    const int64_t k0 = chunk * kChunk;
+    if (keys[k0 - 1] != keys[k0]) return;
+    const int64_t u = (int64_t)runs_before(block_base, chunk_local, chunk, chunks) - 1;
+    if (u >= cap) return;
+    for (int col = lane_id() * 4; col < D; col += kWave * 4)
+        *reinterpret_cast<f32x4*>(row_grads + u * D + col) = f32x4{0.f, 0.f, 0.f, 0.f};
+}
+
+__global__ void bwd_empty_kernel(int64_t* num_unique) { *num_unique = 0; }
+
+template <int LG>
+static fs_status launch_segreduce(fs_dtype dtype, const void* grad, int units, int D, const uint32_t* keys,
+                                  const uint32_t* vals, int64_t m, int64_t chunks, const uint32_t* block_base,
+                                  const uint32_t* chunk_local, int64_t* uniq_rows, float* row_grads, int64_t cap,
+                                  float* carry, int atomic, hipStream_t stream)
+{
+    constexpr int GPB = kBlock / LG;
+    const dim3 grid((unsigned)((chunks + GPB - 1) / GPB), (unsigned)((units + LG - 1) / LG));
+    const u32x4* g = static_cast<const u32x4*>(grad);
+    if (dtype == FS_F32)
+        FS_LAUNCH("bwd_segreduce", (bwd_segreduce_kernel<LG, FS_F32>), grid, dim3(kBlock), stream, g, units, D, keys,
+                  vals, m, chunks, block_base, chunk_local, uniq_rows, row_grads, cap, carry, atomic);
+    else if (dtype == FS_F16)
+        FS_LAUNCH("bwd_segreduce", (bwd_segreduce_kernel<LG, FS_F16>), grid, dim3(kBlock), stream, g, units, D, keys,
+                  vals, m, chunks, block_base, chunk_local, uniq_rows, row_grads, cap, carry, atomic);
+    else
+        FS_LAUNCH("bwd_segreduce", (bwd_segreduce_kernel<LG, FS_BF16>), grid, dim3(kBlock), stream, g, units, D, keys,
+                  vals, m, chunks, block_base, chunk_local, uniq_rows, row_grads, cap, carry, atomic);
+    return FS_OK;
+}
+
+}  // namespace fs
+
+extern "C" fs_status fs_seq_grad_bwd(
+    const void* grad_out, int64_t n, int32_t D, fs_dtype dtype,
+    const int64_t* rows, const int32_t* pos, int64_t j0, int64_t j1, int64_t R,
+    int32_t variant,
+    int64_t* uniq_rows, float* row_grads, int64_t cap_unique, int64_t* num_unique,
+    void* workspace, size_t* workspace_bytes, void* stream, int32_t* dev_status)
+{
+    using namespace fs;
+    if (!workspace_bytes) return FS_ERR_NULL;
+    const int es = dtype_bytes(dtype);
+    if (es == 0) return FS_ERR_DTYPE;
+    if (R < 1 || R >= 4294967295LL || n < 0 || n >= (1LL << 31) || D < 1 || j0 < 0 || j0 > j1 || cap_unique < 0)
+        return FS_ERR_SIZE;
+    if (variant != 0 && variant != 1) return FS_ERR_CONFIG;
+    const int64_t row_bytes = (int64_t)D * es;
+    if (row_bytes % 16 != 0) return FS_ERR_ALIGN;
+    const int64_t m = j1 - j0;
+    if (m >= (1LL << 31)) return FS_ERR_SIZE;
+    const int units = (int)(row_bytes / 16);
+    const int64_t chunks = (m + kChunk - 1) / kChunk;
+    const int64_t blocks = (chunks + kChunksPerBlock - 1) / kChunksPerBlock;
+
+    Carver ws(workspace);
+    uint32_t* keys_a = ws.take<uint32_t>((size_t)m);
+    uint32_t* vals_a = ws.take<uint32_t>((size_t)m);
+    uint32_t* keys_b = ws.take<uint32_t>((size_t)m);
+    uint32_t* vals_b = ws.take<uint32_t>((size_t)m);
+    char* sort_scratch = ws.take<char>(radix_sort_scratch_bytes(m));
+    uint32_t* chunk_local = ws.take<uint32_t>((size_t)chunks);
+    uint32_t* block_base = ws.take<uint32_t>((size_t)blocks + 1);
+    float* carry = ws.take<float>(variant == 0 ? (size_t)chunks * (size_t)D : 0);
+    if (!workspace) { *workspace_bytes = ws.used; return FS_OK; }
+    if (*workspace_bytes < ws.used || (reinterpret_cast<uintptr_t>(workspace) & 255)) return FS_ERR_WORKSPACE;
+    if (!num_unique) return FS_ERR_NULL;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (m == 0) {
+        FS_LAUNCH("bwd_empty", bwd_empty_kernel, dim3(1), dim3(1), s, num_unique);
+        return FS_OK;
+    }
+    if (!grad_out || !rows || !pos) return FS_ERR_NULL;
+    if (cap_unique > 0 && (!uniq_rows || !row_grads)) return FS_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(grad_out) | reinterpret_cast<uintptr_t>(row_grads)) & 15) return FS_ERR_ALIGN;
+
+    FS_LAUNCH("bwd_make_keys", bwd_make_keys_kernel, dim3((unsigned)((m + kBlock - 1) / kBlock)), dim3(kBlock), s,
+              rows + j0, pos + j0, m, R, n, keys_a, vals_a, dev_status);
+    uint32_t* keys = nullptr;
+    uint32_t* vals = nullptr;
+    fs_status rc = radix_sort_pairs(keys_a, vals_a, keys_b, vals_b, m, nullptr, bits_for((uint64_t)(R - 1)),
+                                    sort_scratch, s, &keys, &vals);
+    if (rc != FS_OK) return rc;
+    FS_LAUNCH("bwd_count_heads", bwd_count_heads_kernel, dim3((unsigned)blocks), dim3(kBlock), s,
+              keys, vals, m, chunks, chunk_local, block_base, dev_status);
+    FS_LAUNCH("bwd_scan_blocks", bwd_scan_blocks_kernel, dim3(1), dim3(kBlock), s,
+              block_base, blocks, cap_unique, num_unique, dev_status);
+    const unsigned wave_grid = (unsigned)((chunks + kWavesPerBlock - 1) / kWavesPerBlock);
+    if (variant == 1)
+        FS_LAUNCH("bwd_zero_spilled", bwd_zero_spilled_kernel, dim3(wave_grid), dim3(kBlock), s,
+                  keys, m, chunks, block_base, chunk_local, row_grads, (int)D, cap_unique);
+#define FS_SEG(LG)                                                                                              \
+    rc = launch_segreduce<LG>(dtype, grad_out, units, (int)D, keys, vals, m, chunks, block_base, chunk_local,     \
+                              uniq_rows, row_grads, cap_unique, carry, (int)variant, s)
+    if (units <= 2) FS_SEG(2);
+    else if (units <= 4) FS_SEG(4);
+    else if (units <= 8) FS_SEG(8);
+    else if (units <= 16) FS_SEG(16);
+    else if (units <= 32) FS_SEG(32);
+    else FS_SEG(64);
+#undef FS_SEG
+    if (rc != FS_OK) return rc;
+    if (variant == 0)
+        FS_LAUNCH("bwd_fold", bwd_fold_kernel, dim3(wave_grid), dim3(kBlock), s,
+                  keys, m, chunks, block_base, chunk_local, row_grads, (int)D, cap_unique, carry);
+    return FS_OK;
+}

@@ -1,0 +1,111 @@
+// Shared host/device helpers of libflexshard_hip (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "flexshard.h"
+
+namespace fs {
+
+constexpr int kWave = 64;          // CDNA wavefront
+constexpr int kBlock = 256;        // threads per workgroup used by every kernel here
+constexpr int kWavesPerBlock = kBlock / kWave;
+constexpr int kXcds = 8;           // MI355X: 8 XCDs, workgroups are dealt to them round-robin
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// ---- opt-in per-kernel timing (see fs_prof_begin in flexshard.h) -----------
+void prof_pre(const char* name, hipStream_t stream);
+void prof_post(hipStream_t stream);
+extern bool g_prof_on;
+
+#define FS_LAUNCH_SMEM(name, kernel, grid, block, smem, stream, ...)                    \
+    do {                                                                                \
+        if (fs::g_prof_on) fs::prof_pre(name, stream);                                  \
+        hipLaunchKernelGGL(kernel, grid, block, smem, stream, __VA_ARGS__);             \
+        if (fs::g_prof_on) fs::prof_post(stream);                                       \
+        if (hipGetLastError() != hipSuccess) return FS_ERR_DEVICE;                      \
+    } while (0)
+#define FS_LAUNCH(name, kernel, grid, block, stream, ...)                               \
+    FS_LAUNCH_SMEM(name, kernel, grid, block, 0, stream, __VA_ARGS__)
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Carves 256-byte aligned pieces out of a caller-provided workspace; with a null
+// base it only adds up sizes.
+struct Carver {
+    char* base;
+    size_t used = 0;
+    explicit Carver(void* p) : base(static_cast<char*>(p)) {}
+    template <typename T>
+    T* take(size_t count)
+    {
+        size_t off = used;
+        used += align_up(count * sizeof(T), 256);
+        return base ? reinterpret_cast<T*>(base + off) : nullptr;
+    }
+};
+
+inline int dtype_bytes(fs_dtype d)
+{
+    return d == FS_F32 ? 4 : (d == FS_F16 || d == FS_BF16) ? 2 : 0;
+}
+
+inline int bits_for(uint64_t max_value)   // number of bits needed to write max_value
+{
+    int b = 1;
+    while (b < 64 && (max_value >> b) != 0) ++b;
+    return b;
+}
+
+#ifdef __HIPCC__
+// ---- device helpers ---------------------------------------------------------
+__device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
+__device__ __forceinline__ int wave_id() { return threadIdx.x >> 6; }
+
+// number of set bits of `mask` below this lane
+__device__ __forceinline__ int popc_below(uint64_t mask)
+{
+    return __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(mask >> 32),
+                                     __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(mask), 0u));
+}
+
+__device__ __forceinline__ uint64_t ballot(bool p) { return __ballot(p); }
+
+// Lanes of the wave whose `key` has the same low `nbits` bits as this lane's,
+// restricted to lanes with `valid`.  nbits ballots, no LDS.
+__device__ __forceinline__ uint64_t match_bits(uint32_t key, int nbits, bool valid)
+{
+    uint64_t m = ballot(valid);
+#pragma unroll 1
+    for (int b = 0; b < nbits; ++b) {
+        const bool bit = (key >> b) & 1u;
+        const uint64_t v = ballot(bit);
+        m &= bit ? v : ~v;
+    }
+    return m;
+}
+
+// Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Map
+// the hardware block id to a logical tile so that every XCD walks one
+// contiguous range of tiles.  The grid must have kXcds * tiles_per_xcd blocks.
+__device__ __forceinline__ int64_t xcd_contiguous_tile(int64_t bid, int64_t tiles_per_xcd)
+{
+    return (bid % kXcds) * tiles_per_xcd + bid / kXcds;
+}
+
+template <typename T>
+__device__ __forceinline__ T load_stream(const T* p) { return __builtin_nontemporal_load(p); }
+template <typename T>
+__device__ __forceinline__ void store_stream(T* p, T v) { __builtin_nontemporal_store(v, p); }
+
+__device__ __forceinline__ void report(int32_t* status, int32_t bits)
+{
+    if (status != nullptr && bits != 0) atomicOr(status, bits);
+}
+#endif  // __HIPCC__
+
+}  // namespace fs

@@ -1,0 +1,262 @@
+// fs_plan_replication: row-frequency histogram and top-k rows under a byte budget.
+//
+// ACCUMULATE  plan_histogram: each block walks a span of 32768 sampled ids.  Zipf samples hit
+//             a few rows most of the time, so a block keeps a 4096-entry direct-mapped cache of
+//             (row, count) in LDS (first row to claim a slot keeps it); only misses and the final
+//             flush reach the global counters, as saturating 32-bit atomic adds.
+// SELECT      plan_mark_count / plan_scan / plan_compact: stable compaction of the candidate rows
+//             (count > 0, or all) in ascending row order into (key = ~count, value = row);
+//             a stable radix sort by key then yields (count desc, row asc); plan_emit writes the
+//             first k = min(budget / bytes_per_row, #candidates) rows, k, and the tier-0 tags.
+// The candidate count lives in device memory; the sort kernels read it there.
+#include "fs_common.h"
+#include "radix_sort.h"
+
+namespace fs {
+
+constexpr int kHistSpan = 32768;          // ids per block
+constexpr int kHistSlots = 4096;          // LDS cache entries
+constexpr int kHistSlotBits = 12;
+constexpr int kSelTile = kBlock * 8;      // rows per block in the compaction
+
+__device__ __forceinline__ void add_saturating(uint32_t* p, uint32_t v, int32_t* faults)
+{
+    const uint32_t old = atomicAdd(p, v);
+    if (old > 0xFFFFFFFFu - v) {          // wrapped: pin the counter at the maximum
+        atomicExch(p, 0xFFFFFFFFu);
+        *faults |= FS_DEV_COUNT_OVERFLOW;
+    }
+}
+
+__device__ __forceinline__ int plan_table_of(const int64_t* __restrict__ offsets, int T, int64_t B, int64_t i)
+{
+    int lo = 0, hi = T - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (offsets[(int64_t)mid * B] <= i) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+
+__global__ __launch_bounds__(kBlock) void plan_check_offsets_kernel(
+    const int64_t* __restrict__ offsets, int64_t S, int64_t n, int32_t* ok_flag, int32_t* status)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    bool bad = false;
+    for (int64_t s = tid; s < S; s += stride) bad |= offsets[s] > offsets[s + 1];
+    if (tid == 0) bad |= offsets[0] != 0 || offsets[S] != n;
+    if (ballot(bad) != 0 && lane_id() == 0) { report(status, FS_DEV_BAD_OFFSETS); atomicExch(ok_flag, 0); }
+}
+
+__global__ __launch_bounds__(kBlock) void plan_histogram_kernel(
+    const int64_t* __restrict__ ids, const int64_t* __restrict__ offsets, int T, int64_t B,
+    const int64_t* __restrict__ row_base, int64_t n, uint32_t* __restrict__ counts,
+    const int32_t* __restrict__ ok_flag, int32_t* status)
+{
+    __shared__ uint32_t tags[kHistSlots];      // row + 1, 0 = free
+    __shared__ uint32_t hits[kHistSlots];
+    __shared__ int span_tables[2];
+    if (*ok_flag == 0) return;                 // bad offsets: count nothing
+    const int64_t base = (int64_t)blockIdx.x * kHistSpan;
+    const int64_t end = base + kHistSpan < n ? base + kHistSpan : n;
+    for (int s = threadIdx.x; s < kHistSlots; s += kBlock) { tags[s] = 0; hits[s] = 0; }
+    if (threadIdx.x == 0) {
+        span_tables[0] = plan_table_of(offsets, T, B, base);
+        span_tables[1] = plan_table_of(offsets, T, B, end - 1);
+    }
+    __syncthreads();
+    const int t_lo = span_tables[0];
+    const int t_hi = span_tables[1];
+    int32_t faults = 0;
+    for (int64_t i = base + threadIdx.x; i < end; i += kBlock) {
+        int t = t_lo;
+        while (t < t_hi && offsets[(int64_t)(t + 1) * B] <= i) ++t;
+        const int64_t first = row_base[t];
+        const int64_t rows_t = row_base[t + 1] - first;
+        int64_t id = load_stream(ids + i);
+        if (id < 0 || id >= rows_t) { faults |= FS_DEV_BAD_ID; id = 0; }
+        const uint32_t g = (uint32_t)(first + id);
+        const uint32_t slot = (g * 2654435761u) >> (32 - kHistSlotBits);
+        uint32_t tag = tags[slot];
+        if (tag == 0) tag = atomicCAS(&tags[slot], 0u, g + 1u);
+        if (tag == 0 || tag == g + 1u) atomicAdd(&hits[slot], 1u);
+        else add_saturating(counts + g, 1u, &faults);
+    }
+    __syncthreads();
+    for (int s = threadIdx.x; s < kHistSlots; s += kBlock)
+        if (tags[s] != 0 && hits[s] != 0) add_saturating(counts + (tags[s] - 1u), hits[s], &faults);
+    if (ballot(faults != 0) != 0) {
+        for (int off = 32; off > 0; off >>= 1) faults |= __shfl_down(faults, off);
+        if (lane_id() == 0) report(status, faults);
+    }
+}
+
+// ---- selection --------------------------------------------------------------
+__global__ __launch_bounds__(kBlock) void plan_mark_count_kernel(
+    const uint32_t* __restrict__ counts, int64_t R, int allow_zero, uint32_t* __restrict__ tile_count)
+{
+    __shared__ uint32_t wave_sum[kWavesPerBlock];
+    const int64_t base = (int64_t)blockIdx.x * kSelTile;
+    uint32_t mine = 0;
+#pragma unroll
+    for (int it = 0; it < kSelTile / kBlock; ++it) {
+        const int64_t g = base + (int64_t)it * kBlock + threadIdx.x;
+        const bool cand = g < R && (allow_zero || counts[g] != 0);
+        mine += (uint32_t)__popcll(ballot(cand));     // same value in every lane of the wave
+    }
+    if (lane_id() == 0) wave_sum[wave_id()] = mine;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t s = 0;
+        for (int k = 0; k < kWavesPerBlock; ++k) s += wave_sum[k];
+        tile_count[blockIdx.x] = s;
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void plan_scan_kernel(uint32_t* __restrict__ tile_count, int64_t tiles,
+                                                           int64_t* __restrict__ num_candidates)
+{
+    __shared__ uint32_t part[kBlock];
+    const int64_t per = (tiles + kBlock - 1) / kBlock;
+    const int64_t lo = (int64_t)threadIdx.x * per < tiles ? (int64_t)threadIdx.x * per : tiles;
+    const int64_t hi = lo + per < tiles ? lo + per : tiles;
+    uint32_t sum = 0;
+    for (int64_t k = lo; k < hi; ++k) sum += tile_count[k];
+    part[threadIdx.x] = sum;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t run = 0;
+        for (int k = 0; k < kBlock; ++k) { const uint32_t v = part[k]; part[k] = run; run += v; }
+        *num_candidates = (int64_t)run;
+    }
+    __syncthreads();
+    uint32_t run = part[threadIdx.x];
+    for (int64_t k = lo; k < hi; ++k) { const uint32_t v = tile_count[k]; tile_count[k] = run; run += v; }
+}
+
+__global__ __launch_bounds__(kBlock) void plan_compact_kernel(
+    const uint32_t* __restrict__ counts, int64_t R, int allow_zero, const uint32_t* __restrict__ tile_base,
+    uint32_t* __restrict__ keys, uint32_t* __restrict__ vals)
+{
+    __shared__ uint32_t wave_sum[kWavesPerBlock];
+    constexpr int kItems = kSelTile / kBlock;
+    constexpr int kSpan = kWave * kItems;                 // consecutive rows per wave
+    const int w = wave_id();
+    const int lane = lane_id();
+    const int64_t base = (int64_t)blockIdx.x * kSelTile + (int64_t)w * kSpan;
+    uint32_t cnt[kItems];
+    uint32_t before[kItems];
+    bool cand[kItems];
+    uint32_t total = 0;
+#pragma unroll
+    for (int it = 0; it < kItems; ++it) {
+        const int64_t g = base + it * kWave + lane;
+        cnt[it] = g < R ? counts[g] : 0u;
+        cand[it] = g < R && (allow_zero || cnt[it] != 0);
+        const uint64_t b = ballot(cand[it]);
+        before[it] = total + (uint32_t)popc_below(b);
+        total += (uint32_t)__popcll(b);
+    }
+    if (lane == 0) wave_sum[w] = total;
+    __syncthreads();
+    uint32_t off = tile_base[blockIdx.x];
+    for (int k = 0; k < w; ++k) off += wave_sum[k];
+#pragma unroll
+    for (int it = 0; it < kItems; ++it) {
+        if (cand[it]) {
+            const int64_t g = base + it * kWave + lane;
+            keys[off + before[it]] = ~cnt[it];
+            vals[off + before[it]] = (uint32_t)g;
+        }
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void plan_emit_kernel(
+    const uint32_t* __restrict__ vals, const int64_t* __restrict__ num_candidates, int64_t cap,
+    int64_t* __restrict__ sel_rows, int64_t* __restrict__ num_selected, uint32_t* __restrict__ placement)
+{
+    const int64_t nc = *num_candidates;
+    const int64_t k = cap < nc ? cap : nc;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < k; i += stride) {
+        const uint32_t g = vals[i];
+        sel_rows[i] = (int64_t)g;
+        if (placement != nullptr) placement[g] &= FS_OWNER_MASK;
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) *num_selected = k;
+}
+
+__global__ void plan_set_flag_kernel(int32_t* flag) { *flag = 1; }
+
+}  // namespace fs
+
+extern "C" fs_status fs_plan_replication(
+    const int64_t* ids, const int64_t* offsets, int32_t T, int32_t B,
+    const int64_t* row_base, int64_t n, int64_t R,
+    uint32_t* counts, int32_t flags,
+    int64_t budget_bytes, int64_t bytes_per_row,
+    int64_t* sel_rows, int64_t* num_selected,
+    uint32_t* placement,
+    void* workspace, size_t* workspace_bytes, void* stream, int32_t* dev_status)
+{
+    using namespace fs;
+    if (!workspace_bytes) return FS_ERR_NULL;
+    if (flags & ~(FS_PLAN_ACCUMULATE | FS_PLAN_SELECT | FS_PLAN_TAG | FS_PLAN_ALLOW_ZERO)) return FS_ERR_CONFIG;
+    if ((flags & FS_PLAN_TAG) && !(flags & FS_PLAN_SELECT)) return FS_ERR_CONFIG;
+    if (R < 1 || R >= 4294967295LL) return FS_ERR_SIZE;
+    const bool acc = flags & FS_PLAN_ACCUMULATE;
+    const bool sel = flags & FS_PLAN_SELECT;
+    if (acc && (n < 0 || n >= (1LL << 31) || T < 1 || B < 1 || (int64_t)T * B >= (1LL << 31))) return FS_ERR_SIZE;
+    if (sel && (budget_bytes < 0 || bytes_per_row < 1)) return FS_ERR_SIZE;
+
+    const int64_t sel_tiles = sel ? (R + kSelTile - 1) / kSelTile : 0;
+    const int64_t m_max = sel ? R : 0;
+    Carver ws(workspace);
+    int32_t* ok_flag = ws.take<int32_t>(1);
+    int64_t* num_cand = ws.take<int64_t>(1);
+    uint32_t* tile_count = ws.take<uint32_t>((size_t)sel_tiles);
+    uint32_t* keys_a = ws.take<uint32_t>((size_t)m_max);
+    uint32_t* vals_a = ws.take<uint32_t>((size_t)m_max);
+    uint32_t* keys_b = ws.take<uint32_t>((size_t)m_max);
+    uint32_t* vals_b = ws.take<uint32_t>((size_t)m_max);
+    char* sort_scratch = ws.take<char>(sel ? radix_sort_scratch_bytes(m_max) : 0);
+    if (!workspace) { *workspace_bytes = ws.used; return FS_OK; }
+    if (*workspace_bytes < ws.used || (reinterpret_cast<uintptr_t>(workspace) & 255)) return FS_ERR_WORKSPACE;
+    if (!counts) return FS_ERR_NULL;
+    if (acc && (!offsets || !row_base || (n > 0 && !ids))) return FS_ERR_NULL;
+    if (sel && !num_selected) return FS_ERR_NULL;
+    if ((flags & FS_PLAN_TAG) && !placement) return FS_ERR_NULL;
+    const int64_t cap = sel ? budget_bytes / bytes_per_row : 0;
+    if (sel && cap > 0 && !sel_rows) return FS_ERR_NULL;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (acc) {
+        const int64_t S = (int64_t)T * B;
+        FS_LAUNCH("plan_set_flag", plan_set_flag_kernel, dim3(1), dim3(1), s, ok_flag);
+        const unsigned grid = (unsigned)((S + kBlock - 1) / kBlock < 1024 ? (S + kBlock - 1) / kBlock : 1024);
+        FS_LAUNCH("plan_check_offsets", plan_check_offsets_kernel, dim3(grid), dim3(kBlock), s,
+                  offsets, S, n, ok_flag, dev_status);
+        if (n > 0) {
+            const int64_t blocks = (n + kHistSpan - 1) / kHistSpan;
+            FS_LAUNCH("plan_histogram", plan_histogram_kernel, dim3((unsigned)blocks), dim3(kBlock), s,
+                      ids, offsets, (int)T, (int64_t)B, row_base, n, counts, ok_flag, dev_status);
+        }
+    }
+    if (sel) {
+        const int allow_zero = (flags & FS_PLAN_ALLOW_ZERO) ? 1 : 0;
+        FS_LAUNCH("plan_mark_count", plan_mark_count_kernel, dim3((unsigned)sel_tiles), dim3(kBlock), s,
+                  counts, R, allow_zero, tile_count);
+        FS_LAUNCH("plan_scan", plan_scan_kernel, dim3(1), dim3(kBlock), s, tile_count, sel_tiles, num_cand);
+        FS_LAUNCH("plan_compact", plan_compact_kernel, dim3((unsigned)sel_tiles), dim3(kBlock), s,
+                  counts, R, allow_zero, tile_count, keys_a, vals_a);
+        uint32_t* keys = nullptr;
+        uint32_t* vals = nullptr;
+        fs_status rc = radix_sort_pairs(keys_a, vals_a, keys_b, vals_b, m_max, num_cand, 32, sort_scratch, s,
+                                        &keys, &vals);
+        if (rc != FS_OK) return rc;
+        FS_LAUNCH("plan_emit", plan_emit_kernel, dim3(1024), dim3(kBlock), s,
+                  vals, num_cand, cap, sel_rows, num_selected, (flags & FS_PLAN_TAG) ? placement : nullptr);
+    }
+    return FS_OK;
+}

@@ -1,0 +1,25 @@
+// Stable LSD radix sort of (uint32 key, uint32 value) pairs, used by the backward
+// (key = row, value = position) and by the replication plan (key = inverted count,
+// value = row).  Hand-written for 64-lane waves: see radix_sort.hip.
+#pragma once
+
+#include "fs_common.h"
+
+namespace fs {
+
+constexpr int kSortItems = 8;                        // keys per thread
+constexpr int kSortTile = kBlock * kSortItems;       // keys per block
+constexpr int kSortMaxDigitBits = 8;
+
+// Scratch the sort needs for up to m_max pairs (beyond the two key/value buffers).
+size_t radix_sort_scratch_bytes(int64_t m_max);
+
+// Sorts pairs by the low `key_bits` bits of the key, stable.  Input in (keys_a, vals_a);
+// (keys_b, vals_b) is the second buffer.  The number of pairs is *m_dev if m_dev != nullptr
+// (device memory, read by the kernels; must be <= m_max) else m_max.  On return
+// *keys_out / *vals_out name the buffer that holds the result.
+fs_status radix_sort_pairs(uint32_t* keys_a, uint32_t* vals_a, uint32_t* keys_b, uint32_t* vals_b,
+                           int64_t m_max, const int64_t* m_dev, int key_bits, void* scratch,
+                           hipStream_t stream, uint32_t** keys_out, uint32_t** vals_out);
+
+}  // namespace fs

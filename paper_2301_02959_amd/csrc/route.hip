@@ -1,0 +1,298 @@
+// fs_route_bucketize: jagged ids -> (tier, owner) -> stable bucketize by owner.
+//
+// A stable counting sort of the n lookups by destination bucket, in four steps
+// that touch each lookup twice:
+//   route_prepare   validate offsets, clear counters
+//   route_remap     one 2048-lookup tile per block: table of each lookup, global
+//                   row g, placement entry, destination; per-tile bucket
+//                   histogram (wave-aggregated LDS adds); dest (u16) and g (u32)
+//                   go to the workspace
+//   route_scan      one block per bucket: exclusive scan of that bucket's per-tile
+//                   counts over the tiles, and the bucket's total
+//   route_scatter   same tiles: each wave ranks its 512 consecutive lookups by
+//                   ballot matching against a wave-private running histogram in
+//                   LDS, adds the tile's and the bucket's base, writes
+//                   out_rows / out_pos
+//   route_finalize  bucket_offsets and tier_counts
+// No spin-waits anywhere: the only cross-block communication is between launches.
+#include "fs_common.h"
+
+namespace fs {
+
+constexpr int kRouteItems = 8;                        // lookups per thread
+constexpr int kRouteTile = kBlock * kRouteItems;      // lookups per block
+constexpr int kRouteWaveSpan = kWave * kRouteItems;   // consecutive lookups per wave
+
+struct RouteCounters {
+    unsigned long long tier[3];
+    unsigned int bad_offsets;
+};
+
+__global__ __launch_bounds__(kBlock) void route_prepare_kernel(
+    const int64_t* __restrict__ offsets, int64_t S, int64_t n, RouteCounters* counters, int32_t* status)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (tid == 0) {
+        counters->tier[0] = 0; counters->tier[1] = 0; counters->tier[2] = 0;
+    }
+    bool bad = false;
+    for (int64_t s = tid; s < S; s += stride) bad |= offsets[s] > offsets[s + 1];
+    if (tid == 0) bad |= offsets[0] != 0 || offsets[S] != n;
+    if (ballot(bad) != 0 && lane_id() == 0) report(status, FS_DEV_BAD_OFFSETS);
+}
+
+// Table of lookup i: the largest t in [0, T) with offsets[t * B] <= i.  Clamped, so bad
+// offsets cannot take it out of range.
+__device__ __forceinline__ int table_of(const int64_t* __restrict__ offsets, int T, int64_t B, int64_t i)
+{
+    int lo = 0, hi = T - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (offsets[(int64_t)mid * B] <= i) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+
+__global__ __launch_bounds__(kBlock) void route_remap_kernel(
+    const int64_t* __restrict__ ids, const int64_t* __restrict__ offsets, int T, int64_t B,
+    const int64_t* __restrict__ row_base, const uint32_t* __restrict__ placement,
+    int64_t n, int U, int W, int self, int dest_bits,
+    uint16_t* __restrict__ dest_out, uint32_t* __restrict__ g_out,
+    uint32_t* __restrict__ tile_hist /* [U][tiles] */, int64_t tiles,
+    RouteCounters* counters, int32_t* status)
+{
+    extern __shared__ uint32_t lds_hist[];            // [U]
+    __shared__ int tile_tables[2];
+    const int64_t tile = blockIdx.x;
+    const int64_t base = tile * kRouteTile;
+    for (int b = threadIdx.x; b < U; b += kBlock) lds_hist[b] = 0;
+    if (threadIdx.x == 0) {
+        const int64_t last = (base + kRouteTile < n ? base + kRouteTile : n) - 1;
+        tile_tables[0] = table_of(offsets, T, B, base);
+        tile_tables[1] = table_of(offsets, T, B, last);
+    }
+    __syncthreads();
+    const int t_lo = tile_tables[0];
+    const int t_hi = tile_tables[1];
+    const int group_base = (self / W) * W;
+    int32_t faults = 0;
+    unsigned int tiers[3] = {0, 0, 0};
+
+#pragma unroll 2
+    for (int it = 0; it < kRouteItems; ++it) {
+        const int64_t i = base + (int64_t)it * kBlock + threadIdx.x;
+        const bool valid = i < n;
+        uint32_t dest = 0;
+        if (valid) {
+            int t = t_lo;
+            while (t < t_hi && offsets[(int64_t)(t + 1) * B] <= i) ++t;
+            const int64_t first = row_base[t];
+            const int64_t rows_t = row_base[t + 1] - first;
+            int64_t id = load_stream(ids + i);
+            if (id < 0 || id >= rows_t) { faults |= FS_DEV_BAD_ID; id = 0; }
+            const int64_t g = first + id;
+            const uint32_t e = placement[g];
+            const uint32_t tier = e >> FS_TIER_SHIFT;
+            const uint32_t owner = e & FS_OWNER_MASK;
+            if (tier == FS_TIER_GLOBAL) {
+                dest = self; tiers[0]++;
+            } else if (tier == FS_TIER_GROUP) {
+                tiers[1]++;
+                if (owner < (uint32_t)W) dest = group_base + owner;
+                else { dest = self; faults |= FS_DEV_BAD_PLACEMENT; }
+            } else if (tier == FS_TIER_SHARDED) {
+                tiers[2]++;
+                if (owner < (uint32_t)U) dest = owner;
+                else { dest = self; faults |= FS_DEV_BAD_PLACEMENT; }
+            } else {
+                dest = self; tiers[0]++; faults |= FS_DEV_BAD_PLACEMENT;
+            }
+            dest_out[i] = (uint16_t)dest;
+            g_out[i] = (uint32_t)g;
+        }
+        // one LDS add per distinct bucket per wave
+        const uint64_t same = match_bits(dest, dest_bits, valid);
+        if (valid && popc_below(same) == 0) atomicAdd(&lds_hist[dest], (uint32_t)__popcll(same));
+    }
+    __syncthreads();
+    for (int b = threadIdx.x; b < U; b += kBlock) tile_hist[(int64_t)b * tiles + tile] = lds_hist[b];
+
+    // tier counters and fault bits: reduce over the wave, one atomic per wave
+#pragma unroll
+    for (int k = 0; k < 3; ++k) {
+        unsigned int v = tiers[k];
+        for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off);
+        if (lane_id() == 0 && v != 0) atomicAdd(&counters->tier[k], (unsigned long long)v);
+    }
+    for (int off = 32; off > 0; off >>= 1) faults |= __shfl_down(faults, off);
+    if (lane_id() == 0) report(status, faults);
+}
+
+// One block per bucket b: tile_hist[b][0..tiles) -> exclusive prefix in place, total[b].
+__global__ __launch_bounds__(kBlock) void route_scan_kernel(uint32_t* __restrict__ tile_hist, int64_t tiles,
+                                                            uint32_t* __restrict__ totals)
+{
+    __shared__ uint32_t part[kBlock];
+    uint32_t* h = tile_hist + (int64_t)blockIdx.x * tiles;
+    const int64_t per = (tiles + kBlock - 1) / kBlock;
+    const int64_t lo = (int64_t)threadIdx.x * per;
+    const int64_t hi = lo + per < tiles ? lo + per : tiles;
+    uint32_t sum = 0;
+    for (int64_t k = lo; k < hi; ++k) sum += h[k];
+    part[threadIdx.x] = sum;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t run = 0;
+        for (int k = 0; k < kBlock; ++k) { const uint32_t v = part[k]; part[k] = run; run += v; }
+        totals[blockIdx.x] = run;
+    }
+    __syncthreads();
+    uint32_t run = part[threadIdx.x];
+    for (int64_t k = lo; k < hi; ++k) { const uint32_t v = h[k]; h[k] = run; run += v; }
+}
+
+__global__ __launch_bounds__(kBlock) void route_scatter_kernel(
+    const uint16_t* __restrict__ dest_in, const uint32_t* __restrict__ g_in, int64_t n, int U, int dest_bits,
+    const uint32_t* __restrict__ tile_hist /* scanned */, int64_t tiles, const uint32_t* __restrict__ totals,
+    int64_t* __restrict__ out_rows, int32_t* __restrict__ out_pos)
+{
+    extern __shared__ uint32_t lds[];
+    uint32_t* bucket_base = lds;                                        // [U] first output index of the tile in bucket b
+    uint16_t* wave_hist = reinterpret_cast<uint16_t*>(lds + U);         // [waves][U]
+    __shared__ uint32_t scan_part[kBlock];
+    const int64_t tile = blockIdx.x;
+    const int64_t base = tile * kRouteTile;
+    const int w = wave_id();
+    const int lane = lane_id();
+
+    // exclusive scan of the bucket totals (every block repeats it: U is small)
+    {
+        const int per = (U + kBlock - 1) / kBlock;
+        const int lo = threadIdx.x * per;
+        const int hi = lo + per < U ? lo + per : U;
+        uint32_t sum = 0;
+        for (int b = lo; b < hi; ++b) sum += totals[b];
+        scan_part[threadIdx.x] = sum;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            uint32_t run = 0;
+            for (int k = 0; k < kBlock; ++k) { const uint32_t v = scan_part[k]; scan_part[k] = run; run += v; }
+        }
+        __syncthreads();
+        uint32_t run = scan_part[threadIdx.x];
+        for (int b = lo; b < hi; ++b) {
+            bucket_base[b] = run + tile_hist[(int64_t)b * tiles + tile];
+            run += totals[b];
+        }
+    }
+    for (int b = threadIdx.x; b < kWavesPerBlock * U; b += kBlock) wave_hist[b] = 0;
+    __syncthreads();
+
+    uint16_t* my_hist = wave_hist + w * U;
+    uint32_t dest[kRouteItems];
+    uint32_t rank[kRouteItems];
+    uint32_t g[kRouteItems];
+#pragma unroll
+    for (int it = 0; it < kRouteItems; ++it) {
+        const int64_t i = base + (int64_t)w * kRouteWaveSpan + it * kWave + lane;
+        const bool valid = i < n;
+        dest[it] = valid ? dest_in[i] : 0;
+        g[it] = valid ? g_in[i] : 0;
+    }
+#pragma unroll
+    for (int it = 0; it < kRouteItems; ++it) {
+        const int64_t i = base + (int64_t)w * kRouteWaveSpan + it * kWave + lane;
+        const bool valid = i < n;
+        const uint64_t same = match_bits(dest[it], dest_bits, valid);
+        const uint32_t before = popc_below(same);
+        uint32_t seen = 0;
+        if (valid) seen = my_hist[dest[it]];
+        __builtin_amdgcn_wave_barrier();
+        rank[it] = seen + before;
+        if (valid && before == 0) my_hist[dest[it]] = (uint16_t)(seen + __popcll(same));
+        __builtin_amdgcn_wave_barrier();
+    }
+    __syncthreads();
+    // per bucket: turn the waves' counts into the waves' first output index
+    for (int b = threadIdx.x; b < U; b += kBlock) {
+        uint32_t run = 0;
+#pragma unroll
+        for (int k = 0; k < kWavesPerBlock; ++k) {
+            const uint32_t v = wave_hist[k * U + b];
+            wave_hist[k * U + b] = (uint16_t)run;
+            run += v;
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int it = 0; it < kRouteItems; ++it) {
+        const int64_t i = base + (int64_t)w * kRouteWaveSpan + it * kWave + lane;
+        if (i < n) {
+            const uint32_t j = bucket_base[dest[it]] + my_hist[dest[it]] + rank[it];
+            out_rows[j] = (int64_t)g[it];
+            out_pos[j] = (int32_t)i;
+        }
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void route_finalize_kernel(
+    const uint32_t* __restrict__ totals, int U, int64_t n, const RouteCounters* counters,
+    int64_t* __restrict__ bucket_offsets, int64_t* __restrict__ tier_counts)
+{
+    if (threadIdx.x == 0) {
+        int64_t run = 0;
+        for (int b = 0; b < U; ++b) { bucket_offsets[b] = run; run += (n > 0 ? totals[b] : 0u); }
+        bucket_offsets[U] = run;
+        if (tier_counts != nullptr)
+            for (int k = 0; k < 3; ++k) tier_counts[k] = n > 0 ? (int64_t)counters->tier[k] : 0;
+    }
+}
+
+}  // namespace fs
+
+extern "C" fs_status fs_route_bucketize(
+    const int64_t* ids, const int64_t* offsets, int32_t T, int32_t B,
+    const int64_t* row_base, const uint32_t* placement,
+    int64_t n, int32_t U, int32_t W, int32_t self,
+    int64_t* bucket_offsets, int64_t* out_rows, int32_t* out_pos,
+    int64_t* tier_counts,
+    void* workspace, size_t* workspace_bytes, void* stream, int32_t* dev_status)
+{
+    using namespace fs;
+    if (!workspace_bytes) return FS_ERR_NULL;
+    if (n < 0 || n >= (1LL << 31) || T < 1 || B < 1 || (int64_t)T * B >= (1LL << 31)) return FS_ERR_SIZE;
+    if (U < 1 || U > FS_MAX_BUCKETS || W < 1 || U % W != 0 || self < 0 || self >= U) return FS_ERR_CONFIG;
+
+    const int64_t tiles = (n + kRouteTile - 1) / kRouteTile;
+    Carver ws(workspace);
+    RouteCounters* counters = ws.take<RouteCounters>(1);
+    uint32_t* totals = ws.take<uint32_t>((size_t)U);
+    uint32_t* tile_hist = ws.take<uint32_t>((size_t)U * (size_t)tiles);
+    uint32_t* g_tmp = ws.take<uint32_t>((size_t)n);
+    uint16_t* dest_tmp = ws.take<uint16_t>((size_t)n);
+    if (!workspace) { *workspace_bytes = ws.used; return FS_OK; }
+    if (*workspace_bytes < ws.used || (reinterpret_cast<uintptr_t>(workspace) & 255)) return FS_ERR_WORKSPACE;
+    if (!offsets || !row_base || !placement || !bucket_offsets) return FS_ERR_NULL;
+    if (n > 0 && (!ids || !out_rows || !out_pos)) return FS_ERR_NULL;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int64_t S = (int64_t)T * B;
+    const int dest_bits = bits_for((uint64_t)(U - 1));
+    const unsigned prep_grid = (unsigned)((S + kBlock - 1) / kBlock < 1024 ? (S + kBlock - 1) / kBlock : 1024);
+    FS_LAUNCH("route_prepare", route_prepare_kernel, dim3(prep_grid), dim3(kBlock), s,
+              offsets, S, n, counters, dev_status);
+    if (n > 0) {
+        FS_LAUNCH_SMEM("route_remap", route_remap_kernel, dim3((unsigned)tiles), dim3(kBlock),
+                       (size_t)U * sizeof(uint32_t), s,
+                       ids, offsets, (int)T, (int64_t)B, row_base, placement, n, (int)U, (int)W, (int)self,
+                       dest_bits, dest_tmp, g_tmp, tile_hist, tiles, counters, dev_status);
+        FS_LAUNCH("route_scan", route_scan_kernel, dim3((unsigned)U), dim3(kBlock), s, tile_hist, tiles, totals);
+        FS_LAUNCH_SMEM("route_scatter", route_scatter_kernel, dim3((unsigned)tiles), dim3(kBlock),
+                       (size_t)U * sizeof(uint32_t) + (size_t)kWavesPerBlock * U * sizeof(uint16_t), s,
+                       dest_tmp, g_tmp, n, (int)U, dest_bits, tile_hist, tiles, totals, out_rows, out_pos);
+    }
+    FS_LAUNCH("route_finalize", route_finalize_kernel, dim3(1), dim3(kBlock), s,
+              totals, (int)U, n, counters, bucket_offsets, tier_counts);
+    return FS_OK;
+}

@@ -1,0 +1,124 @@
+"""GPU parity: fs_plan_replication (histogram + top-k under a budget) against the CPU oracle, bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+import fs_inputs
+import oracle
+from helpers import entry, random_jagged
+
+pytestmark = pytest.mark.gpu
+
+A, S, TAG, Z = oracle.PLAN_ACCUMULATE, oracle.PLAN_SELECT, oracle.PLAN_TAG, oracle.PLAN_ALLOW_ZERO
+
+
+@pytest.fixture(scope="module")
+def G():
+    import gpu_common
+    assert torch.cuda.is_available()
+    return gpu_common
+
+
+def hip_plan(G, ids, offsets, T, B, row_base, R, counts_np, flags, budget=0, bpr=1, placement_np=None, n=None):
+    import paper_2301_02959_amd as fs
+    dev = G.DEV
+    counts = torch.from_numpy(counts_np.view(np.int32).copy()).to(dev)
+    ids_d = G.to_dev(ids, torch.int64) if ids is not None else None
+    off_d = G.to_dev(offsets, torch.int64) if offsets is not None else None
+    rb_d = G.to_dev(row_base, torch.int64) if row_base is not None else None
+    if n is None:
+        n = int(offsets[-1]) if offsets is not None else 0
+    cap = min(R, budget // bpr) if (flags & S and bpr >= 1 and budget >= 0) else 0
+    sel = torch.full((max(cap, 1),), -7, dtype=torch.int64, device=dev)
+    nsel = torch.full((1,), -7, dtype=torch.int64, device=dev)
+    pl = G.placement_dev(placement_np) if placement_np is not None else None
+    st = torch.zeros(1, dtype=torch.int32, device=dev)
+    rc = fs.fs_plan_replication(ids_d, off_d, T, B, rb_d, n, R, counts, flags, budget, bpr, sel, nsel, pl, st,
+                                raise_on_error=False)
+    torch.cuda.synchronize()
+    k = int(nsel.item()) if flags & S and rc == 0 else 0
+    return (rc, int(st.item()), counts.cpu().numpy().view(np.uint32), sel[:k].cpu().numpy(),
+            pl.cpu().numpy().view(np.uint32) if pl is not None else None)
+
+
+@pytest.mark.parametrize("case", [dict(T=3, B=11, E=4000, L=600), dict(T=1, B=1, E=50_000, L=200_000),
+                                  dict(T=4, B=1, E=300, L=90_000)])
+def test_histogram_matches(G, case):
+    rng = np.random.default_rng(case["E"])
+    T, B, E = case["T"], case["B"], case["E"]
+    ids, offsets, row_base, n = random_jagged(rng, T, B, E, case["L"], zero_frac=0.0)
+    ids = (ids.astype(np.float64) ** 3 / float(E) ** 2).astype(np.int64)       # skewed towards small ids
+    base = rng.integers(0, 5, T * E).astype(np.uint32)
+    oc = base.copy()
+    orc, ost, _ = oracle.plan_replication(ids, offsets, T, B, row_base, T * E, oc, A)
+    rc, st, hc, _, _ = hip_plan(G, ids, offsets, T, B, row_base, T * E, base, A)
+    assert rc == orc == 0 and st == ost == 0
+    assert np.array_equal(hc, oc) and hc.sum() - base.sum() == n
+
+
+def test_histogram_zipf_profile_and_select(G):
+    """c5's laws on a small table: profile, then choose under a budget, tag, and compare everything."""
+    cfg = fs_inputs.CONFIGS["c5"].scaled(E=200_000, T=3)
+    chunks = list(fs_inputs.make_profile_sample(cfg, per_table=400_000, device="cpu", chunk=150_000))
+    R = cfg.R
+    oc = np.zeros(R, np.uint32)
+    hc = np.zeros(R, np.uint32)
+    for t, ids_t in chunks:                      # one call per chunk: counts accumulate across calls
+        ids = ids_t.numpy()
+        offsets = np.zeros(cfg.T + 1, np.int64)
+        offsets[t + 1:] = len(ids)
+        row_base = np.arange(cfg.T + 1) * cfg.E
+        orc, ost, _ = oracle.plan_replication(ids, offsets, cfg.T, 1, row_base, R, oc, A)
+        rc, st, hc, _, _ = hip_plan(G, ids, offsets, cfg.T, 1, row_base, R, hc, A)
+        assert rc == orc == 0 and st == ost == 0
+    assert np.array_equal(hc, oc) and oc.sum() == 3 * 400_000
+    pl = np.full(R, entry(2, 3), np.uint32)
+    for budget_rows in (1000, int((oc > 0).sum()) + 10):       # budget binds / the non-zero rule binds
+        opl, hpl = pl.copy(), pl.copy()
+        orc, ost, osel = oracle.plan_replication(None, None, 1, 1, None, R, oc.copy(), S | TAG, budget_rows * 256 + 17, 256, opl)
+        rc, st, _, hsel, hpl = hip_plan(G, None, None, 1, 1, None, R, oc, S | TAG, budget_rows * 256 + 17, 256, hpl)
+        assert rc == orc == 0 and st == ost == 0
+        assert np.array_equal(hsel, osel) and np.array_equal(hpl, opl)
+        assert len(osel) == min(budget_rows, int((oc > 0).sum()))
+
+
+@pytest.mark.parametrize("seed", range(3))
+def test_select_ties_zeros_and_allow_zero(G, seed):
+    rng = np.random.default_rng(seed)
+    R = 70_001                                              # several compaction tiles + ragged tail
+    counts = np.minimum(rng.pareto(1.0, R) * 2, 1e9).astype(np.uint32)      # ~1/3 zeros, heavy ties
+    counts[rng.integers(0, R, 5)] = 2 ** 32 - 1
+    nz = int((counts > 0).sum())
+    for flags, cap in ((S, 0), (S, 1), (S, 5000), (S, nz), (S, nz + 100), (S | Z, nz + 100), (S | Z, R + 5)):
+        orc, ost, osel = oracle.plan_replication(None, None, 1, 1, None, R, counts.copy(), flags, cap * 8, 8)
+        rc, st, _, hsel, _ = hip_plan(G, None, None, 1, 1, None, R, counts, flags, cap * 8, 8)
+        assert rc == orc == 0 and np.array_equal(hsel, osel), (flags, cap)
+
+
+def test_saturation_faults_and_one_call_does_all(G):
+    counts = np.array([2 ** 32 - 3, 0, 5, 0], np.uint32)
+    orc, ost, _ = oracle.plan_replication([0, 0, 0, 0, 2], [0, 5], 1, 1, [0, 4], 4, counts.copy(), A)
+    rc, st, hc, _, _ = hip_plan(G, [0, 0, 0, 0, 2], [0, 5], 1, 1, [0, 4], 4, counts, A)
+    assert st == ost == oracle.COUNT_OVERFLOW and hc.tolist() == [2 ** 32 - 1, 0, 6, 0]
+    rc, st, hc, _, _ = hip_plan(G, [0, 0], [0, 2], 1, 1, [0, 4], 4, counts, A)
+    assert st == 0 and hc[0] == 2 ** 32 - 1
+    rc, st, hc, _, _ = hip_plan(G, [9, -1, 1], [0, 3], 1, 1, [0, 4], 4, np.zeros(4, np.uint32), A)
+    assert st == oracle.BAD_ID and hc.tolist() == [2, 1, 0, 0]
+    rc, st, hc, _, _ = hip_plan(G, [1, 1, 1], [0, 2], 1, 1, [0, 4], 4, np.zeros(4, np.uint32), A, n=3)
+    assert st == oracle.BAD_OFFSETS and hc.sum() == 0
+    # accumulate + select + tag in one call
+    rng = np.random.default_rng(5)
+    ids, offsets, row_base, n = random_jagged(rng, 2, 30, 500, 80)
+    pl = np.array([entry(2, r % 4) for r in range(1000)], np.uint32)
+    oc, opl = np.zeros(1000, np.uint32), pl.copy()
+    orc, ost, osel = oracle.plan_replication(ids, offsets, 2, 30, row_base, 1000, oc, A | S | TAG, 64 * 50, 64, opl)
+    rc, st, hc, hsel, hpl = hip_plan(G, ids, offsets, 2, 30, row_base, 1000, np.zeros(1000, np.uint32), A | S | TAG, 64 * 50, 64, pl)
+    assert rc == 0 and np.array_equal(hc, oc) and np.array_equal(hsel, osel) and np.array_equal(hpl, opl)
+    # host faults
+    z = np.zeros(4, np.uint32)
+    assert hip_plan(G, None, None, 1, 1, None, 4, z, 16)[0] == 6
+    assert hip_plan(G, None, None, 1, 1, None, 4, z, TAG)[0] == 6
+    assert hip_plan(G, None, None, 1, 1, None, 4, z, S, -1, 1)[0] == 2
+    assert hip_plan(G, None, None, 1, 1, None, 4, z, S, 1, 0)[0] == 2
+    assert hip_plan(G, None, None, 1, 1, None, 4, z, S | TAG, 1, 1)[0] == 1
+    assert hip_plan(G, None, None, 1, 1, None, 4, z, 0)[0] == 0
