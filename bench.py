@@ -1,0 +1,251 @@
+#!/usr/bin/env python3
+"""Benchmark of the tiered sequence-embedding lookup on one MI355X.
+
+One step = one pass of the whole hot path over one synthetic batch resident in HBM:
+  fs_plan_replication (histogram of the batch + top-k under a budget)
+  -> fs_route_bucketize -> fs_seq_gather_fwd (all buckets) -> fs_seq_grad_bwd (all buckets).
+Prints ONE JSON line: lookups/s over the whole step, the roofline of the dominant kernel
+(timed live with HIP events around each launch) and the CPU oracle timed on a bounded sample.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config c3] [--variant 0|1]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="c3", help="c1..c5 (c3 = the configuration the target is stated on)")
+    ap.add_argument("--variant", type=int, default=0, help="backward: 0 sort/bit-exact, 1 atomic partials")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-tables", type=int, default=0, help="tables in the oracle's sample (0 = automatic)")
+    ap.add_argument("--scale-rows", type=int, default=1, help="divide E by this (debugging only; reported)")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print(f"bench.py: this build runs on ONE GPU only (owner buckets are output partitions, no "
+              f"collectives); --gpus {args.gpus} is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import fs_inputs
+    import paper_2301_02959_amd as fs
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    cfg = fs_inputs.CONFIGS[args.config]
+    if args.scale_rows > 1:
+        cfg = cfg.scaled(E=cfg.E // args.scale_rows)
+
+    # ---------------------------------------------------------------- inputs, resident in HBM
+    t_gen = time.time()
+    batch = fs_inputs.make_batch(cfg, dev, keep_perms=False)
+    placement = fs_inputs.make_placement(cfg, batch["perms"], dev)
+    batch["perms"] = None
+    n = batch["n"]
+    ids, offsets, row_base = batch["ids"], batch["offsets"], batch["row_base"]
+    weights = fs_inputs.make_table(cfg, dev)
+    grad_out = fs_inputs.make_grad(cfg, n, dev)
+    torch.cuda.synchronize()
+    t_gen = time.time() - t_gen
+    R, D, U, W, T, B = cfg.R, cfg.D, cfg.U, cfg.W, cfg.T, cfg.B
+    self_b = cfg.self_bucket
+    row_bytes = cfg.row_bytes
+
+    # ---------------------------------------------------------------- outputs and workspaces
+    bucket_offsets = torch.zeros(U + 1, dtype=torch.int64, device=dev)
+    out_rows = torch.zeros(n, dtype=torch.int64, device=dev)
+    out_pos = torch.zeros(n, dtype=torch.int32, device=dev)
+    tier_counts = torch.zeros(3, dtype=torch.int64, device=dev)
+    status = torch.zeros(1, dtype=torch.int32, device=dev)
+    out = torch.empty(n, D, dtype=cfg.torch_dtype, device=dev)
+    cap_unique = min(n, R)
+    uniq_rows = torch.zeros(cap_unique, dtype=torch.int64, device=dev)
+    row_grads = torch.empty(cap_unique, D, dtype=torch.float32, device=dev)
+    num_unique = torch.zeros(1, dtype=torch.int64, device=dev)
+    counts = torch.zeros(R, dtype=torch.int32, device=dev)
+    budget_rows = max(1, int((cfg.f_global if cfg.f_global > 0 else 0.01) * R))
+    sel_rows = torch.zeros(budget_rows, dtype=torch.int64, device=dev)
+    num_selected = torch.zeros(1, dtype=torch.int64, device=dev)
+    plan_flags = fs.FS_PLAN_ACCUMULATE | fs.FS_PLAN_SELECT
+
+    import ctypes
+
+    def ws_for(query):
+        size = ctypes.c_size_t(0)
+        query(size)
+        return torch.empty(max(int(size.value), 256), dtype=torch.uint8, device=dev)
+
+    L = fs.lib()
+    z = ctypes.c_void_p(0)
+    ws_route = torch.empty(max(fs.route_workspace_bytes(T, B, n, U, W, self_b), 256), dtype=torch.uint8, device=dev)
+
+    def q_bwd(size):
+        rc = L.fs_seq_grad_bwd(z, ctypes.c_int64(n), ctypes.c_int32(D), ctypes.c_int(fs_inputs.DTYPE_CODE[cfg.dtype]),
+                               z, z, ctypes.c_int64(0), ctypes.c_int64(n), ctypes.c_int64(R), ctypes.c_int32(args.variant),
+                               z, z, ctypes.c_int64(cap_unique), z, z, ctypes.byref(size), z, z)
+        assert rc == 0, rc
+
+    def q_plan(size):
+        rc = L.fs_plan_replication(z, z, ctypes.c_int32(T), ctypes.c_int32(B), z, ctypes.c_int64(n), ctypes.c_int64(R),
+                                   z, ctypes.c_int32(plan_flags), ctypes.c_int64(budget_rows * row_bytes),
+                                   ctypes.c_int64(row_bytes), z, z, z, z, ctypes.byref(size), z, z)
+        assert rc == 0, rc
+
+    ws_bwd = ws_for(q_bwd)
+    ws_plan = ws_for(q_plan)
+
+    def step():
+        fs.fs_plan_replication(ids, offsets, T, B, row_base, n, R, counts, plan_flags, budget_rows * row_bytes,
+                               row_bytes, sel_rows, num_selected, None, status, workspace=ws_plan)
+        fs.fs_route_bucketize(ids, offsets, T, B, row_base, placement, n, U, W, self_b, bucket_offsets, out_rows,
+                              out_pos, tier_counts, status, workspace=ws_route)
+        fs.fs_seq_gather_fwd(weights, out_rows, out_pos, 0, n, out, status)
+        fs.fs_seq_grad_bwd(grad_out, out_rows, out_pos, 0, n, R, args.variant, uniq_rows, row_grads, cap_unique,
+                           num_unique, status, workspace=ws_bwd)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # ---------------------------------------------------------------- timed region
+    records_per_step = 64
+    fs.fs_prof_begin(records_per_step * args.steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    records = fs.fs_prof_end(records_per_step * args.steps)
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    assert int(status.item()) == 0, f"device status {int(status.item())}"
+    n_u = int(num_unique.item())
+
+    per_kernel = {}
+    for name, ms in records:
+        tot, cnt = per_kernel.get(name, (0.0, 0))
+        per_kernel[name] = (tot + ms, cnt + 1)
+    kernel_ms = {k: v[0] / args.steps for k, v in per_kernel.items()}           # per step (summed launches)
+    kernel_avg = {k: v[0] / v[1] for k, v in per_kernel.items()}                # per launch
+    stage_ms = {
+        "plan": sum(v for k, v in kernel_ms.items() if k.startswith("plan_")),
+        "route": sum(v for k, v in kernel_ms.items() if k.startswith("route_")),
+        "gather": kernel_ms.get("gather_rows", 0.0),
+        "bwd": sum(v for k, v in kernel_ms.items() if k.startswith("bwd_")),
+        "sort": sum(v for k, v in kernel_ms.items() if k.startswith("sort_")),
+    }
+
+    # algorithmic bytes per launch of the two bandwidth kernels
+    alg = {
+        "gather_rows": n * row_bytes + n_u * row_bytes + n * 12,                # write out, read each distinct row once, indices
+        "bwd_segreduce": n * row_bytes + n_u * D * 4 + n * 8,                   # read grad_out once, write row_grads, sorted pairs
+    }
+    dominant = max(alg, key=lambda k: kernel_avg.get(k, 0.0))
+    achieved = alg[dominant] / (kernel_avg[dominant] * 1e-3) / 1e9
+    traffic = None
+    tfile = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tfile):
+        try:
+            traffic = json.load(open(tfile)).get(f"{cfg.name}:{dominant}")
+        except Exception:
+            traffic = None
+    roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                "algorithmic_bytes": alg[dominant], "avg_ms": round(kernel_avg[dominant], 4)}
+    other = [k for k in alg if k != dominant][0]
+    if other in kernel_avg:
+        roofline["also"] = {"kernel": other, "achieved": round(alg[other] / (kernel_avg[other] * 1e-3) / 1e9, 1),
+                            "frac": round(alg[other] / (kernel_avg[other] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                            "algorithmic_bytes": alg[other], "avg_ms": round(kernel_avg[other], 4)}
+
+    result = {
+        "metric": "embedding lookups/sec and achieved HBM GB/s (% of peak), fwd+bwd, 1 GPU",
+        "value": round(n / (ms_per_step * 1e-3), 1), "unit": "lookups/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": {"f32": "f32", "f16": "f16", "bf16": "bf16"}[cfg.dtype] + " rows, f32 accumulation, int64/int32 indices",
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: {T} tables x {cfg.E} rows x D={D} {cfg.dtype}, batch {B}, "
+                               f"{cfg.length_law} lengths, Zipf({cfg.alpha}), {U} buckets (W={W})",
+                   "lookups": n, "distinct_rows": n_u, "bwd_variant": args.variant,
+                   "tier_counts": [int(x) for x in tier_counts.tolist()], "scale_rows": args.scale_rows},
+        "roofline": roofline,
+        "stage_ms": {k: round(v, 4) for k, v in stage_ms.items()},
+        "kernel_ms_per_step": {k: round(v, 4) for k, v in sorted(kernel_ms.items())},
+        "input_gen_s": round(t_gen, 1),
+    }
+
+    # ---------------------------------------------------------------- CPU oracle on a bounded sample
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(args, cfg, ids, offsets, placement, weights, grad_out)
+
+    print(json.dumps(result), flush=True)
+
+
+def cpu_baseline(args, cfg, ids, offsets, placement, weights, grad_out):
+    """The oracle as it stands (one thread) on the first tables of the same batch: plan + route +
+    gather + backward on the host copy of exactly those inputs."""
+    import numpy as np
+    import torch
+    import fs_inputs
+    import oracle
+
+    B, E, D = cfg.B, cfg.E, cfg.D
+    tables = args.cpu_tables
+    if tables <= 0:                                   # aim at a few million lookups
+        per_table = max(1, int(offsets[B].item()))
+        tables = max(1, min(cfg.T, int(2_000_000 // per_table) or 1))
+    n_s = int(offsets[tables * B].item())
+    ids_h = ids[:n_s].cpu().numpy()
+    off_h = offsets[:tables * B + 1].cpu().numpy()
+    rb_h = (np.arange(tables + 1) * E).astype(np.int64)
+    pl_h = placement[:tables * E].cpu().numpy().view(np.uint32)
+    w_h = fs_inputs.as_numpy_bits(weights[:tables * E])
+    g_h = fs_inputs.as_numpy_bits(grad_out[:n_s])
+    code = {"f32": oracle.F32, "f16": oracle.F16, "bf16": oracle.BF16}[cfg.dtype]
+    R_s = tables * E
+    counts = np.zeros(R_s, np.uint32)
+    budget_rows = max(1, int((cfg.f_global if cfg.f_global > 0 else 0.01) * R_s))
+    out_h = np.zeros((n_s, D), w_h.dtype)
+    oracle.lib()
+    t0 = time.perf_counter()
+    rc0, _, _ = oracle.plan_replication(ids_h, off_h, tables, B, rb_h, R_s, counts,
+                                        oracle.PLAN_ACCUMULATE | oracle.PLAN_SELECT, budget_rows * cfg.row_bytes,
+                                        cfg.row_bytes)
+    rc1, st, bo, rows, pos, tc = oracle.route_bucketize(ids_h, off_h, tables, B, rb_h, pl_h, cfg.U, cfg.W,
+                                                        cfg.self_bucket)
+    rc2, _ = oracle.seq_gather_fwd(w_h, rows, pos, 0, n_s, out_h, dtype=code)
+    rc3, _, u, g32, _, nu = oracle.seq_grad_bwd(g_h, rows, pos, 0, n_s, R_s, dtype=code, want64=False,
+                                                cap_unique=min(n_s, R_s))
+    dt = time.perf_counter() - t0
+    assert rc0 == rc1 == rc2 == rc3 == 0
+    return {"value": round(n_s / dt, 1), "unit": "lookups/s", "cores": 1, "kind": "oracle",
+            "sample": f"first {tables} of {cfg.T} tables of the same batch ({n_s} lookups, {nu} distinct rows), "
+                      f"plan + route + gather + backward, single-threaded C oracle, {dt:.2f} s",
+            "host_cores_available": os.cpu_count()}
+
+
+if __name__ == "__main__":
+    main()

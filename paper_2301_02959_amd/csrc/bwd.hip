@@ -9,9 +9,10 @@
 //   bwd_scan_blocks   exclusive scan of the per-block sums -> index of every run,
 //                     *num_unique
 //   bwd_segreduce     a group of LG lanes (one 16-byte piece of the row per lane) walks
-//                     one chunk left to right with 8 gradient rows in flight; a run that
-//                     starts in the chunk goes to row_grads, the piece that continues a
-//                     run from the previous chunk goes to carry[chunk]
+//                     one chunk left to right with 8 gradient rows in flight; the chunk's
+//                     keys and positions are staged in LDS by coalesced loads and read back
+//                     as broadcasts; a run that starts in the chunk goes to row_grads, the
+//                     piece that continues a run from the previous chunk goes to carry[chunk]
 //   bwd_fold          for every run that spills over a chunk end: row_grads += carry of
 //                     the following chunks, left to right
 // which is exactly the summation order stated in flexshard.h (chunk = FS_BWD_TILE).
@@ -163,6 +164,12 @@ struct Vec<FS_BF16> {
     }
 };
 
+// A group of LG lanes (LG >= 8) walks one chunk of 256 sorted lookups left to right.  The
+// group first stages the chunk's keys, positions and per-lookup flags in LDS with coalesced
+// loads (a per-step index load in front of every gradient row would stall the row loads):
+//   end: the run's piece ends here (next key differs, or last lookup of the chunk)
+//   go:  the next sorted lookup has the same key (also across the chunk end)
+// then reads them back as LDS broadcasts, 8 lookups (= 8 gradient rows in flight) per batch.
 template <int LG, int DT>
 __global__ __launch_bounds__(kBlock) void bwd_segreduce_kernel(
     const u32x4* __restrict__ grad, int units, int D,
@@ -171,66 +178,95 @@ __global__ __launch_bounds__(kBlock) void bwd_segreduce_kernel(
     int64_t* __restrict__ uniq_rows, float* __restrict__ row_grads, int64_t cap,
     float* __restrict__ carry, int atomic)
 {
+    static_assert(LG >= 8 && LG <= kWave, "groups of 8..64 lanes");
     constexpr int N = Vec<DT>::N;
     constexpr int GPB = kBlock / LG;
+    constexpr uint32_t kEnd = 1u, kGo = 2u;
+    __shared__ uint32_t s_val[GPB][kChunk];
+    __shared__ uint32_t s_key[GPB][kChunk];
+    __shared__ uint8_t s_flag[GPB][kChunk];
     const int lig = threadIdx.x % LG;
     const int gi = threadIdx.x / LG;
-    const int64_t chunk = (int64_t)blockIdx.x * GPB + gi;
-    const int c = blockIdx.y * LG + lig;                 // 16-byte piece of the row
-    if (chunk >= chunks || c >= units) return;
+    int64_t chunk = (int64_t)blockIdx.x * GPB + gi;
+    const bool group_on = chunk < chunks;                        // idle groups walk the last chunk, writing nothing
+    if (!group_on) chunk = chunks - 1;
+    const int c = blockIdx.y * LG + lig;                         // 16-byte piece of the row
+    const bool lane_on = group_on && c < units;
+    const int cc = c < units ? c : 0;
     const int64_t k0 = chunk * kChunk;
     const int64_t k1 = k0 + kChunk < m ? k0 + kChunk : m;
-    const int col = c * N;
+    const int cnt = (int)(k1 - k0);
+    const int col = cc * N;
 
+    {
+        constexpr int PER = kChunk / LG;
+        uint32_t key[PER], next[PER], val[PER];
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {                          // all loads first, then the LDS writes
+            const int64_t k = k0 + i * LG + lig;
+            key[i] = k < k1 ? keys[k] : kNoKey;
+            next[i] = k + 1 < m ? keys[k + 1] : kNoKey;
+            val[i] = k < k1 ? vals[k] : 0u;                      // past the end: position 0, loaded but unused
+        }
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int e = i * LG + lig;
+            const bool go = k0 + e < k1 && next[i] == key[i];
+            const bool end = k0 + e + 1 >= k1 || !go;
+            s_key[gi][e] = key[i];
+            s_val[gi][e] = val[i];
+            s_flag[gi][e] = (uint8_t)((end ? kEnd : 0u) | (go ? kGo : 0u));
+        }
+    }
     bool piece_cont = k0 > 0 && keys[k0 - 1] == keys[k0];    // first piece continues the previous chunk's run
     int64_t u = (int64_t)runs_before(block_base, chunk_local, chunk, chunks) - 1;
     bool fresh = true;
     float acc[N];
+    __syncthreads();
 
-    for (int64_t kb = k0; kb < k1; kb += kBwdUnroll) {
-        uint32_t kk[kBwdUnroll + 1];
-        uint32_t pp[kBwdUnroll];
+#pragma unroll 1
+    for (int e0 = 0; e0 < cnt; e0 += kBwdUnroll) {
         u32x4 x[kBwdUnroll];
-#pragma unroll
-        for (int j = 0; j <= kBwdUnroll; ++j) kk[j] = kb + j < m ? keys[kb + j] : kNoKey;
-#pragma unroll
-        for (int j = 0; j < kBwdUnroll; ++j) pp[j] = kb + j < k1 ? vals[kb + j] : 0u;
-#pragma unroll
-        for (int j = 0; j < kBwdUnroll; ++j)
-            if (kb + j < k1) x[j] = load_stream(grad + (int64_t)pp[j] * units + c);
+        uint32_t ff[kBwdUnroll];
 #pragma unroll
         for (int j = 0; j < kBwdUnroll; ++j) {
-            const int64_t k = kb + j;
-            if (k < k1) {
+            const uint32_t pj = s_val[gi][e0 + j];
+            ff[j] = s_flag[gi][e0 + j];
+            x[j] = load_stream(grad + (int64_t)pj * units + cc);  // unconditional: a predicated load serialises the batch
+        }
+#pragma unroll
+        for (int j = 0; j < kBwdUnroll; ++j) {
+            if (e0 + j < cnt) {
                 float f[N];
                 Vec<DT>::load(x[j], f);
                 if (fresh) {
                     if (!piece_cont) ++u;
 #pragma unroll
-                    for (int i = 0; i < N; ++i) acc[i] = f[i];
+                    for (int q = 0; q < N; ++q) acc[q] = f[q];
                 } else {
 #pragma unroll
-                    for (int i = 0; i < N; ++i) acc[i] = acc[i] + f[i];
+                    for (int q = 0; q < N; ++q) acc[q] = acc[q] + f[q];
                 }
-                const bool last_in_chunk = k + 1 == k1;
-                const bool run_goes_on = kk[j + 1] == kk[j];          // kNoKey past the end
-                if (last_in_chunk || !run_goes_on) {
-                    if (piece_cont && !atomic) {
+                if (ff[j] & kEnd) {                              // the piece ends here
+                    const bool run_goes_on = (ff[j] & kGo) != 0;
+                    if (!lane_on) {
+                        // nothing to write
+                    } else if (piece_cont && !atomic) {
                         float* dst = carry + chunk * D + col;
 #pragma unroll
-                        for (int i = 0; i < N; i += 4)
-                            *reinterpret_cast<f32x4*>(dst + i) = f32x4{acc[i], acc[i + 1], acc[i + 2], acc[i + 3]};
+                        for (int q = 0; q < N; q += 4)
+                            *reinterpret_cast<f32x4*>(dst + q) = f32x4{acc[q], acc[q + 1], acc[q + 2], acc[q + 3]};
                     } else if (u < cap) {
                         float* dst = row_grads + u * D + col;
                         if (atomic && (piece_cont || run_goes_on)) {
 #pragma unroll
-                            for (int i = 0; i < N; ++i) unsafeAtomicAdd(dst + i, acc[i]);
+                            for (int q = 0; q < N; ++q) unsafeAtomicAdd(dst + q, acc[q]);
                         } else {
 #pragma unroll
-                            for (int i = 0; i < N; i += 4)
-                                *reinterpret_cast<f32x4*>(dst + i) = f32x4{acc[i], acc[i + 1], acc[i + 2], acc[i + 3]};
+                            for (int q = 0; q < N; q += 4)
+                                *reinterpret_cast<f32x4*>(dst + q) = f32x4{acc[q], acc[q + 1], acc[q + 2], acc[q + 3]};
                         }
-                        if (!piece_cont && c == 0) uniq_rows[u] = (int64_t)kk[j];
+                        if (!piece_cont && c == 0) uniq_rows[u] = (int64_t)s_key[gi][e0 + j];
                     }
                     fresh = true;
                     piece_cont = false;
@@ -395,9 +431,7 @@ extern "C" fs_status fs_seq_grad_bwd(
 #define FS_SEG(LG)                                                                                              \
     rc = launch_segreduce<LG>(dtype, grad_out, units, (int)D, keys, vals, m, chunks, block_base, chunk_local,     \
                               uniq_rows, row_grads, cap_unique, carry, (int)variant, s)
-    if (units <= 2) FS_SEG(2);
-    else if (units <= 4) FS_SEG(4);
-    else if (units <= 8) FS_SEG(8);
+    if (units <= 8) FS_SEG(8);
     else if (units <= 16) FS_SEG(16);
     else if (units <= 32) FS_SEG(32);
     else FS_SEG(64);

@@ -1,62 +1,90 @@
 // fs_seq_gather_fwd: out[pos[j], :] = weights[rows[j], :] for j in [j0, j1).
 //
-// HBM-bound bit copy.  A row of `units` 16-byte pieces is moved by a group of LG
-// lanes (LG = the power of two >= units, at most 64), one 128-bit load and one
-// 128-bit non-temporal store per lane; a wave therefore moves 64/LG rows per
-// instruction and each group keeps UNR rows in flight.  Table reads stay
-// cacheable (popular rows are re-read from L2 / Infinity Cache), the output is
-// streamed past the caches.  Blocks are mapped so that each XCD walks one
-// contiguous range of j: inside a bucket j is ascending in the flat position,
-// i.e. table-major, so an XCD's L2 holds the hot rows of one or two tables.
+// HBM-bound bit copy.  A wave owns 64 consecutive lookups: it fetches their 64 row
+// indices and 64 positions with ONE coalesced load each (a per-row index load in
+// front of every row costs a third of the bandwidth: the store cannot issue before
+// its index has come back from HBM), then hands them to the lanes with
+// ds_bpermute.  A row of `units` 16-byte pieces is moved by a group of LG lanes
+// (LG = the power of two >= units, at most 64), one 128-bit load and one 128-bit
+// non-temporal store per lane, so a wave moves 64/LG rows per instruction and keeps
+// UNR instructions in flight.  Table reads stay cacheable (popular rows are re-read
+// from L2 / Infinity Cache), the output is streamed past the caches.
+// Blocks take tiles in launch order: the round-robin deal of blocks to the 8 XCDs
+// then spreads the cold, other-bucket tail of the j range over all of them (giving
+// each XCD one contiguous eighth of j leaves the last XCD with all the cache misses).
 #include "fs_common.h"
 
 namespace fs {
 
-constexpr int kGatherUnroll = 8;
+constexpr int kGatherRowsPerWave = kWave;
+constexpr int kGatherRowsPerBlock = kGatherRowsPerWave * kWavesPerBlock;
+
+template <int LG>
+struct GatherShape {
+    static constexpr int RPI = kWave / LG;                                   // rows per instruction
+    static constexpr int UNR = RPI >= 8 ? kWave / RPI : (LG == 16 ? 8 : 16); // instructions in flight
+};
+
+// Moves the wave's 64 rows.  GUARD = false: every lookup of the wave is valid, loads and
+// stores carry no per-lane predicate (a predicated load makes the compiler wait for each
+// load before it issues the next, which serialises the 16 loads of a batch).
+template <int LG, bool GUARD>
+__device__ __forceinline__ void gather_wave(const u32x4* __restrict__ weights, int units, u32x4* __restrict__ out,
+                                            int64_t my_row, int32_t my_pos, int my_ok)
+{
+    constexpr int RPI = GatherShape<LG>::RPI;
+    constexpr int UNR = GatherShape<LG>::UNR;
+    const int lane = lane_id();
+    const int g = lane / LG;
+    const int lig = lane % LG;
+#pragma unroll 1
+    for (int s = 0; s < kGatherRowsPerWave; s += UNR * RPI) {
+        int64_t src[UNR];
+        int64_t dst[UNR];
+        bool ok[UNR];
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const int from = s + u * RPI + g;            // lane that holds this row's indices
+            const int64_t r = __shfl(my_row, from);
+            const int32_t p = __shfl(my_pos, from);
+            ok[u] = GUARD ? __shfl(my_ok, from) != 0 : true;
+            src[u] = r * units;
+            dst[u] = (int64_t)p * units;
+        }
+        for (int c = lig; c < units; c += LG) {
+            u32x4 v[UNR];
+#pragma unroll
+            for (int u = 0; u < UNR; ++u) v[u] = weights[src[u] + c];       // invalid lookups read row 0
+#pragma unroll
+            for (int u = 0; u < UNR; ++u)
+                if (!GUARD || ok[u]) store_stream(out + dst[u] + c, v[u]);
+        }
+    }
+}
 
 template <int LG>
 __global__ __launch_bounds__(kBlock) void gather_rows_kernel(
     const u32x4* __restrict__ weights, int64_t R, int units,
     const int64_t* __restrict__ rows, const int32_t* __restrict__ pos, int64_t m,
-    u32x4* __restrict__ out, int64_t n, int64_t tiles, int64_t tiles_per_xcd,
-    int32_t* status)
+    u32x4* __restrict__ out, int64_t n, int32_t* status)
 {
-    constexpr int GPB = kBlock / LG;               // row groups per block
-    constexpr int TILE = GPB * kGatherUnroll;      // rows per block
-    const int64_t tile = xcd_contiguous_tile(blockIdx.x, tiles_per_xcd);
-    if (tile >= tiles) return;
-    const int lig = threadIdx.x % LG;
-    const int gi = threadIdx.x / LG;
-    const int64_t base = tile * TILE;
+    const int lane = lane_id();
+    const int64_t wbase = ((int64_t)blockIdx.x * kWavesPerBlock + wave_id()) * kGatherRowsPerWave;
+    if (wbase >= m) return;                              // wave-uniform
 
-    int64_t src[kGatherUnroll];
-    int64_t dst[kGatherUnroll];
-    bool ok[kGatherUnroll];
-    bool bad = false;
-#pragma unroll
-    for (int u = 0; u < kGatherUnroll; ++u) {
-        const int64_t jj = base + (int64_t)u * GPB + gi;
-        ok[u] = jj < m;
-        int64_t r = 0;
-        int64_t p = 0;
-        if (ok[u]) {
-            r = load_stream(rows + jj);
-            p = load_stream(pos + jj);
-            if (r < 0 || r >= R || p < 0 || p >= n) { ok[u] = false; bad = true; }
-        }
-        src[u] = r * units;
-        dst[u] = p * units;
+    // one coalesced load of the wave's 64 (row, position) pairs
+    const int64_t jj = wbase + lane;
+    int64_t my_row = 0;
+    int32_t my_pos = 0;
+    int my_ok = 0;
+    if (jj < m) {
+        my_row = load_stream(rows + jj);
+        my_pos = load_stream(pos + jj);
+        my_ok = (my_row >= 0 && my_row < R && my_pos >= 0 && (int64_t)my_pos < n) ? 1 : 0;
+        if (!my_ok) { report(status, FS_DEV_BAD_ID); my_row = 0; my_pos = 0; }
     }
-    for (int c = lig; c < units; c += LG) {
-        u32x4 v[kGatherUnroll];
-#pragma unroll
-        for (int u = 0; u < kGatherUnroll; ++u)
-            if (ok[u]) v[u] = weights[src[u] + c];
-#pragma unroll
-        for (int u = 0; u < kGatherUnroll; ++u)
-            if (ok[u]) store_stream(out + dst[u] + c, v[u]);
-    }
-    if (bad && lig == 0) report(status, FS_DEV_BAD_ID);
+    if (ballot(my_ok != 0) == ~0ull) gather_wave<LG, false>(weights, units, out, my_row, my_pos, my_ok);
+    else gather_wave<LG, true>(weights, units, out, my_row, my_pos, my_ok);   // ragged tail or a bad index
 }
 
 template <int LG>
@@ -64,14 +92,11 @@ static fs_status launch_gather(const void* weights, int64_t R, int units, const 
                                const int32_t* pos, int64_t m, void* out, int64_t n,
                                hipStream_t stream, int32_t* status)
 {
-    constexpr int TILE = (kBlock / LG) * kGatherUnroll;
-    const int64_t tiles = (m + TILE - 1) / TILE;
-    const int64_t per_xcd = (tiles + kXcds - 1) / kXcds;
-    const int64_t grid = per_xcd * kXcds;
+    const int64_t grid = (m + kGatherRowsPerBlock - 1) / kGatherRowsPerBlock;
     if (grid > 0x7FFFFFFF) return FS_ERR_SIZE;
     FS_LAUNCH("gather_rows", gather_rows_kernel<LG>, dim3((unsigned)grid), dim3(kBlock), stream,
               static_cast<const u32x4*>(weights), R, units, rows, pos, m,
-              static_cast<u32x4*>(out), n, tiles, per_xcd, status);
+              static_cast<u32x4*>(out), n, status);
     return FS_OK;
 }
 

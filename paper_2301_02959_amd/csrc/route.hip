@@ -2,13 +2,13 @@
 //
 // A stable counting sort of the n lookups by destination bucket, in four steps
 // that touch each lookup twice:
-//   route_prepare   validate offsets, clear counters
+//   route_prepare   validate offsets
 //   route_remap     one 2048-lookup tile per block: table of each lookup, global
 //                   row g, placement entry, destination; per-tile bucket
-//                   histogram (wave-aggregated LDS adds); dest (u16) and g (u32)
-//                   go to the workspace
-//   route_scan      one block per bucket: exclusive scan of that bucket's per-tile
-//                   counts over the tiles, and the bucket's total
+//                   histogram (wave-aggregated LDS adds) plus the tile's three tier
+//                   counts; dest (u16) and g (u32) go to the workspace
+//   route_scan      one block per bucket (and per tier): exclusive scan of its per-tile
+//                   counts over the tiles, and its total
 //   route_scatter   same tiles: each wave ranks its 512 consecutive lookups by
 //                   ballot matching against a wave-private running histogram in
 //                   LDS, adds the tile's and the bucket's base, writes
@@ -23,19 +23,11 @@ constexpr int kRouteItems = 8;                        // lookups per thread
 constexpr int kRouteTile = kBlock * kRouteItems;      // lookups per block
 constexpr int kRouteWaveSpan = kWave * kRouteItems;   // consecutive lookups per wave
 
-struct RouteCounters {
-    unsigned long long tier[3];
-    unsigned int bad_offsets;
-};
-
 __global__ __launch_bounds__(kBlock) void route_prepare_kernel(
-    const int64_t* __restrict__ offsets, int64_t S, int64_t n, RouteCounters* counters, int32_t* status)
+    const int64_t* __restrict__ offsets, int64_t S, int64_t n, int32_t* status)
 {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (tid == 0) {
-        counters->tier[0] = 0; counters->tier[1] = 0; counters->tier[2] = 0;
-    }
     bool bad = false;
     for (int64_t s = tid; s < S; s += stride) bad |= offsets[s] > offsets[s + 1];
     if (tid == 0) bad |= offsets[0] != 0 || offsets[S] != n;
@@ -59,11 +51,12 @@ __global__ __launch_bounds__(kBlock) void route_remap_kernel(
     const int64_t* __restrict__ row_base, const uint32_t* __restrict__ placement,
     int64_t n, int U, int W, int self, int dest_bits,
     uint16_t* __restrict__ dest_out, uint32_t* __restrict__ g_out,
-    uint32_t* __restrict__ tile_hist /* [U][tiles] */, int64_t tiles,
-    RouteCounters* counters, int32_t* status)
+    uint32_t* __restrict__ tile_hist /* [U + 3][tiles]: buckets, then the three tiers */, int64_t tiles,
+    int32_t* status)
 {
     extern __shared__ uint32_t lds_hist[];            // [U]
     __shared__ int tile_tables[2];
+    __shared__ unsigned int wave_tiers[kWavesPerBlock][3];
     const int64_t tile = blockIdx.x;
     const int64_t base = tile * kRouteTile;
     for (int b = threadIdx.x; b < U; b += kBlock) lds_hist[b] = 0;
@@ -115,15 +108,20 @@ __global__ __launch_bounds__(kBlock) void route_remap_kernel(
         const uint64_t same = match_bits(dest, dest_bits, valid);
         if (valid && popc_below(same) == 0) atomicAdd(&lds_hist[dest], (uint32_t)__popcll(same));
     }
-    __syncthreads();
-    for (int b = threadIdx.x; b < U; b += kBlock) tile_hist[(int64_t)b * tiles + tile] = lds_hist[b];
-
-    // tier counters and fault bits: reduce over the wave, one atomic per wave
+    // tier counts travel as three more histogram rows (no global atomics: 3 hot addresses
+    // shared by every wave of the grid serialise in L2)
 #pragma unroll
     for (int k = 0; k < 3; ++k) {
         unsigned int v = tiers[k];
         for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off);
-        if (lane_id() == 0 && v != 0) atomicAdd(&counters->tier[k], (unsigned long long)v);
+        if (lane_id() == 0) wave_tiers[wave_id()][k] = v;
+    }
+    __syncthreads();
+    for (int b = threadIdx.x; b < U; b += kBlock) tile_hist[(int64_t)b * tiles + tile] = lds_hist[b];
+    if (threadIdx.x < 3) {
+        unsigned int v = 0;
+        for (int k = 0; k < kWavesPerBlock; ++k) v += wave_tiers[k][threadIdx.x];
+        tile_hist[(int64_t)(U + threadIdx.x) * tiles + tile] = v;
     }
     for (int off = 32; off > 0; off >>= 1) faults |= __shfl_down(faults, off);
     if (lane_id() == 0) report(status, faults);
@@ -237,7 +235,7 @@ __global__ __launch_bounds__(kBlock) void route_scatter_kernel(
 }
 
 __global__ __launch_bounds__(kBlock) void route_finalize_kernel(
-    const uint32_t* __restrict__ totals, int U, int64_t n, const RouteCounters* counters,
+    const uint32_t* __restrict__ totals /* [U + 3] */, int U, int64_t n,
     int64_t* __restrict__ bucket_offsets, int64_t* __restrict__ tier_counts)
 {
     if (threadIdx.x == 0) {
@@ -245,7 +243,7 @@ __global__ __launch_bounds__(kBlock) void route_finalize_kernel(
         for (int b = 0; b < U; ++b) { bucket_offsets[b] = run; run += (n > 0 ? totals[b] : 0u); }
         bucket_offsets[U] = run;
         if (tier_counts != nullptr)
-            for (int k = 0; k < 3; ++k) tier_counts[k] = n > 0 ? (int64_t)counters->tier[k] : 0;
+            for (int k = 0; k < 3; ++k) tier_counts[k] = n > 0 ? (int64_t)totals[U + k] : 0;
     }
 }
 
@@ -266,9 +264,8 @@ extern "C" fs_status fs_route_bucketize(
 
     const int64_t tiles = (n + kRouteTile - 1) / kRouteTile;
     Carver ws(workspace);
-    RouteCounters* counters = ws.take<RouteCounters>(1);
-    uint32_t* totals = ws.take<uint32_t>((size_t)U);
-    uint32_t* tile_hist = ws.take<uint32_t>((size_t)U * (size_t)tiles);
+    uint32_t* totals = ws.take<uint32_t>((size_t)U + 3);
+    uint32_t* tile_hist = ws.take<uint32_t>(((size_t)U + 3) * (size_t)tiles);
     uint32_t* g_tmp = ws.take<uint32_t>((size_t)n);
     uint16_t* dest_tmp = ws.take<uint16_t>((size_t)n);
     if (!workspace) { *workspace_bytes = ws.used; return FS_OK; }
@@ -281,18 +278,18 @@ extern "C" fs_status fs_route_bucketize(
     const int dest_bits = bits_for((uint64_t)(U - 1));
     const unsigned prep_grid = (unsigned)((S + kBlock - 1) / kBlock < 1024 ? (S + kBlock - 1) / kBlock : 1024);
     FS_LAUNCH("route_prepare", route_prepare_kernel, dim3(prep_grid), dim3(kBlock), s,
-              offsets, S, n, counters, dev_status);
+              offsets, S, n, dev_status);
     if (n > 0) {
         FS_LAUNCH_SMEM("route_remap", route_remap_kernel, dim3((unsigned)tiles), dim3(kBlock),
                        (size_t)U * sizeof(uint32_t), s,
                        ids, offsets, (int)T, (int64_t)B, row_base, placement, n, (int)U, (int)W, (int)self,
-                       dest_bits, dest_tmp, g_tmp, tile_hist, tiles, counters, dev_status);
-        FS_LAUNCH("route_scan", route_scan_kernel, dim3((unsigned)U), dim3(kBlock), s, tile_hist, tiles, totals);
+                       dest_bits, dest_tmp, g_tmp, tile_hist, tiles, dev_status);
+        FS_LAUNCH("route_scan", route_scan_kernel, dim3((unsigned)U + 3), dim3(kBlock), s, tile_hist, tiles, totals);
         FS_LAUNCH_SMEM("route_scatter", route_scatter_kernel, dim3((unsigned)tiles), dim3(kBlock),
                        (size_t)U * sizeof(uint32_t) + (size_t)kWavesPerBlock * U * sizeof(uint16_t), s,
                        dest_tmp, g_tmp, n, (int)U, dest_bits, tile_hist, tiles, totals, out_rows, out_pos);
     }
     FS_LAUNCH("route_finalize", route_finalize_kernel, dim3(1), dim3(kBlock), s,
-              totals, (int)U, n, counters, bucket_offsets, tier_counts);
+              totals, (int)U, n, bucket_offsets, tier_counts);
     return FS_OK;
 }
