@@ -197,6 +197,21 @@ def main():
         "input_gen_s": round(t_gen, 1),
     }
 
+    # ---------------------------------------------------------------- the box's plain-copy bandwidth, for context
+    copy_bytes = min(out.numel() * out.element_size(), grad_out.numel() * grad_out.element_size()) // 16 * 16
+    if copy_bytes > 0:
+        for _ in range(2):
+            fs.fs_util_copy(out, grad_out, copy_bytes)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            fs.fs_util_copy(out, grad_out, copy_bytes)
+        e1.record()
+        torch.cuda.synchronize()
+        copy_ms = e0.elapsed_time(e1) / 5
+        result["plain_copy"] = {"bytes_each_way": copy_bytes, "ms": round(copy_ms, 4),
+                                "GBps_read_plus_write": round(2 * copy_bytes / (copy_ms * 1e-3) / 1e9, 1)}
+
     # ---------------------------------------------------------------- CPU oracle on a bounded sample
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(args, cfg, ids, offsets, placement, weights, grad_out)
@@ -214,9 +229,11 @@ def cpu_baseline(args, cfg, ids, offsets, placement, weights, grad_out):
 
     B, E, D = cfg.B, cfg.E, cfg.D
     tables = args.cpu_tables
-    if tables <= 0:                                   # aim at a few million lookups
+    if tables <= 0:                                   # aim at ~8M lookups (about 5-10 s of one core)
         per_table = max(1, int(offsets[B].item()))
-        tables = max(1, min(cfg.T, int(2_000_000 // per_table) or 1))
+        tables = max(1, min(cfg.T, -(-8_000_000 // per_table)))
+        while tables > 1 and tables * E * cfg.row_bytes > 24e9:      # keep the host copy of the table modest
+            tables -= 1
     n_s = int(offsets[tables * B].item())
     ids_h = ids[:n_s].cpu().numpy()
     off_h = offsets[:tables * B + 1].cpu().numpy()

@@ -240,6 +240,14 @@ int32_t fs_version(void);
 int32_t fs_bwd_tile(void);
 
 /*
+ * Plain 128-bit copy kernel, dst[0..bytes) = src[0..bytes).  Not part of the method: the
+ * benchmark uses it as the measured copy bandwidth of the box and the profiles use it to
+ * scale the HBM byte counters (a launch of known traffic).  bytes must be a multiple of 16,
+ * both pointers 16-byte aligned (FS_ERR_ALIGN), bytes >= 0 (FS_ERR_SIZE).
+ */
+fs_status fs_util_copy(void* dst, const void* src, int64_t bytes, void* stream);
+
+/*
  * Opt-in per-kernel timing.  fs_prof_begin(max_records) makes every later
  * kernel launch of this library (on any stream) bracketed by a pair of HIP
  * events; fs_prof_end() synchronises those events, writes up to `cap` records

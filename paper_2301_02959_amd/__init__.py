@@ -14,7 +14,7 @@ from typing import List, Optional, Tuple
 import torch
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "libflexshard_hip.so")
+LIB_PATH = os.environ.get("FLEXSHARD_HIP_LIB", os.path.join(_PKG, "libflexshard_hip.so"))
 
 FS_F32, FS_F16, FS_BF16 = 0, 1, 2
 FS_DEV_BAD_ID, FS_DEV_BAD_OFFSETS, FS_DEV_BAD_PLACEMENT = 1, 2, 4
@@ -27,7 +27,7 @@ STATUS_NAMES = {0: "FS_OK", 1: "FS_ERR_NULL", 2: "FS_ERR_SIZE", 3: "FS_ERR_DTYPE
                 5: "FS_ERR_WORKSPACE", 6: "FS_ERR_CONFIG", 7: "FS_ERR_DEVICE"}
 
 EXPORTS = ["fs_route_bucketize", "fs_seq_gather_fwd", "fs_seq_grad_bwd", "fs_plan_replication",
-           "fs_version", "fs_bwd_tile", "fs_prof_begin", "fs_prof_end"]
+           "fs_util_copy", "fs_version", "fs_bwd_tile", "fs_prof_begin", "fs_prof_end"]
 
 _DTYPES = {torch.float32: FS_F32, torch.float16: FS_F16, torch.bfloat16: FS_BF16}
 
@@ -50,7 +50,7 @@ def lib() -> ctypes.CDLL:
                 "(hipcc, gfx950); this package has no other code path")
         _lib = ctypes.CDLL(LIB_PATH)
         for name in ("fs_route_bucketize", "fs_seq_gather_fwd", "fs_seq_grad_bwd", "fs_plan_replication",
-                     "fs_prof_begin"):
+                     "fs_prof_begin", "fs_util_copy"):
             getattr(_lib, name).restype = ctypes.c_int
         _lib.fs_version.restype = ctypes.c_int32
         _lib.fs_bwd_tile.restype = ctypes.c_int32
@@ -174,6 +174,12 @@ def fs_plan_replication(ids, offsets, T: int, B: int, row_base, n: int, R: int, 
     else:
         size = ctypes.c_size_t(workspace.numel())
     return _check("fs_plan_replication", call(_ptr(workspace), ctypes.byref(size)), raise_on_error)
+
+
+def fs_util_copy(dst, src, nbytes: Optional[int] = None, raise_on_error: bool = True) -> int:
+    nbytes = src.numel() * src.element_size() if nbytes is None else nbytes
+    code = lib().fs_util_copy(_ptr(dst), _ptr(src), ctypes.c_int64(nbytes), _stream())
+    return _check("fs_util_copy", code, raise_on_error)
 
 
 def fs_version() -> int:
