@@ -80,9 +80,6 @@ def main():
     tier_counts = torch.zeros(3, dtype=torch.int64, device=dev)
     status = torch.zeros(1, dtype=torch.int32, device=dev)
     out = torch.empty(n, D, dtype=cfg.torch_dtype, device=dev)
-    cap_unique = min(n, R)
-    uniq_rows = torch.zeros(cap_unique, dtype=torch.int64, device=dev)
-    row_grads = torch.empty(cap_unique, D, dtype=torch.float32, device=dev)
     num_unique = torch.zeros(1, dtype=torch.int64, device=dev)
     counts = torch.zeros(R, dtype=torch.int32, device=dev)
     budget_rows = max(1, int((cfg.f_global if cfg.f_global > 0 else 0.01) * R))
@@ -113,8 +110,19 @@ def main():
                                    ctypes.c_int64(row_bytes), z, z, z, z, ctypes.byref(size), z, z)
         assert rc == 0, rc
 
+    cap_unique = 0
     ws_bwd = ws_for(q_bwd)
     ws_plan = ws_for(q_plan)
+
+    # size row_grads to the batch: a first call with capacity 0 only counts the distinct rows
+    fs.fs_route_bucketize(ids, offsets, T, B, row_base, placement, n, U, W, self_b, bucket_offsets, out_rows,
+                          out_pos, tier_counts, status, workspace=ws_route)
+    fs.fs_seq_grad_bwd(grad_out, out_rows, out_pos, 0, n, R, args.variant, None, None, 0, num_unique, None,
+                       workspace=ws_bwd)
+    torch.cuda.synchronize()
+    cap_unique = int(num_unique.item())
+    uniq_rows = torch.zeros(max(cap_unique, 1), dtype=torch.int64, device=dev)
+    row_grads = torch.empty(max(cap_unique, 1), D, dtype=torch.float32, device=dev)
 
     def step():
         fs.fs_plan_replication(ids, offsets, T, B, row_base, n, R, counts, plan_flags, budget_rows * row_bytes,
