@@ -13,6 +13,8 @@
 //                     keys and positions are staged in LDS by coalesced loads and read back
 //                     as broadcasts; a run that starts in the chunk goes to row_grads, the
 //                     piece that continues a run from the previous chunk goes to carry[chunk]
+//   bwd_singletons    runs of one lookup (most runs: the cold tail) are skipped by the walk and
+//                     converted here, fully parallel
 //   bwd_fold          for every run that spills over a chunk end: row_grads += carry of
 //                     the following chunks, left to right
 // which is exactly the summation order stated in flexshard.h (chunk = FS_BWD_TILE).
@@ -26,7 +28,10 @@ namespace fs {
 
 constexpr int kChunk = FS_BWD_TILE;
 constexpr int kChunksPerBlock = 64;          // bwd_count_heads: chunks per block
-constexpr int kBwdUnroll = 8;
+#ifndef FS_BWD_UNROLL
+#define FS_BWD_UNROLL 8
+#endif
+constexpr int kBwdUnroll = FS_BWD_UNROLL;
 constexpr uint32_t kNoKey = 0xFFFFFFFFu;     // never a row: R < 2^32 - 1
 
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
@@ -100,28 +105,27 @@ __global__ __launch_bounds__(kBlock) void bwd_count_heads_kernel(
 }
 
 // One block: block_sum[0..blocks) -> exclusive prefix in place, block_sum[blocks] = total.
-__global__ __launch_bounds__(kBlock) void bwd_scan_blocks_kernel(
+constexpr int kScanBlock = 1024;
+
+__global__ __launch_bounds__(kScanBlock) void bwd_scan_blocks_kernel(
     uint32_t* __restrict__ block_sum, int64_t blocks, int64_t cap, int64_t* __restrict__ num_unique,
     int32_t* status)
 {
-    __shared__ uint32_t part[kBlock];
-    const int64_t per = (blocks + kBlock - 1) / kBlock;
-    const int64_t lo = (int64_t)threadIdx.x * per < blocks ? (int64_t)threadIdx.x * per : blocks;
-    const int64_t hi = lo + per < blocks ? lo + per : blocks;
-    uint32_t sum = 0;
-    for (int64_t k = lo; k < hi; ++k) sum += block_sum[k];
-    part[threadIdx.x] = sum;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        uint32_t run = 0;
-        for (int k = 0; k < kBlock; ++k) { const uint32_t v = part[k]; part[k] = run; run += v; }
-        block_sum[blocks] = run;
-        *num_unique = (int64_t)run;
-        if ((int64_t)run > cap) report(status, FS_DEV_UNIQUE_OVERFLOW);
+    __shared__ uint32_t wave_sums[16];
+    uint32_t carry = 0;                                          // coalesced rounds of 1024 entries
+    for (int64_t base = 0; base < blocks; base += kScanBlock) {
+        const int64_t k = base + threadIdx.x;
+        const uint32_t v = k < blocks ? block_sum[k] : 0u;
+        uint32_t total;
+        const uint32_t before = block_exclusive_scan(v, wave_sums, &total);
+        if (k < blocks) block_sum[k] = carry + before;
+        carry += total;
     }
-    __syncthreads();
-    uint32_t run = part[threadIdx.x];
-    for (int64_t k = lo; k < hi; ++k) { const uint32_t v = block_sum[k]; block_sum[k] = run; run += v; }
+    if (threadIdx.x == 0) {
+        block_sum[blocks] = carry;
+        *num_unique = (int64_t)carry;
+        if ((int64_t)carry > cap) report(status, FS_DEV_UNIQUE_OVERFLOW);
+    }
 }
 
 __device__ __forceinline__ uint32_t runs_before(const uint32_t* __restrict__ block_base,
@@ -172,6 +176,8 @@ struct Vec<FS_BF16> {
 // They are read back as LDS broadcasts, 8 lookups per batch, the next batch's 8 gradient
 // rows already in flight while the current batch is summed.
 constexpr uint32_t kEndBit = 0x80000000u;        // positions are < 2^31
+constexpr uint32_t kSkip = 0xFFFFFFFFu;          // a run of one lookup: bwd_singletons writes it (not a position + flag:
+                                                 // positions stop at 2^31 - 2)
 
 
 template <int LG, int DT>
@@ -205,11 +211,12 @@ __global__ __launch_bounds__(kBlock) void bwd_segreduce_kernel(
 
     {
         constexpr int PER = kChunk / LG;
-        uint32_t key[PER], next[PER], val[PER];
+        uint32_t key[PER], prev[PER], next[PER], val[PER];
 #pragma unroll
         for (int i = 0; i < PER; ++i) {                          // all loads first, then the LDS writes
             const int64_t k = k0 + i * LG + lig;
             key[i] = k < k1 ? keys[k] : kNoKey;
+            prev[i] = k > 0 ? keys[k - 1] : kNoKey;
             next[i] = k + 1 < m ? keys[k + 1] : kNoKey;
             val[i] = k < k1 ? vals[k] : 0u;                      // past the end: position 0, loaded but unused
         }
@@ -217,8 +224,9 @@ __global__ __launch_bounds__(kBlock) void bwd_segreduce_kernel(
         for (int i = 0; i < PER; ++i) {
             const int e = i * LG + lig;
             const bool end = k0 + e + 1 >= k1 || next[i] != key[i];
+            const bool single = k0 + e < k1 && prev[i] != key[i] && next[i] != key[i];
             s_key[gi][e] = key[i];
-            s_val[gi][e] = val[i] | (end ? kEndBit : 0u);
+            s_val[gi][e] = single ? kSkip : (val[i] | (end ? kEndBit : 0u));
             if (e == kChunk - 1) s_key[gi][kChunk] = next[i];
         }
         if (lig < kPad) s_val[gi][kChunk + lig] = 0u;
@@ -237,11 +245,13 @@ __global__ __launch_bounds__(kBlock) void bwd_segreduce_kernel(
 #define FS_ISSUE(X, PV, E0)                                                                  \
     _Pragma("unroll") for (int j = 0; j < U8; ++j) {                                         \
         PV[j] = my_val[(E0) + j];                                                            \
-        X[j] = load_stream(my_grad + (int64_t)(PV[j] & ~kEndBit) * units);                   \
+        X[j] = load_stream(my_grad + (int64_t)(PV[j] == kSkip ? 0u : PV[j] & ~kEndBit) * units); \
     }
 #define FS_CONSUME(X, PV, E0)                                                                \
     _Pragma("unroll") for (int j = 0; j < U8; ++j) {                                         \
-        if ((E0) + j < cnt) {                                                                \
+        if ((E0) + j < cnt && PV[j] == kSkip) {                                              \
+            ++u;                       /* a run of one: counted here, written elsewhere */   \
+        } else if ((E0) + j < cnt) {                                                         \
             float f[N];                                                                      \
             Vec<DT>::load(X[j], f);                                                          \
             if (fresh) {                                                                     \
@@ -317,6 +327,90 @@ __global__ __launch_bounds__(kBlock) void bwd_segreduce_kernel(
     }
 #undef FS_ISSUE
 #undef FS_CONSUME
+}
+
+// Runs of one lookup need no sum: row_grads[u] = f32(grad_out[pos]).  They are most of the runs
+// (the cold tail of the popularity distribution) and a store in the sequential walk above stalls
+// the wave's later loads (loads and stores share one in-order counter), so this kernel converts
+// them instead, fully parallel: a wave takes one chunk, finds its singletons and their run
+// indices with ballots, lists them in LDS and moves 64/LG rows per instruction, 8 in flight.
+template <int LG, int DT>
+__global__ __launch_bounds__(kBlock) void bwd_singletons_kernel(
+    const u32x4* __restrict__ grad, int units, int D,
+    const uint32_t* __restrict__ keys, const uint32_t* __restrict__ vals, int64_t m, int64_t chunks,
+    const uint32_t* __restrict__ block_base, const uint32_t* __restrict__ chunk_local,
+    int64_t* __restrict__ uniq_rows, float* __restrict__ row_grads, int64_t cap)
+{
+    constexpr int N = Vec<DT>::N;
+    constexpr int RPI = kWave / LG;
+    constexpr int UNR = 8;
+    __shared__ uint32_t s_pos[kWavesPerBlock][kChunk];
+    __shared__ uint32_t s_run[kWavesPerBlock][kChunk];
+    __shared__ uint32_t s_key[kWavesPerBlock][kChunk];
+    const int w = wave_id();
+    const int lane = lane_id();
+    const int64_t chunk = (int64_t)blockIdx.x * kWavesPerBlock + w;
+    if (chunk >= chunks) return;                                 // wave-uniform; no block barrier below
+    const int64_t k0 = chunk * kChunk;
+    const int64_t k1 = k0 + kChunk < m ? k0 + kChunk : m;
+    const uint32_t first_run = runs_before(block_base, chunk_local, chunk, chunks);
+
+    uint32_t heads_before = 0, singles = 0;
+#pragma unroll
+    for (int q = 0; q < kChunk / kWave; ++q) {
+        const int64_t k = k0 + q * kWave + lane;
+        const bool valid = k < k1;
+        const uint32_t key = valid ? keys[k] : kNoKey;
+        const uint32_t prev = (valid && k > 0) ? keys[k - 1] : kNoKey;
+        const uint32_t next = (valid && k + 1 < m) ? keys[k + 1] : kNoKey;
+        const bool head = valid && key != prev;
+        const bool single = head && key != next;
+        const uint64_t hb = ballot(head);
+        const uint64_t sb = ballot(single);
+        if (single) {
+            const uint32_t at = singles + (uint32_t)popc_below(sb);
+            s_pos[w][at] = vals[k];
+            s_run[w][at] = first_run + heads_before + (uint32_t)popc_below(hb);
+            s_key[w][at] = key;
+        }
+        heads_before += (uint32_t)__popcll(hb);
+        singles += (uint32_t)__popcll(sb);
+    }
+    if (singles == 0) return;                                    // wave-uniform
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+    const int g = lane / LG;
+    const int lig = lane % LG;
+    const int c = blockIdx.y * LG + lig;
+    const bool lane_on = c < units;
+    const int cc = lane_on ? c : 0;
+    const bool all_fit = (int64_t)first_run + heads_before <= cap;
+    for (uint32_t s = 0; s < singles; s += UNR * RPI) {
+        u32x4 x[UNR];
+        uint32_t run[UNR];
+        uint32_t at[UNR];
+#pragma unroll
+        for (int j = 0; j < UNR; ++j) {                          // past the end: the last singleton again (same bytes
+            const uint32_t want = s + j * RPI + g;               // to the same place), so nothing is predicated
+            at[j] = want < singles ? want : singles - 1;
+            run[j] = s_run[w][at[j]];
+            x[j] = load_stream(grad + (int64_t)s_pos[w][at[j]] * units + cc);
+        }
+#pragma unroll
+        for (int j = 0; j < UNR; ++j) {
+            if (lane_on && (all_fit || (int64_t)run[j] < cap)) {
+                float f[N];
+                Vec<DT>::load(x[j], f);
+                float* dst = row_grads + (int64_t)run[j] * D + cc * N;
+#pragma unroll
+                for (int q = 0; q < N; q += 4)
+                    store_stream(reinterpret_cast<f32x4*>(dst + q), f32x4{f[q], f[q + 1], f[q + 2], f[q + 3]});
+                if (c == 0) uniq_rows[run[j]] = (int64_t)s_key[w][at[j]];
+            }
+        }
+    }
 }
 
 // Does a run that starts in `chunk` go on into chunk + 1?  Returns its key through *key.
@@ -408,6 +502,26 @@ static fs_status launch_segreduce(fs_dtype dtype, const void* grad, int units, i
     return FS_OK;
 }
 
+template <int LG>
+static fs_status launch_singletons(fs_dtype dtype, const void* grad, int units, int D, const uint32_t* keys,
+                                   const uint32_t* vals, int64_t m, int64_t chunks, const uint32_t* block_base,
+                                   const uint32_t* chunk_local, int64_t* uniq_rows, float* row_grads, int64_t cap,
+                                   hipStream_t stream)
+{
+    const dim3 grid((unsigned)((chunks + kWavesPerBlock - 1) / kWavesPerBlock), (unsigned)((units + LG - 1) / LG));
+    const u32x4* g = static_cast<const u32x4*>(grad);
+    if (dtype == FS_F32)
+        FS_LAUNCH("bwd_singletons", (bwd_singletons_kernel<LG, FS_F32>), grid, dim3(kBlock), stream, g, units, D, keys,
+                  vals, m, chunks, block_base, chunk_local, uniq_rows, row_grads, cap);
+    else if (dtype == FS_F16)
+        FS_LAUNCH("bwd_singletons", (bwd_singletons_kernel<LG, FS_F16>), grid, dim3(kBlock), stream, g, units, D, keys,
+                  vals, m, chunks, block_base, chunk_local, uniq_rows, row_grads, cap);
+    else
+        FS_LAUNCH("bwd_singletons", (bwd_singletons_kernel<LG, FS_BF16>), grid, dim3(kBlock), stream, g, units, D, keys,
+                  vals, m, chunks, block_base, chunk_local, uniq_rows, row_grads, cap);
+    return FS_OK;
+}
+
 }  // namespace fs
 
 extern "C" fs_status fs_seq_grad_bwd(
@@ -463,7 +577,7 @@ extern "C" fs_status fs_seq_grad_bwd(
     if (rc != FS_OK) return rc;
     FS_LAUNCH("bwd_count_heads", bwd_count_heads_kernel, dim3((unsigned)blocks), dim3(kBlock), s,
               keys, vals, m, chunks, chunk_local, block_base, dev_status);
-    FS_LAUNCH("bwd_scan_blocks", bwd_scan_blocks_kernel, dim3(1), dim3(kBlock), s,
+    FS_LAUNCH("bwd_scan_blocks", bwd_scan_blocks_kernel, dim3(1), dim3(kScanBlock), s,
               block_base, blocks, cap_unique, num_unique, dev_status);
     const unsigned wave_grid = (unsigned)((chunks + kWavesPerBlock - 1) / kWavesPerBlock);
     if (variant == 1)
@@ -476,6 +590,18 @@ extern "C" fs_status fs_seq_grad_bwd(
     else if (units <= 32) FS_SEG(32);
     else FS_SEG(64);
 #undef FS_SEG
+    if (rc != FS_OK) return rc;
+#define FS_SINGLE(LG)                                                                                           \
+    rc = launch_singletons<LG>(dtype, grad_out, units, (int)D, keys, vals, m, chunks, block_base, chunk_local,    \
+                               uniq_rows, row_grads, cap_unique, s)
+    if (units <= 1) FS_SINGLE(1);
+    else if (units <= 2) FS_SINGLE(2);
+    else if (units <= 4) FS_SINGLE(4);
+    else if (units <= 8) FS_SINGLE(8);
+    else if (units <= 16) FS_SINGLE(16);
+    else if (units <= 32) FS_SINGLE(32);
+    else FS_SINGLE(64);
+#undef FS_SINGLE
     if (rc != FS_OK) return rc;
     if (variant == 0)
         FS_LAUNCH("bwd_fold", bwd_fold_kernel, dim3(wave_grid), dim3(kBlock), s,

@@ -102,6 +102,33 @@ __device__ __forceinline__ T load_stream(const T* p) { return __builtin_nontempo
 template <typename T>
 __device__ __forceinline__ void store_stream(T* p, T v) { __builtin_nontemporal_store(v, p); }
 
+// Exclusive prefix of `v` over the threads of the block (any multiple of 64 threads up to
+// 1024); *total receives the block sum.  `wave_sums` is LDS scratch of 16 words.  Contains
+// block barriers: every thread of the block must call it.
+__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* wave_sums, uint32_t* total)
+{
+    const int lane = lane_id();
+    const int w = wave_id();
+    const int waves = (int)(blockDim.x >> 6);
+    uint32_t incl = v;
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+        const uint32_t up = __shfl_up(incl, off);
+        if (lane >= off) incl += up;
+    }
+    __syncthreads();                       // wave_sums may still be read from a previous call
+    if (lane == kWave - 1) wave_sums[w] = incl;
+    __syncthreads();
+    uint32_t before = 0, all = 0;
+    for (int k = 0; k < waves; ++k) {
+        const uint32_t s = wave_sums[k];
+        if (k < w) before += s;
+        all += s;
+    }
+    *total = all;
+    return before + incl - v;
+}
+
 __device__ __forceinline__ void report(int32_t* status, int32_t bits)
 {
     if (status != nullptr && bits != 0) atomicOr(status, bits);

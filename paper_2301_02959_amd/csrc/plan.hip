@@ -49,7 +49,9 @@ __global__ __launch_bounds__(kBlock) void plan_check_offsets_kernel(
     if (ballot(bad) != 0 && lane_id() == 0) { report(status, FS_DEV_BAD_OFFSETS); atomicExch(ok_flag, 0); }
 }
 
-__global__ __launch_bounds__(kBlock) void plan_histogram_kernel(
+constexpr int kHistBlock = 1024;          // 16 waves per span: a span per 256 threads leaves the chip idle
+
+__global__ __launch_bounds__(kHistBlock) void plan_histogram_kernel(
     const int64_t* __restrict__ ids, const int64_t* __restrict__ offsets, int T, int64_t B,
     const int64_t* __restrict__ row_base, int64_t n, uint32_t* __restrict__ counts,
     const int32_t* __restrict__ ok_flag, int32_t* status)
@@ -60,7 +62,7 @@ __global__ __launch_bounds__(kBlock) void plan_histogram_kernel(
     if (*ok_flag == 0) return;                 // bad offsets: count nothing
     const int64_t base = (int64_t)blockIdx.x * kHistSpan;
     const int64_t end = base + kHistSpan < n ? base + kHistSpan : n;
-    for (int s = threadIdx.x; s < kHistSlots; s += kBlock) { tags[s] = 0; hits[s] = 0; }
+    for (int s = threadIdx.x; s < kHistSlots; s += kHistBlock) { tags[s] = 0; hits[s] = 0; }
     if (threadIdx.x == 0) {
         span_tables[0] = plan_table_of(offsets, T, B, base);
         span_tables[1] = plan_table_of(offsets, T, B, end - 1);
@@ -69,7 +71,7 @@ __global__ __launch_bounds__(kBlock) void plan_histogram_kernel(
     const int t_lo = span_tables[0];
     const int t_hi = span_tables[1];
     int32_t faults = 0;
-    for (int64_t i = base + threadIdx.x; i < end; i += kBlock) {
+    for (int64_t i = base + threadIdx.x; i < end; i += kHistBlock) {
         int t = t_lo;
         while (t < t_hi && offsets[(int64_t)(t + 1) * B] <= i) ++t;
         const int64_t first = row_base[t];
@@ -84,7 +86,7 @@ __global__ __launch_bounds__(kBlock) void plan_histogram_kernel(
         else add_saturating(counts + g, 1u, &faults);
     }
     __syncthreads();
-    for (int s = threadIdx.x; s < kHistSlots; s += kBlock)
+    for (int s = threadIdx.x; s < kHistSlots; s += kHistBlock)
         if (tags[s] != 0 && hits[s] != 0) add_saturating(counts + (tags[s] - 1u), hits[s], &faults);
     if (ballot(faults != 0) != 0) {
         for (int off = 32; off > 0; off >>= 1) faults |= __shfl_down(faults, off);
@@ -114,25 +116,22 @@ __global__ __launch_bounds__(kBlock) void plan_mark_count_kernel(
     }
 }
 
-__global__ __launch_bounds__(kBlock) void plan_scan_kernel(uint32_t* __restrict__ tile_count, int64_t tiles,
-                                                           int64_t* __restrict__ num_candidates)
+constexpr int kScanBlock = 1024;
+
+__global__ __launch_bounds__(kScanBlock) void plan_scan_kernel(uint32_t* __restrict__ tile_count, int64_t tiles,
+                                                               int64_t* __restrict__ num_candidates)
 {
-    __shared__ uint32_t part[kBlock];
-    const int64_t per = (tiles + kBlock - 1) / kBlock;
-    const int64_t lo = (int64_t)threadIdx.x * per < tiles ? (int64_t)threadIdx.x * per : tiles;
-    const int64_t hi = lo + per < tiles ? lo + per : tiles;
-    uint32_t sum = 0;
-    for (int64_t k = lo; k < hi; ++k) sum += tile_count[k];
-    part[threadIdx.x] = sum;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        uint32_t run = 0;
-        for (int k = 0; k < kBlock; ++k) { const uint32_t v = part[k]; part[k] = run; run += v; }
-        *num_candidates = (int64_t)run;
+    __shared__ uint32_t wave_sums[16];
+    uint32_t carry = 0;                                          // coalesced rounds of 1024 tiles
+    for (int64_t base = 0; base < tiles; base += kScanBlock) {
+        const int64_t k = base + threadIdx.x;
+        const uint32_t v = k < tiles ? tile_count[k] : 0u;
+        uint32_t total;
+        const uint32_t before = block_exclusive_scan(v, wave_sums, &total);
+        if (k < tiles) tile_count[k] = carry + before;
+        carry += total;
     }
-    __syncthreads();
-    uint32_t run = part[threadIdx.x];
-    for (int64_t k = lo; k < hi; ++k) { const uint32_t v = tile_count[k]; tile_count[k] = run; run += v; }
+    if (threadIdx.x == 0) *num_candidates = (int64_t)carry;
 }
 
 __global__ __launch_bounds__(kBlock) void plan_compact_kernel(
@@ -239,7 +238,7 @@ extern "C" fs_status fs_plan_replication(
                   offsets, S, n, ok_flag, dev_status);
         if (n > 0) {
             const int64_t blocks = (n + kHistSpan - 1) / kHistSpan;
-            FS_LAUNCH("plan_histogram", plan_histogram_kernel, dim3((unsigned)blocks), dim3(kBlock), s,
+            FS_LAUNCH("plan_histogram", plan_histogram_kernel, dim3((unsigned)blocks), dim3(kHistBlock), s,
                       ids, offsets, (int)T, (int64_t)B, row_base, n, counts, ok_flag, dev_status);
         }
     }
@@ -247,7 +246,7 @@ extern "C" fs_status fs_plan_replication(
         const int allow_zero = (flags & FS_PLAN_ALLOW_ZERO) ? 1 : 0;
         FS_LAUNCH("plan_mark_count", plan_mark_count_kernel, dim3((unsigned)sel_tiles), dim3(kBlock), s,
                   counts, R, allow_zero, tile_count);
-        FS_LAUNCH("plan_scan", plan_scan_kernel, dim3(1), dim3(kBlock), s, tile_count, sel_tiles, num_cand);
+        FS_LAUNCH("plan_scan", plan_scan_kernel, dim3(1), dim3(kScanBlock), s, tile_count, sel_tiles, num_cand);
         FS_LAUNCH("plan_compact", plan_compact_kernel, dim3((unsigned)sel_tiles), dim3(kBlock), s,
                   counts, R, allow_zero, tile_count, keys_a, vals_a);
         uint32_t* keys = nullptr;
