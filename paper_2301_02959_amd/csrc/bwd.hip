@@ -1,8 +1,7 @@
 // fs_seq_grad_bwd: row_grads[u(r), :] = sum of f32(grad_out[pos[j], :]) over the lookups of row r.
 //
 // Sort-by-row segmented reduction:
-//   bwd_make_keys     (row, pos) -> (u32 key, u32 value), validated
-//   radix sort        stable by row; lookups of one row keep their j order, which is
+//   radix sort        stable by row, the first pass reading and validating (row, pos) itself; lookups of one row keep their j order, which is
 //                     ascending pos for any fs_route_bucketize output
 //   bwd_count_heads   per 256-lookup chunk of the sorted order: number of runs that
 //                     start in it, with a block-local exclusive prefix
@@ -35,23 +34,6 @@ constexpr int kBwdUnroll = FS_BWD_UNROLL;
 constexpr uint32_t kNoKey = 0xFFFFFFFFu;     // never a row: R < 2^32 - 1
 
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
-
-__global__ __launch_bounds__(kBlock) void bwd_make_keys_kernel(
-    const int64_t* __restrict__ rows, const int32_t* __restrict__ pos, int64_t m, int64_t R, int64_t n,
-    uint32_t* __restrict__ keys, uint32_t* __restrict__ vals, int32_t* status)
-{
-    const int64_t q = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    bool bad = false;
-    if (q < m) {
-        int64_t r = load_stream(rows + q);
-        int64_t p = load_stream(pos + q);
-        if (r < 0 || r >= R) { r = 0; bad = true; }
-        if (p < 0 || p >= n) { p = 0; bad = true; }
-        keys[q] = (uint32_t)r;
-        vals[q] = (uint32_t)p;
-    }
-    if (ballot(bad) != 0 && lane_id() == 0) report(status, FS_DEV_BAD_ID);
-}
 
 // Block b covers chunks [64 b, 64 b + 64): wave w walks 16 of them.  chunk_local[c] = runs that
 // start in the block's chunks before c; block_sum[b] = runs that start in the block.
@@ -447,16 +429,17 @@ __global__ __launch_bounds__(kBlock) void bwd_fold_kernel(
         if (keys[mid] == key) lo = mid + 1; else hi = mid;
     }
     const int64_t last_chunk = (lo - 1) / kChunk;
+    constexpr int kAhead = 32;                   // carries in flight: the longest run's chain is latency-bound
     for (int col = lane_id() * 4; col < D; col += kWave * 4) {
         f32x4 acc = *reinterpret_cast<const f32x4*>(row_grads + u * D + col);
         int64_t cc = chunk + 1;
-        for (; cc + kBwdUnroll <= last_chunk + 1; cc += kBwdUnroll) {
-            f32x4 part[kBwdUnroll];
+        for (; cc + kAhead <= last_chunk + 1; cc += kAhead) {
+            f32x4 part[kAhead];
 #pragma unroll
-            for (int j = 0; j < kBwdUnroll; ++j)
+            for (int j = 0; j < kAhead; ++j)
                 part[j] = *reinterpret_cast<const f32x4*>(carry + (cc + j) * D + col);
 #pragma unroll
-            for (int j = 0; j < kBwdUnroll; ++j) acc = acc + part[j];
+            for (int j = 0; j < kAhead; ++j) acc = acc + part[j];
         }
         for (; cc <= last_chunk; ++cc) acc = acc + *reinterpret_cast<const f32x4*>(carry + cc * D + col);
         *reinterpret_cast<f32x4*>(row_grads + u * D + col) = acc;
@@ -568,12 +551,16 @@ extern "C" fs_status fs_seq_grad_bwd(
     if (cap_unique > 0 && (!uniq_rows || !row_grads)) return FS_ERR_NULL;
     if ((reinterpret_cast<uintptr_t>(grad_out) | reinterpret_cast<uintptr_t>(row_grads)) & 15) return FS_ERR_ALIGN;
 
-    FS_LAUNCH("bwd_make_keys", bwd_make_keys_kernel, dim3((unsigned)((m + kBlock - 1) / kBlock)), dim3(kBlock), s,
-              rows + j0, pos + j0, m, R, n, keys_a, vals_a, dev_status);
     uint32_t* keys = nullptr;
     uint32_t* vals = nullptr;
+    SortSource source;                           // the sort's first pass reads (row, pos) itself
+    source.rows = rows + j0;
+    source.pos = pos + j0;
+    source.R = R;
+    source.n = n;
+    source.status = dev_status;
     fs_status rc = radix_sort_pairs(keys_a, vals_a, keys_b, vals_b, m, nullptr, bits_for((uint64_t)(R - 1)),
-                                    sort_scratch, s, &keys, &vals);
+                                    sort_scratch, s, &keys, &vals, source);
     if (rc != FS_OK) return rc;
     FS_LAUNCH("bwd_count_heads", bwd_count_heads_kernel, dim3((unsigned)blocks), dim3(kBlock), s,
               keys, vals, m, chunks, chunk_local, block_base, dev_status);

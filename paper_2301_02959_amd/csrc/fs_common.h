@@ -89,6 +89,28 @@ __device__ __forceinline__ uint64_t match_bits(uint32_t key, int nbits, bool val
     return m;
 }
 
+// The same with the bit count known at compile time: the loop unrolls, the shifts fold.
+template <int NBITS>
+__device__ __forceinline__ uint64_t match_bits_n(uint32_t key, bool valid)
+{
+    uint64_t m = ballot(valid);
+#pragma unroll
+    for (int b = 0; b < NBITS; ++b) {
+        const bool bit = (key >> b) & 1u;
+        const uint64_t v = ballot(bit);
+        m &= bit ? v : ~v;
+    }
+    return m;
+}
+
+#define FS_DISPATCH_BITS(nbits, CALL)                                                   \
+    switch (nbits) {                                                                    \
+        case 1: CALL(1); break;  case 2: CALL(2); break;  case 3: CALL(3); break;       \
+        case 4: CALL(4); break;  case 5: CALL(5); break;  case 6: CALL(6); break;       \
+        case 7: CALL(7); break;  case 8: CALL(8); break;  case 9: CALL(9); break;       \
+        default: CALL(10); break;                                                       \
+    }
+
 // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Map
 // the hardware block id to a logical tile so that every XCD walks one
 // contiguous range of tiles.  The grid must have kXcds * tiles_per_xcd blocks.

@@ -4,8 +4,8 @@
 //             a few rows most of the time, so a block keeps a 4096-entry direct-mapped cache of
 //             (row, count) in LDS (first row to claim a slot keeps it); only misses and the final
 //             flush reach the global counters, as saturating 32-bit atomic adds.
-// SELECT      plan_mark_count / plan_scan / plan_compact: stable compaction of the candidate rows
-//             (count > 0, or all) in ascending row order into (key = ~count, value = row);
+// SELECT      plan_mark / plan_scan / plan_move: stable compaction of the candidate rows (count > 0,
+//             or all) in ascending row order into (key = ~count, value = row), reading counts once;
 //             a stable radix sort by key then yields (count desc, row asc); plan_emit writes the
 //             first k = min(budget / bytes_per_row, #candidates) rows, k, and the tier-0 tags.
 // The candidate count lives in device memory; the sort kernels read it there.
@@ -71,12 +71,11 @@ __global__ __launch_bounds__(kHistBlock) void plan_histogram_kernel(
     const int t_lo = span_tables[0];
     const int t_hi = span_tables[1];
     int32_t faults = 0;
-    for (int64_t i = base + threadIdx.x; i < end; i += kHistBlock) {
+    auto count_one = [&](int64_t i, int64_t id) {
         int t = t_lo;
         while (t < t_hi && offsets[(int64_t)(t + 1) * B] <= i) ++t;
         const int64_t first = row_base[t];
         const int64_t rows_t = row_base[t + 1] - first;
-        int64_t id = load_stream(ids + i);
         if (id < 0 || id >= rows_t) { faults |= FS_DEV_BAD_ID; id = 0; }
         const uint32_t g = (uint32_t)(first + id);
         const uint32_t slot = (g * 2654435761u) >> (32 - kHistSlotBits);
@@ -84,7 +83,17 @@ __global__ __launch_bounds__(kHistBlock) void plan_histogram_kernel(
         if (tag == 0) tag = atomicCAS(&tags[slot], 0u, g + 1u);
         if (tag == 0 || tag == g + 1u) atomicAdd(&hits[slot], 1u);
         else add_saturating(counts + g, 1u, &faults);
+    };
+    constexpr int kAhead = 8;                                    // ids in flight per thread
+    int64_t i = base + threadIdx.x;
+    for (; i + (int64_t)(kAhead - 1) * kHistBlock < end; i += (int64_t)kAhead * kHistBlock) {
+        int64_t id[kAhead];
+#pragma unroll
+        for (int q = 0; q < kAhead; ++q) id[q] = load_stream(ids + i + (int64_t)q * kHistBlock);
+#pragma unroll
+        for (int q = 0; q < kAhead; ++q) count_one(i + (int64_t)q * kHistBlock, id[q]);
     }
+    for (; i < end; i += kHistBlock) count_one(i, load_stream(ids + i));
     __syncthreads();
     for (int s = threadIdx.x; s < kHistSlots; s += kHistBlock)
         if (tags[s] != 0 && hits[s] != 0) add_saturating(counts + (tags[s] - 1u), hits[s], &faults);
@@ -95,24 +104,51 @@ __global__ __launch_bounds__(kHistBlock) void plan_histogram_kernel(
 }
 
 // ---- selection --------------------------------------------------------------
-__global__ __launch_bounds__(kBlock) void plan_mark_count_kernel(
-    const uint32_t* __restrict__ counts, int64_t R, int allow_zero, uint32_t* __restrict__ tile_count)
+// Reads counts once: the candidates of a 2048-row tile are packed, in row order, at the tile's
+// own place in a staging buffer (keys/vals at [tile * 2048 + i]) and counted.
+__global__ __launch_bounds__(kBlock) void plan_mark_kernel(
+    const uint32_t* __restrict__ counts, int64_t R, int allow_zero, uint32_t* __restrict__ tile_count,
+    uint32_t* __restrict__ stage_keys, uint32_t* __restrict__ stage_vals)
 {
     __shared__ uint32_t wave_sum[kWavesPerBlock];
-    const int64_t base = (int64_t)blockIdx.x * kSelTile;
-    uint32_t mine = 0;
+    constexpr int kItems = kSelTile / kBlock;
+    constexpr int kSpan = kWave * kItems;                 // consecutive rows per wave
+    const int w = wave_id();
+    const int lane = lane_id();
+    const int64_t tile_base = (int64_t)blockIdx.x * kSelTile;
+    const int64_t base = tile_base + (int64_t)w * kSpan;
+    uint32_t cnt[kItems];
+    uint32_t before[kItems];
+    bool cand[kItems];
+    uint32_t total = 0;
 #pragma unroll
-    for (int it = 0; it < kSelTile / kBlock; ++it) {
-        const int64_t g = base + (int64_t)it * kBlock + threadIdx.x;
-        const bool cand = g < R && (allow_zero || counts[g] != 0);
-        mine += (uint32_t)__popcll(ballot(cand));     // same value in every lane of the wave
+    for (int it = 0; it < kItems; ++it) {
+        const int64_t g = base + it * kWave + lane;
+        cnt[it] = g < R ? counts[g] : 0u;
     }
-    if (lane_id() == 0) wave_sum[wave_id()] = mine;
+#pragma unroll
+    for (int it = 0; it < kItems; ++it) {
+        const int64_t g = base + it * kWave + lane;
+        cand[it] = g < R && (allow_zero || cnt[it] != 0);
+        const uint64_t b = ballot(cand[it]);
+        before[it] = total + (uint32_t)popc_below(b);
+        total += (uint32_t)__popcll(b);
+    }
+    if (lane == 0) wave_sum[w] = total;
     __syncthreads();
-    if (threadIdx.x == 0) {
-        uint32_t s = 0;
-        for (int k = 0; k < kWavesPerBlock; ++k) s += wave_sum[k];
-        tile_count[blockIdx.x] = s;
+    uint32_t off = 0, all = 0;
+    for (int k = 0; k < kWavesPerBlock; ++k) {
+        if (k < w) off += wave_sum[k];
+        all += wave_sum[k];
+    }
+    if (threadIdx.x == 0) tile_count[blockIdx.x] = all;
+#pragma unroll
+    for (int it = 0; it < kItems; ++it) {
+        if (cand[it]) {
+            const int64_t g = base + it * kWave + lane;
+            stage_keys[tile_base + off + before[it]] = ~cnt[it];
+            stage_vals[tile_base + off + before[it]] = (uint32_t)g;
+        }
     }
 }
 
@@ -122,52 +158,39 @@ __global__ __launch_bounds__(kScanBlock) void plan_scan_kernel(uint32_t* __restr
                                                                int64_t* __restrict__ num_candidates)
 {
     __shared__ uint32_t wave_sums[16];
-    uint32_t carry = 0;                                          // coalesced rounds of 1024 tiles
-    for (int64_t base = 0; base < tiles; base += kScanBlock) {
-        const int64_t k = base + threadIdx.x;
-        const uint32_t v = k < tiles ? tile_count[k] : 0u;
-        uint32_t total;
-        const uint32_t before = block_exclusive_scan(v, wave_sums, &total);
-        if (k < tiles) tile_count[k] = carry + before;
-        carry += total;
+    uint32_t carry = 0;                                          // coalesced rounds of 1024 tiles, 8 rounds of loads in flight
+    for (int64_t base = 0; base < tiles; base += 8 * kScanBlock) {
+        uint32_t v[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const int64_t k = base + (int64_t)q * kScanBlock + threadIdx.x;
+            v[q] = k < tiles ? tile_count[k] : 0u;
+        }
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const int64_t k = base + (int64_t)q * kScanBlock + threadIdx.x;
+            uint32_t total;
+            const uint32_t before = block_exclusive_scan(v[q], wave_sums, &total);
+            if (k < tiles) tile_count[k] = carry + before;
+            carry += total;
+        }
     }
     if (threadIdx.x == 0) *num_candidates = (int64_t)carry;
 }
 
-__global__ __launch_bounds__(kBlock) void plan_compact_kernel(
-    const uint32_t* __restrict__ counts, int64_t R, int allow_zero, const uint32_t* __restrict__ tile_base,
+// Moves each tile's packed candidates to their final place (tile_base = scanned tile counts).
+__global__ __launch_bounds__(kBlock) void plan_move_kernel(
+    const uint32_t* __restrict__ tile_base, int64_t tiles, const int64_t* __restrict__ num_candidates,
+    const uint32_t* __restrict__ stage_keys, const uint32_t* __restrict__ stage_vals,
     uint32_t* __restrict__ keys, uint32_t* __restrict__ vals)
 {
-    __shared__ uint32_t wave_sum[kWavesPerBlock];
-    constexpr int kItems = kSelTile / kBlock;
-    constexpr int kSpan = kWave * kItems;                 // consecutive rows per wave
-    const int w = wave_id();
-    const int lane = lane_id();
-    const int64_t base = (int64_t)blockIdx.x * kSelTile + (int64_t)w * kSpan;
-    uint32_t cnt[kItems];
-    uint32_t before[kItems];
-    bool cand[kItems];
-    uint32_t total = 0;
-#pragma unroll
-    for (int it = 0; it < kItems; ++it) {
-        const int64_t g = base + it * kWave + lane;
-        cnt[it] = g < R ? counts[g] : 0u;
-        cand[it] = g < R && (allow_zero || cnt[it] != 0);
-        const uint64_t b = ballot(cand[it]);
-        before[it] = total + (uint32_t)popc_below(b);
-        total += (uint32_t)__popcll(b);
-    }
-    if (lane == 0) wave_sum[w] = total;
-    __syncthreads();
-    uint32_t off = tile_base[blockIdx.x];
-    for (int k = 0; k < w; ++k) off += wave_sum[k];
-#pragma unroll
-    for (int it = 0; it < kItems; ++it) {
-        if (cand[it]) {
-            const int64_t g = base + it * kWave + lane;
-            keys[off + before[it]] = ~cnt[it];
-            vals[off + before[it]] = (uint32_t)g;
-        }
+    const int64_t tile = blockIdx.x;
+    const uint32_t first = tile_base[tile];
+    const uint32_t next = tile + 1 < tiles ? tile_base[tile + 1] : (uint32_t)*num_candidates;
+    const int64_t from = tile * kSelTile;
+    for (uint32_t i = threadIdx.x; i < next - first; i += kBlock) {
+        keys[first + i] = stage_keys[from + i];
+        vals[first + i] = stage_vals[from + i];
     }
 }
 
@@ -244,11 +267,11 @@ extern "C" fs_status fs_plan_replication(
     }
     if (sel) {
         const int allow_zero = (flags & FS_PLAN_ALLOW_ZERO) ? 1 : 0;
-        FS_LAUNCH("plan_mark_count", plan_mark_count_kernel, dim3((unsigned)sel_tiles), dim3(kBlock), s,
-                  counts, R, allow_zero, tile_count);
+        FS_LAUNCH("plan_mark", plan_mark_kernel, dim3((unsigned)sel_tiles), dim3(kBlock), s,
+                  counts, R, allow_zero, tile_count, keys_b, vals_b);
         FS_LAUNCH("plan_scan", plan_scan_kernel, dim3(1), dim3(kScanBlock), s, tile_count, sel_tiles, num_cand);
-        FS_LAUNCH("plan_compact", plan_compact_kernel, dim3((unsigned)sel_tiles), dim3(kBlock), s,
-                  counts, R, allow_zero, tile_count, keys_a, vals_a);
+        FS_LAUNCH("plan_move", plan_move_kernel, dim3((unsigned)sel_tiles), dim3(kBlock), s,
+                  tile_count, sel_tiles, num_cand, keys_b, vals_b, keys_a, vals_a);
         uint32_t* keys = nullptr;
         uint32_t* vals = nullptr;
         fs_status rc = radix_sort_pairs(keys_a, vals_a, keys_b, vals_b, m_max, num_cand, 32, sort_scratch, s,
