@@ -162,7 +162,7 @@ constexpr uint32_t kSkip = 0xFFFFFFFFu;          // a run of one lookup: bwd_sin
                                                  // positions stop at 2^31 - 2)
 
 
-template <int LG, int DT>
+template <int LG, int DT, bool EXACT>            // EXACT: units == LG, the row stride is a compile-time constant
 __global__ __launch_bounds__(kBlock) void bwd_segreduce_kernel(
     const u32x4* __restrict__ grad, int units, int D,
     const uint32_t* __restrict__ keys, const uint32_t* __restrict__ vals, int64_t m, int64_t chunks,
@@ -227,7 +227,7 @@ __global__ __launch_bounds__(kBlock) void bwd_segreduce_kernel(
 #define FS_ISSUE(X, PV, E0)                                                                  \
     _Pragma("unroll") for (int j = 0; j < U8; ++j) {                                         \
         PV[j] = my_val[(E0) + j];                                                            \
-        X[j] = load_stream(my_grad + (int64_t)(PV[j] == kSkip ? 0u : PV[j] & ~kEndBit) * units); \
+        X[j] = load_stream(my_grad + (int64_t)(PV[j] == kSkip ? 0u : PV[j] & ~kEndBit) * (EXACT ? LG : units)); \
     }
 #define FS_CONSUME(X, PV, E0)                                                                \
     _Pragma("unroll") for (int j = 0; j < U8; ++j) {                                         \
@@ -316,7 +316,7 @@ __global__ __launch_bounds__(kBlock) void bwd_segreduce_kernel(
 // the wave's later loads (loads and stores share one in-order counter), so this kernel converts
 // them instead, fully parallel: a wave takes one chunk, finds its singletons and their run
 // indices with ballots, lists them in LDS and moves 64/LG rows per instruction, 8 in flight.
-template <int LG, int DT>
+template <int LG, int DT, bool EXACT>
 __global__ __launch_bounds__(kBlock) void bwd_singletons_kernel(
     const u32x4* __restrict__ grad, int units, int D,
     const uint32_t* __restrict__ keys, const uint32_t* __restrict__ vals, int64_t m, int64_t chunks,
@@ -378,7 +378,7 @@ __global__ __launch_bounds__(kBlock) void bwd_singletons_kernel(
             const uint32_t want = s + j * RPI + g;               // to the same place), so nothing is predicated
             at[j] = want < singles ? want : singles - 1;
             run[j] = s_run[w][at[j]];
-            x[j] = load_stream(grad + (int64_t)s_pos[w][at[j]] * units + cc);
+            x[j] = load_stream(grad + (int64_t)s_pos[w][at[j]] * (EXACT ? LG : units) + cc);
         }
 #pragma unroll
         for (int j = 0; j < UNR; ++j) {
@@ -473,15 +473,14 @@ static fs_status launch_segreduce(fs_dtype dtype, const void* grad, int units, i
     constexpr int GPB = kBlock / LG;
     const dim3 grid((unsigned)((chunks + GPB - 1) / GPB), (unsigned)((units + LG - 1) / LG));
     const u32x4* g = static_cast<const u32x4*>(grad);
-    if (dtype == FS_F32)
-        FS_LAUNCH("bwd_segreduce", (bwd_segreduce_kernel<LG, FS_F32>), grid, dim3(kBlock), stream, g, units, D, keys,
-                  vals, m, chunks, block_base, chunk_local, uniq_rows, row_grads, cap, carry, atomic);
-    else if (dtype == FS_F16)
-        FS_LAUNCH("bwd_segreduce", (bwd_segreduce_kernel<LG, FS_F16>), grid, dim3(kBlock), stream, g, units, D, keys,
-                  vals, m, chunks, block_base, chunk_local, uniq_rows, row_grads, cap, carry, atomic);
-    else
-        FS_LAUNCH("bwd_segreduce", (bwd_segreduce_kernel<LG, FS_BF16>), grid, dim3(kBlock), stream, g, units, D, keys,
-                  vals, m, chunks, block_base, chunk_local, uniq_rows, row_grads, cap, carry, atomic);
+#define FS_SEG_LAUNCH(DT, EX)                                                                                      \
+    FS_LAUNCH("bwd_segreduce", (bwd_segreduce_kernel<LG, DT, EX>), grid, dim3(kBlock), stream, g, units, D, keys, vals, \
+              m, chunks, block_base, chunk_local, uniq_rows, row_grads, cap, carry, atomic)
+    const bool exact = units == LG;
+    if (dtype == FS_F32) { if (exact) FS_SEG_LAUNCH(FS_F32, true); else FS_SEG_LAUNCH(FS_F32, false); }
+    else if (dtype == FS_F16) { if (exact) FS_SEG_LAUNCH(FS_F16, true); else FS_SEG_LAUNCH(FS_F16, false); }
+    else { if (exact) FS_SEG_LAUNCH(FS_BF16, true); else FS_SEG_LAUNCH(FS_BF16, false); }
+#undef FS_SEG_LAUNCH
     return FS_OK;
 }
 
@@ -493,15 +492,14 @@ static fs_status launch_singletons(fs_dtype dtype, const void* grad, int units, 
 {
     const dim3 grid((unsigned)((chunks + kWavesPerBlock - 1) / kWavesPerBlock), (unsigned)((units + LG - 1) / LG));
     const u32x4* g = static_cast<const u32x4*>(grad);
-    if (dtype == FS_F32)
-        FS_LAUNCH("bwd_singletons", (bwd_singletons_kernel<LG, FS_F32>), grid, dim3(kBlock), stream, g, units, D, keys,
-                  vals, m, chunks, block_base, chunk_local, uniq_rows, row_grads, cap);
-    else if (dtype == FS_F16)
-        FS_LAUNCH("bwd_singletons", (bwd_singletons_kernel<LG, FS_F16>), grid, dim3(kBlock), stream, g, units, D, keys,
-                  vals, m, chunks, block_base, chunk_local, uniq_rows, row_grads, cap);
-    else
-        FS_LAUNCH("bwd_singletons", (bwd_singletons_kernel<LG, FS_BF16>), grid, dim3(kBlock), stream, g, units, D, keys,
-                  vals, m, chunks, block_base, chunk_local, uniq_rows, row_grads, cap);
+#define FS_SINGLE_LAUNCH(DT, EX)                                                                                   \
+    FS_LAUNCH("bwd_singletons", (bwd_singletons_kernel<LG, DT, EX>), grid, dim3(kBlock), stream, g, units, D, keys,     \
+              vals, m, chunks, block_base, chunk_local, uniq_rows, row_grads, cap)
+    const bool exact = units == LG && LG >= 16;
+    if (dtype == FS_F32) { if (exact) FS_SINGLE_LAUNCH(FS_F32, (LG >= 16)); else FS_SINGLE_LAUNCH(FS_F32, false); }
+    else if (dtype == FS_F16) { if (exact) FS_SINGLE_LAUNCH(FS_F16, (LG >= 16)); else FS_SINGLE_LAUNCH(FS_F16, false); }
+    else { if (exact) FS_SINGLE_LAUNCH(FS_BF16, (LG >= 16)); else FS_SINGLE_LAUNCH(FS_BF16, false); }
+#undef FS_SINGLE_LAUNCH
     return FS_OK;
 }
 

@@ -28,7 +28,9 @@ struct GatherShape {
 // Moves the wave's 64 rows.  GUARD = false: every lookup of the wave is valid, loads and
 // stores carry no per-lane predicate (a predicated load makes the compiler wait for each
 // load before it issues the next, which serialises the 16 loads of a batch).
-template <int LG, bool GUARD>
+// EXACT: the row is exactly LG pieces long (power-of-two row sizes), so there is no loop over
+// pieces and no idle lane.
+template <int LG, bool GUARD, bool EXACT>
 __device__ __forceinline__ void gather_wave(const u32x4* __restrict__ weights, int units, u32x4* __restrict__ out,
                                             int64_t my_row, int32_t my_pos, int my_ok)
 {
@@ -48,21 +50,30 @@ __device__ __forceinline__ void gather_wave(const u32x4* __restrict__ weights, i
             const int64_t r = __shfl(my_row, from);
             const int32_t p = __shfl(my_pos, from);
             ok[u] = GUARD ? __shfl(my_ok, from) != 0 : true;
-            src[u] = r * units;
-            dst[u] = (int64_t)p * units;
+            src[u] = EXACT ? r * LG : r * units;             // a compile-time stride folds into shifts
+            dst[u] = EXACT ? (int64_t)p * LG : (int64_t)p * units;
         }
-        for (int c = lig; c < units; c += LG) {
+        if (EXACT) {
             u32x4 v[UNR];
 #pragma unroll
-            for (int u = 0; u < UNR; ++u) v[u] = weights[src[u] + c];       // invalid lookups read row 0
+            for (int u = 0; u < UNR; ++u) v[u] = weights[src[u] + lig];     // invalid lookups read row 0
 #pragma unroll
             for (int u = 0; u < UNR; ++u)
-                if (!GUARD || ok[u]) store_stream(out + dst[u] + c, v[u]);
+                if (!GUARD || ok[u]) store_stream(out + dst[u] + lig, v[u]);
+        } else {
+            for (int c = lig; c < units; c += LG) {
+                u32x4 v[UNR];
+#pragma unroll
+                for (int u = 0; u < UNR; ++u) v[u] = weights[src[u] + c];
+#pragma unroll
+                for (int u = 0; u < UNR; ++u)
+                    if (!GUARD || ok[u]) store_stream(out + dst[u] + c, v[u]);
+            }
         }
     }
 }
 
-template <int LG>
+template <int LG, bool EXACT>
 __global__ __launch_bounds__(kBlock) void gather_rows_kernel(
     const u32x4* __restrict__ weights, int64_t R, int units,
     const int64_t* __restrict__ rows, const int32_t* __restrict__ pos, int64_t m,
@@ -80,11 +91,12 @@ __global__ __launch_bounds__(kBlock) void gather_rows_kernel(
     if (jj < m) {
         my_row = load_stream(rows + jj);
         my_pos = load_stream(pos + jj);
-        my_ok = (my_row >= 0 && my_row < R && my_pos >= 0 && (int64_t)my_pos < n) ? 1 : 0;
+        // unsigned compares: one test each also catches the negative values (n < 2^31)
+        my_ok = ((uint64_t)my_row < (uint64_t)R && (uint32_t)my_pos < (uint32_t)n) ? 1 : 0;
         if (!my_ok) { report(status, FS_DEV_BAD_ID); my_row = 0; my_pos = 0; }
     }
-    if (ballot(my_ok != 0) == ~0ull) gather_wave<LG, false>(weights, units, out, my_row, my_pos, my_ok);
-    else gather_wave<LG, true>(weights, units, out, my_row, my_pos, my_ok);   // ragged tail or a bad index
+    if (ballot(my_ok != 0) == ~0ull) gather_wave<LG, false, EXACT>(weights, units, out, my_row, my_pos, my_ok);
+    else gather_wave<LG, true, EXACT>(weights, units, out, my_row, my_pos, my_ok);   // ragged tail or a bad index
 }
 
 template <int LG>
@@ -94,9 +106,12 @@ static fs_status launch_gather(const void* weights, int64_t R, int units, const 
 {
     const int64_t grid = (m + kGatherRowsPerBlock - 1) / kGatherRowsPerBlock;
     if (grid > 0x7FFFFFFF) return FS_ERR_SIZE;
-    FS_LAUNCH("gather_rows", gather_rows_kernel<LG>, dim3((unsigned)grid), dim3(kBlock), stream,
-              static_cast<const u32x4*>(weights), R, units, rows, pos, m,
-              static_cast<u32x4*>(out), n, status);
+    if (units == LG)
+        FS_LAUNCH("gather_rows", (gather_rows_kernel<LG, true>), dim3((unsigned)grid), dim3(kBlock), stream,
+                  static_cast<const u32x4*>(weights), R, units, rows, pos, m, static_cast<u32x4*>(out), n, status);
+    else
+        FS_LAUNCH("gather_rows", (gather_rows_kernel<LG, false>), dim3((unsigned)grid), dim3(kBlock), stream,
+                  static_cast<const u32x4*>(weights), R, units, rows, pos, m, static_cast<u32x4*>(out), n, status);
     return FS_OK;
 }
 
