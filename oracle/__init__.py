@@ -135,7 +135,7 @@ def plan_replication(ids, offsets, T: int, B: int, row_base, R: int, counts: np.
     cap = 0
     if flags & PLAN_SELECT and bytes_per_row >= 1 and budget_bytes >= 0:
         cap = min(R, budget_bytes // bytes_per_row)
-    sel = np.full(max(cap, 1), -1, dtype=np.int64)
+    sel = np.full(cap + 16, -1, dtype=np.int64)      # slack: a selection that is too long must show, not be cut
     nsel = ctypes.c_int64(0)
     status = ctypes.c_int32(0)
     rc = lib().oracle_plan_replication(

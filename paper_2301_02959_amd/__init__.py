@@ -75,7 +75,7 @@ def _check(fn: str, code: int, raise_on_error: bool) -> int:
     return code
 
 
-def _workspace(query, device) -> Tuple[torch.Tensor, ctypes.c_size_t]:
+def _workspace(query, device) -> Tuple[Optional[torch.Tensor], ctypes.c_size_t, int]:
     """Ask the entry point for its scratch size, then allocate it through torch."""
     size = ctypes.c_size_t(0)
     code = query(ctypes.c_void_p(0), ctypes.byref(size))

@@ -11,7 +11,6 @@ namespace fs {
 constexpr int kWave = 64;          // CDNA wavefront
 constexpr int kBlock = 256;        // threads per workgroup used by every kernel here
 constexpr int kWavesPerBlock = kBlock / kWave;
-constexpr int kXcds = 8;           // MI355X: 8 XCDs, workgroups are dealt to them round-robin
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
@@ -110,14 +109,6 @@ __device__ __forceinline__ uint64_t match_bits_n(uint32_t key, bool valid)
         case 7: CALL(7); break;  case 8: CALL(8); break;  case 9: CALL(9); break;       \
         default: CALL(10); break;                                                       \
     }
-
-// Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Map
-// the hardware block id to a logical tile so that every XCD walks one
-// contiguous range of tiles.  The grid must have kXcds * tiles_per_xcd blocks.
-__device__ __forceinline__ int64_t xcd_contiguous_tile(int64_t bid, int64_t tiles_per_xcd)
-{
-    return (bid % kXcds) * tiles_per_xcd + bid / kXcds;
-}
 
 template <typename T>
 __device__ __forceinline__ T load_stream(const T* p) { return __builtin_nontemporal_load(p); }

@@ -137,6 +137,10 @@ def test_data_faults():
     # g = [0, 1, 3, 5]; dest: g0 ->1, g1 owner 9 >= U -> self 0, g3 tier1 owner 5 >= W -> self 0, g5 -> 0
     assert bo.tolist() == [0, 3, 4] and rows.tolist() == [1, 3, 5, 0] and pos.tolist() == [1, 2, 3, 0]
     assert tc.tolist() == [0, 1, 3]
+    # tier 1: the owner must lie inside a group (< W) even when it would be a valid bucket (< U)
+    rc, st, bo, rows, pos, tc = oracle.route_bucketize(np.array([0, 1]), np.array([0, 2]), 1, 1, np.array([0, 2]),
+                                                       np.array([entry(1, 5), entry(1, 1)], np.uint32), 8, 4, 6)
+    assert st == oracle.BAD_PLACEMENT and bo.tolist() == [0, 0, 0, 0, 0, 0, 1, 2, 2] and rows.tolist() == [1, 0]
     # tier 3 counts under tier 0 and is served locally
     rc, st, bo, rows, pos, tc = oracle.route_bucketize(np.array([2]), np.array([0, 1]), 1, 1, np.array([0, 3]), placement[:3], 2, 1, 1)
     assert st == oracle.BAD_PLACEMENT and bo.tolist() == [0, 0, 1] and tc.tolist() == [1, 0, 0]
