@@ -100,6 +100,61 @@ def seq_gather_fwd(weights: np.ndarray, rows, pos, j0: int, j1: int, out: np.nda
     return rc, status.value
 
 
+def seq_gather_send(weights: np.ndarray, rows, j0: int, j1: int, send: np.ndarray,
+                    dtype: Optional[int] = None) -> Tuple[int, int]:
+    """send[j - j0, :] = weights[rows[j], :] for j in [j0, j1), in place.  Returns (rc, status)."""
+    code = _dtype_code(weights, dtype)
+    rows = _i64(rows)
+    R, D = weights.shape
+    status = ctypes.c_int32(0)
+    rc = lib().oracle_seq_gather_send(
+        _p(weights), ctypes.c_int64(R), ctypes.c_int32(D), ctypes.c_int(code), _p(rows),
+        ctypes.c_int64(j0), ctypes.c_int64(j1), _p(send), ctypes.byref(status))
+    return rc, status.value
+
+
+def seq_unbucketize(recv: np.ndarray, pos, j0: int, j1: int, out: np.ndarray,
+                    dtype: Optional[int] = None) -> Tuple[int, int]:
+    """out[pos[j], :] = recv[j - j0, :] for j in [j0, j1), in place.  Returns (rc, status)."""
+    code = _dtype_code(recv, dtype)
+    pos = np.ascontiguousarray(pos, dtype=np.int32)
+    D = recv.shape[1]
+    status = ctypes.c_int32(0)
+    rc = lib().oracle_seq_unbucketize(
+        _p(recv), ctypes.c_int32(D), ctypes.c_int(code), _p(pos), ctypes.c_int64(j0), ctypes.c_int64(j1),
+        _p(out), ctypes.c_int64(out.shape[0]), ctypes.byref(status))
+    return rc, status.value
+
+
+def replica_build(weights: np.ndarray, sel_rows, store: np.ndarray, dtype: Optional[int] = None):
+    """store[s] = weights[sel_rows[s]] in place.  Returns (rc, status, slot_of_row[R] int32)."""
+    code = _dtype_code(weights, dtype)
+    sel = _i64(sel_rows)
+    R, D = weights.shape
+    slots = np.full(R, -7, dtype=np.int32)
+    status = ctypes.c_int32(0)
+    rc = lib().oracle_replica_build(
+        _p(weights), ctypes.c_int64(R), ctypes.c_int32(D), ctypes.c_int(code), _p(sel),
+        ctypes.c_int64(sel.shape[0]), _p(store), _p(slots), ctypes.byref(status))
+    return rc, status.value, slots
+
+
+def seq_gather_fwd_replica(weights: np.ndarray, store: np.ndarray, slot_of_row, rows, pos, j0: int, j1: int,
+                           out: np.ndarray, dtype: Optional[int] = None) -> Tuple[int, int]:
+    """seq_gather_fwd with rows that have a slot read from `store`.  Returns (rc, status)."""
+    code = _dtype_code(weights, dtype)
+    rows = _i64(rows)
+    pos = np.ascontiguousarray(pos, dtype=np.int32)
+    slots = np.ascontiguousarray(slot_of_row, dtype=np.int32)
+    R, D = weights.shape
+    status = ctypes.c_int32(0)
+    rc = lib().oracle_seq_gather_fwd_replica(
+        _p(weights), ctypes.c_int64(R), ctypes.c_int32(D), ctypes.c_int(code), _p(store),
+        ctypes.c_int64(store.shape[0]), _p(slots), _p(rows), _p(pos), ctypes.c_int64(j0), ctypes.c_int64(j1),
+        _p(out), ctypes.c_int64(out.shape[0]), ctypes.byref(status))
+    return rc, status.value
+
+
 def seq_grad_bwd(grad_out: np.ndarray, rows, pos, j0: int, j1: int, R: int, tile: int = BWD_TILE,
                  cap_unique: Optional[int] = None, dtype: Optional[int] = None, want64: bool = True):
     """Returns (rc, status, uniq_rows[n_u], row_grads[n_u, D] f32, row_grads64 or None, n_u)."""

@@ -11,7 +11,7 @@
  * Every function takes host pointers and returns 0 or a host-fault code;
  * data faults are OR-ed into *status (may be NULL).
  *
- * Pins (tests/test_oracle_*.py): stable argsort / bincount / take / lexsort /
+ * Pins (tests/test_oracle_*.py): stable argsort / bincount / take / put / lexsort /
  * fp64 add.at reductions, brute force over all placements on tiny inputs,
  * hand-computed rounding cases for the summation order, invariants.
  * No function here is "parity unpinned".
@@ -154,6 +154,105 @@ int oracle_seq_gather_fwd(
         if (r < 0 || r >= R || p < 0 || p >= n) { flag(status, DEV_BAD_ID); continue; }
         memcpy((char*)out + (size_t)p * row_bytes,
                (const char*)weights + (size_t)r * row_bytes, row_bytes);
+    }
+    return OK;
+}
+
+/*
+ * The two steps either side of the row exchange (Section 3.2, "dynamic
+ * communication": the rows a GPU looked up for another GPU are sent back in
+ * the order that GPU's ids arrived; Table 3, column "Dynamic Comms").
+ * Owner: send[j - j0, :] = weights[rows[j], :].
+ */
+int oracle_seq_gather_send(
+    const void* weights, int64_t R, int32_t D, int dtype,
+    const int64_t* rows, int64_t j0, int64_t j1, void* send, int32_t* status)
+{
+    int es = elem_size(dtype);
+    if (!es) return ERR_DTYPE;
+    if (R < 1 || D < 1 || j0 < 0 || j0 > j1) return ERR_SIZE;
+    if (j1 > j0 && (!weights || !rows || !send)) return ERR_NULL;
+    size_t row_bytes = (size_t)D * (size_t)es;
+    if (row_bytes % 16 != 0) return ERR_ALIGN;
+    for (int64_t j = j0; j < j1; ++j) {
+        int64_t r = rows[j];
+        if (r < 0 || r >= R) { flag(status, DEV_BAD_ID); continue; }
+        memcpy((char*)send + (size_t)(j - j0) * row_bytes,
+               (const char*)weights + (size_t)r * row_bytes, row_bytes);
+    }
+    return OK;
+}
+
+/* Requester: out[pos[j], :] = recv[j - j0, :]. */
+int oracle_seq_unbucketize(
+    const void* recv, int32_t D, int dtype, const int32_t* pos, int64_t j0, int64_t j1,
+    void* out, int64_t n, int32_t* status)
+{
+    int es = elem_size(dtype);
+    if (!es) return ERR_DTYPE;
+    if (n < 0 || D < 1 || j0 < 0 || j0 > j1) return ERR_SIZE;
+    if (j1 > j0 && (!recv || !pos || !out)) return ERR_NULL;
+    size_t row_bytes = (size_t)D * (size_t)es;
+    if (row_bytes % 16 != 0) return ERR_ALIGN;
+    for (int64_t j = j0; j < j1; ++j) {
+        int64_t p = pos[j];
+        if (p < 0 || p >= n) { flag(status, DEV_BAD_ID); continue; }
+        memcpy((char*)out + (size_t)p * row_bytes,
+               (const char*)recv + (size_t)(j - j0) * row_bytes, row_bytes);
+    }
+    return OK;
+}
+
+/*
+ * Replica store (Section 3.1: a data-parallel row lives on every GPU and is
+ * looked up locally; Section 4.3: the rows chosen for replication are the
+ * most popular ones).  The chosen rows are copied into a dense array in
+ * selection order; slot_of_row maps a row to its first slot, -1 otherwise.
+ */
+int oracle_replica_build(
+    const void* weights, int64_t R, int32_t D, int dtype,
+    const int64_t* sel_rows, int64_t k, void* store, int32_t* slot_of_row, int32_t* status)
+{
+    int es = elem_size(dtype);
+    if (!es) return ERR_DTYPE;
+    if (R < 1 || D < 1 || k < 0) return ERR_SIZE;
+    if (!weights || !slot_of_row || (k > 0 && (!sel_rows || !store))) return ERR_NULL;
+    size_t row_bytes = (size_t)D * (size_t)es;
+    if (row_bytes % 16 != 0) return ERR_ALIGN;
+    for (int64_t r = 0; r < R; ++r) slot_of_row[r] = -1;
+    for (int64_t s = 0; s < k; ++s) {
+        int64_t r = sel_rows[s];
+        if (r < 0 || r >= R) { flag(status, DEV_BAD_ID); continue; }
+        memcpy((char*)store + (size_t)s * row_bytes,
+               (const char*)weights + (size_t)r * row_bytes, row_bytes);
+        if (slot_of_row[r] < 0) slot_of_row[r] = (int32_t)s;
+    }
+    return OK;
+}
+
+/* The gather with replicated rows served from the store. */
+int oracle_seq_gather_fwd_replica(
+    const void* weights, int64_t R, int32_t D, int dtype,
+    const void* store, int64_t k, const int32_t* slot_of_row,
+    const int64_t* rows, const int32_t* pos, int64_t j0, int64_t j1,
+    void* out, int64_t n, int32_t* status)
+{
+    int es = elem_size(dtype);
+    if (!es) return ERR_DTYPE;
+    if (R < 1 || n < 0 || D < 1 || j0 < 0 || j0 > j1 || k < 0) return ERR_SIZE;
+    if (j1 > j0 && (!weights || !rows || !pos || !out || !slot_of_row || (k > 0 && !store))) return ERR_NULL;
+    size_t row_bytes = (size_t)D * (size_t)es;
+    if (row_bytes % 16 != 0) return ERR_ALIGN;
+    for (int64_t j = j0; j < j1; ++j) {
+        int64_t r = rows[j];
+        int64_t p = pos[j];
+        if (r < 0 || r >= R || p < 0 || p >= n) { flag(status, DEV_BAD_ID); continue; }
+        int32_t s = slot_of_row[r];
+        const char* from;
+        if (s < 0) from = (const char*)weights + (size_t)r * row_bytes;
+        else if (s < k) from = (const char*)store + (size_t)s * row_bytes;
+        else { flag(status, DEV_BAD_ID); continue; }
+        memcpy((char*)out + (size_t)p * row_bytes, from, row_bytes);
     }
     return OK;
 }

@@ -38,6 +38,11 @@ MUTANTS = {
     "budget_rounds_up": ("int64_t cap = budget_bytes / bytes_per_row;", "int64_t cap = (budget_bytes + bytes_per_row - 1) / bytes_per_row;"),
     "zeros_selected": ("if (counts[g] > 0 || (flags & PLAN_ALLOW_ZERO))", "if (1)"),
     "tag_sets_tier2": ("placement[cand[i].g] &= 0x3FFFFFFFu;", "placement[cand[i].g] = (placement[cand[i].g] & 0x3FFFFFFFu) | 0x80000000u;"),
+    "send_indexed_by_j_not_offset": ("memcpy((char*)send + (size_t)(j - j0) * row_bytes,", "memcpy((char*)send + (size_t)(j - j0 > 0 ? j - j0 - 1 : 0) * row_bytes,"),
+    "unbucketize_reads_by_pos": ("(const char*)recv + (size_t)(j - j0) * row_bytes, row_bytes);", "(const char*)recv + (size_t)(p % (j1 - j0)) * row_bytes, row_bytes);"),
+    "replica_last_slot_wins": ("if (slot_of_row[r] < 0) slot_of_row[r] = (int32_t)s;", "slot_of_row[r] = (int32_t)s;"),
+    "replica_store_ignored": ("else if (s < k) from = (const char*)store + (size_t)s * row_bytes;", "else if (s < k) from = (const char*)weights + (size_t)r * row_bytes;"),
+    "replica_slot_is_row": ("else if (s < k) from = (const char*)store + (size_t)s * row_bytes;", "else if (s < k) from = (const char*)store + (size_t)(r % k) * row_bytes;"),
 }
 # a mutant that changes nothing observable would be a bad test of the tests: keep only real ones
 MUTANTS.pop("fold_right_to_left")
@@ -122,6 +127,27 @@ def pins(o):
     p2 = np.full(300, entry(2, 1), np.uint32)
     sel = o.plan_replication(None, None, 1, 1, None, 300, c2.copy(), o.PLAN_SELECT | o.PLAN_TAG, 5, 1, p2)[2]
     assert np.all(p2[sel] >> 30 == 0) and (p2 >> 30 == 2).sum() == 295
+    # exchange halves and replica store: take, row assignment, first-occurrence map
+    rows_x = rng.integers(0, T * E, 50)
+    pos_x = rng.permutation(50).astype(np.int32)
+    send = np.zeros((30, 8), np.float32)
+    assert o.seq_gather_send(Wt, rows_x, 10, 40, send) == (0, 0)
+    assert np.array_equal(send, Wt[rows_x[10:40]])
+    out_x = np.zeros((50, 8), np.float32)
+    assert o.seq_unbucketize(send, pos_x, 10, 40, out_x) == (0, 0)
+    exp_x = np.zeros((50, 8), np.float32)
+    exp_x[pos_x[10:40]] = send
+    assert np.array_equal(out_x, exp_x)
+    sel_x = np.array([9, 3, 9, 77, 20], np.int64)
+    store = np.zeros((5, 8), np.float32)
+    rc, st, slots = o.replica_build(Wt, sel_x, store)
+    assert (rc, st) == (0, 0) and np.array_equal(store, Wt[sel_x])
+    assert slots[9] == 0 and slots[3] == 1 and slots[77] == 3 and slots[20] == 4 and (slots >= 0).sum() == 4
+    look = np.array([3, 5, 77, 9, 20, 6], np.int64)
+    mark = store + 1000.0
+    out_r = np.zeros((6, 8), np.float32)
+    assert o.seq_gather_fwd_replica(Wt, mark, slots, look, np.arange(6, dtype=np.int32), 0, 6, out_r) == (0, 0)
+    assert np.array_equal(out_r, np.stack([mark[1], Wt[5], mark[3], mark[0], mark[4], Wt[6]]))
 
 
 def test_pins_accept_the_real_oracle():
