@@ -32,6 +32,7 @@ def parse():
     ap.add_argument("--config", default="c3", help="c1..c5 (c3 = the configuration the target is stated on)")
     ap.add_argument("--variant", type=int, default=0, help="backward: 0 sort/bit-exact, 1 atomic partials")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-exchange", action="store_true", help="skip the untimed send / unbucketize / replica-store report")
     ap.add_argument("--cpu-tables", type=int, default=0, help="tables in the oracle's sample (0 = automatic)")
     ap.add_argument("--scale-rows", type=int, default=1, help="divide E by this (debugging only; reported)")
     return ap.parse_args()
@@ -224,6 +225,45 @@ def main():
         copy_ms = e0.elapsed_time(e1) / 5
         result["plain_copy"] = {"bytes_each_way": copy_bytes, "ms": round(copy_ms, 4),
                                 "GBps_read_plus_write": round(2 * copy_bytes / (copy_ms * 1e-3) / 1e9, 1)}
+
+    # ---------------------------------------------------------------- the exchange halves and the replica store
+    # Not part of the step or of `value`: the same lookups once more through fs_seq_gather_send +
+    # fs_seq_unbucketize (the two sides of the row exchange) and through fs_seq_gather_fwd_replica (popular
+    # rows served from the dense store that fs_replica_build fills from the plan's selection).
+    need = n * row_bytes + budget_rows * row_bytes + R * 4
+    if not args.no_exchange and torch.cuda.mem_get_info()[0] > 1.1 * need + (1 << 30):
+        send = torch.empty(n, D, dtype=cfg.torch_dtype, device=dev)
+        store = torch.empty(budget_rows, D, dtype=cfg.torch_dtype, device=dev)
+        slots = torch.empty(R, dtype=torch.int32, device=dev)
+        k_sel = int(num_selected.item())
+
+        def xstep():
+            fs.fs_replica_build(weights, sel_rows, budget_rows, num_selected, store, slots, status)
+            fs.fs_seq_gather_send(weights, out_rows, 0, n, send, status)
+            fs.fs_seq_unbucketize(send, out_pos, 0, n, out, status)
+            fs.fs_seq_gather_fwd_replica(weights, store, budget_rows, slots, out_rows, out_pos, 0, n, out, status)
+
+        for _ in range(2):
+            xstep()
+        reps = 5
+        fs.fs_prof_begin(16 * reps)
+        for _ in range(reps):
+            xstep()
+        torch.cuda.synchronize()
+        xrec = {}
+        for name, ms in fs.fs_prof_end(16 * reps):
+            xrec[name] = xrec.get(name, 0.0) + ms / reps
+        assert int(status.item()) == 0, f"device status {int(status.item())}"
+        xalg = {"gather_send": n * row_bytes + n_u * row_bytes + n * 8,
+                "unbucketize": 2 * n * row_bytes + n * 4,
+                "gather_replica": n * row_bytes + n_u * row_bytes + n * 16}
+        result["exchange_path"] = {
+            "replica_rows": k_sel,
+            "kernels": {k: {"ms": round(v, 4),
+                            **({"GBps": round(xalg[k] / (v * 1e-3) / 1e9, 1),
+                                "frac": round(xalg[k] / (v * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)} if k in xalg else {})}
+                        for k, v in sorted(xrec.items())}}
+        del send, store, slots
 
     # ---------------------------------------------------------------- CPU oracle on a bounded sample
     if not args.no_cpu_baseline:

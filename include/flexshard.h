@@ -151,6 +151,68 @@ fs_status fs_seq_gather_fwd(
     void* out, int64_t n, void* stream, int32_t* dev_status);
 
 /*
+ * The two halves of fs_seq_gather_fwd that sit either side of the row exchange
+ * (Section 3.2 metric 2, "dynamic communication": the looked-up rows travel
+ * from the GPU that owns them back to the GPU that asked, in the order the ids
+ * arrived there; Table 3, column "Dynamic Comms").
+ *
+ * fs_seq_gather_send -- owner side: send[j - j0, :] = weights[rows[j], :] for
+ *   j in [j0, j1); send is [j1 - j0, D], contiguous, in bucket order.
+ * fs_seq_unbucketize -- requester side: out[pos[j], :] = recv[j - j0, :] for
+ *   j in [j0, j1); recv is [j1 - j0, D].
+ * fs_seq_unbucketize(send of fs_seq_gather_send) writes the same bits as
+ * fs_seq_gather_fwd over the same [j0, j1).
+ *
+ * Data faults: rows[j] outside [0, R): send row j - j0 is left untouched;
+ * pos[j] outside [0, n): that j is skipped (both FS_DEV_BAD_ID).
+ * Host faults: as fs_seq_gather_fwd; j1 - j0 >= 2^31 (FS_ERR_SIZE).
+ */
+fs_status fs_seq_gather_send(
+    const void* weights, int64_t R, int32_t D, fs_dtype dtype,
+    const int64_t* rows, int64_t j0, int64_t j1,
+    void* send, void* stream, int32_t* dev_status);
+
+fs_status fs_seq_unbucketize(
+    const void* recv, int32_t D, fs_dtype dtype,
+    const int32_t* pos, int64_t j0, int64_t j1,
+    void* out, int64_t n, void* stream, int32_t* dev_status);
+
+/*
+ * Replica store (Section 3.1, data-parallel placement: a replicated row is
+ * held by every GPU and its lookups are served locally; Section 4.3: the
+ * replicated rows are the most popular ones, so a small dense array serves a
+ * large share of the lookups).
+ *
+ * fs_replica_build -- copies the selected rows into a dense array and writes
+ *   the map from row to slot:
+ *     k' = k if num_selected == NULL else min(k, *num_selected)   (device scalar)
+ *     store[s, :] = weights[sel_rows[s], :]          for s in [0, k')
+ *     slot_of_row[r] = the smallest s < k' with sel_rows[s] == r, else -1,
+ *                      for every r in [0, R)   (overwritten completely)
+ *   store is [k, D]; rows k'.. of it are left untouched.  sel_rows / num_selected
+ *   are what fs_plan_replication writes.
+ *   Data faults: sel_rows[s] outside [0, R): store row s is left untouched and
+ *   no slot points to it (FS_DEV_BAD_ID).
+ *   Host faults: NULL; R < 1, D < 1, k < 0, k >= 2^31 (FS_ERR_SIZE); alignment
+ *   as fs_seq_gather_fwd.
+ *
+ * fs_seq_gather_fwd_replica -- fs_seq_gather_fwd, except that a row r with
+ *   slot_of_row[r] = s >= 0 is read from store[s, :] instead of weights[r, :].
+ *   With a store built from the same weights the output bits are those of
+ *   fs_seq_gather_fwd.  A slot >= k skips that lookup (FS_DEV_BAD_ID).
+ */
+fs_status fs_replica_build(
+    const void* weights, int64_t R, int32_t D, fs_dtype dtype,
+    const int64_t* sel_rows, int64_t k, const int64_t* num_selected,
+    void* store, int32_t* slot_of_row, void* stream, int32_t* dev_status);
+
+fs_status fs_seq_gather_fwd_replica(
+    const void* weights, int64_t R, int32_t D, fs_dtype dtype,
+    const void* store, int64_t k, const int32_t* slot_of_row,
+    const int64_t* rows, const int32_t* pos, int64_t j0, int64_t j1,
+    void* out, int64_t n, void* stream, int32_t* dev_status);
+
+/*
  * fs_seq_grad_bwd -- backward of the sequence lookup (Section 3.2 metrics 4-6:
  * the gradient of every materialised row flows back to the row's owner, where
  * duplicates of one row are summed before the update).

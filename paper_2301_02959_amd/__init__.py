@@ -27,6 +27,7 @@ STATUS_NAMES = {0: "FS_OK", 1: "FS_ERR_NULL", 2: "FS_ERR_SIZE", 3: "FS_ERR_DTYPE
                 5: "FS_ERR_WORKSPACE", 6: "FS_ERR_CONFIG", 7: "FS_ERR_DEVICE"}
 
 EXPORTS = ["fs_route_bucketize", "fs_seq_gather_fwd", "fs_seq_grad_bwd", "fs_plan_replication",
+           "fs_seq_gather_send", "fs_seq_unbucketize", "fs_replica_build", "fs_seq_gather_fwd_replica",
            "fs_util_copy", "fs_version", "fs_bwd_tile", "fs_prof_begin", "fs_prof_end"]
 
 _DTYPES = {torch.float32: FS_F32, torch.float16: FS_F16, torch.bfloat16: FS_BF16}
@@ -50,7 +51,8 @@ def lib() -> ctypes.CDLL:
                 "(hipcc, gfx950); this package has no other code path")
         _lib = ctypes.CDLL(LIB_PATH)
         for name in ("fs_route_bucketize", "fs_seq_gather_fwd", "fs_seq_grad_bwd", "fs_plan_replication",
-                     "fs_prof_begin", "fs_util_copy"):
+                     "fs_seq_gather_send", "fs_seq_unbucketize", "fs_replica_build",
+                     "fs_seq_gather_fwd_replica", "fs_prof_begin", "fs_util_copy"):
             getattr(_lib, name).restype = ctypes.c_int
         _lib.fs_version.restype = ctypes.c_int32
         _lib.fs_bwd_tile.restype = ctypes.c_int32
@@ -127,6 +129,55 @@ def fs_seq_gather_fwd(weights, rows, pos, j0: int, j1: int, out, dev_status=None
         _ptr(weights), ctypes.c_int64(R), ctypes.c_int32(D), ctypes.c_int(dtype), _ptr(rows), _ptr(pos),
         ctypes.c_int64(j0), ctypes.c_int64(j1), _ptr(out), ctypes.c_int64(n), _stream(), _ptr(dev_status))
     return _check("fs_seq_gather_fwd", code, raise_on_error)
+
+
+def fs_seq_gather_send(weights, rows, j0: int, j1: int, send, dev_status=None, raise_on_error: bool = True,
+                       R: Optional[int] = None, D: Optional[int] = None, dtype: Optional[int] = None) -> int:
+    R = weights.shape[0] if R is None else R
+    D = weights.shape[1] if D is None else D
+    dtype = _DTYPES[weights.dtype] if dtype is None else dtype
+    code = lib().fs_seq_gather_send(
+        _ptr(weights), ctypes.c_int64(R), ctypes.c_int32(D), ctypes.c_int(dtype), _ptr(rows),
+        ctypes.c_int64(j0), ctypes.c_int64(j1), _ptr(send), _stream(), _ptr(dev_status))
+    return _check("fs_seq_gather_send", code, raise_on_error)
+
+
+def fs_seq_unbucketize(recv, pos, j0: int, j1: int, out, dev_status=None, raise_on_error: bool = True,
+                       D: Optional[int] = None, dtype: Optional[int] = None, n: Optional[int] = None) -> int:
+    D = recv.shape[1] if D is None else D
+    n = out.shape[0] if n is None else n
+    dtype = _DTYPES[recv.dtype] if dtype is None else dtype
+    code = lib().fs_seq_unbucketize(
+        _ptr(recv), ctypes.c_int32(D), ctypes.c_int(dtype), _ptr(pos), ctypes.c_int64(j0), ctypes.c_int64(j1),
+        _ptr(out), ctypes.c_int64(n), _stream(), _ptr(dev_status))
+    return _check("fs_seq_unbucketize", code, raise_on_error)
+
+
+def fs_replica_build(weights, sel_rows, k: int, num_selected, store, slot_of_row, dev_status=None,
+                     raise_on_error: bool = True, R: Optional[int] = None, D: Optional[int] = None,
+                     dtype: Optional[int] = None) -> int:
+    R = weights.shape[0] if R is None else R
+    D = weights.shape[1] if D is None else D
+    dtype = _DTYPES[weights.dtype] if dtype is None else dtype
+    code = lib().fs_replica_build(
+        _ptr(weights), ctypes.c_int64(R), ctypes.c_int32(D), ctypes.c_int(dtype), _ptr(sel_rows),
+        ctypes.c_int64(k), _ptr(num_selected), _ptr(store), _ptr(slot_of_row), _stream(), _ptr(dev_status))
+    return _check("fs_replica_build", code, raise_on_error)
+
+
+def fs_seq_gather_fwd_replica(weights, store, k: int, slot_of_row, rows, pos, j0: int, j1: int, out,
+                              dev_status=None, raise_on_error: bool = True, R: Optional[int] = None,
+                              D: Optional[int] = None, dtype: Optional[int] = None,
+                              n: Optional[int] = None) -> int:
+    R = weights.shape[0] if R is None else R
+    D = weights.shape[1] if D is None else D
+    n = out.shape[0] if n is None else n
+    dtype = _DTYPES[weights.dtype] if dtype is None else dtype
+    code = lib().fs_seq_gather_fwd_replica(
+        _ptr(weights), ctypes.c_int64(R), ctypes.c_int32(D), ctypes.c_int(dtype), _ptr(store), ctypes.c_int64(k),
+        _ptr(slot_of_row), _ptr(rows), _ptr(pos), ctypes.c_int64(j0), ctypes.c_int64(j1), _ptr(out),
+        ctypes.c_int64(n), _stream(), _ptr(dev_status))
+    return _check("fs_seq_gather_fwd_replica", code, raise_on_error)
 
 
 def fs_seq_grad_bwd(grad_out, rows, pos, j0: int, j1: int, R: int, variant: int,

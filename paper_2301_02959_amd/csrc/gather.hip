@@ -1,4 +1,6 @@
-// fs_seq_gather_fwd: out[pos[j], :] = weights[rows[j], :] for j in [j0, j1).
+// fs_seq_gather_fwd: out[pos[j], :] = weights[rows[j], :] for j in [j0, j1), and its relatives
+// (fs_seq_gather_send, fs_seq_unbucketize, fs_replica_build, fs_seq_gather_fwd_replica), which
+// run the same kernel with one index array replaced by j itself or with a second row source.
 //
 // HBM-bound bit copy.  A wave owns 64 consecutive lookups: it fetches their 64 row
 // indices and 64 positions with ONE coalesced load each (a per-row index load in
@@ -31,8 +33,8 @@ struct GatherShape {
 // EXACT: the row is exactly LG pieces long (power-of-two row sizes), so there is no loop over
 // pieces and no idle lane.
 template <int LG, bool GUARD, bool EXACT>
-__device__ __forceinline__ void gather_wave(const u32x4* __restrict__ weights, int units, u32x4* __restrict__ out,
-                                            int64_t my_row, int32_t my_pos, int my_ok)
+__device__ __forceinline__ void gather_wave(int units, u32x4* __restrict__ out,
+                                            const u32x4* my_src, int32_t my_pos, int my_ok)
 {
     constexpr int RPI = GatherShape<LG>::RPI;
     constexpr int UNR = GatherShape<LG>::UNR;
@@ -41,22 +43,21 @@ __device__ __forceinline__ void gather_wave(const u32x4* __restrict__ weights, i
     const int lig = lane % LG;
 #pragma unroll 1
     for (int s = 0; s < kGatherRowsPerWave; s += UNR * RPI) {
-        int64_t src[UNR];
+        const u32x4* src[UNR];
         int64_t dst[UNR];
         bool ok[UNR];
 #pragma unroll
         for (int u = 0; u < UNR; ++u) {
             const int from = s + u * RPI + g;            // lane that holds this row's indices
-            const int64_t r = __shfl(my_row, from);
+            src[u] = reinterpret_cast<const u32x4*>(__shfl((int64_t) reinterpret_cast<uintptr_t>(my_src), from));
             const int32_t p = __shfl(my_pos, from);
             ok[u] = GUARD ? __shfl(my_ok, from) != 0 : true;
-            src[u] = EXACT ? r * LG : r * units;             // a compile-time stride folds into shifts
             dst[u] = EXACT ? (int64_t)p * LG : (int64_t)p * units;
         }
         if (EXACT) {
             u32x4 v[UNR];
 #pragma unroll
-            for (int u = 0; u < UNR; ++u) v[u] = weights[src[u] + lig];     // invalid lookups read row 0
+            for (int u = 0; u < UNR; ++u) v[u] = src[u][lig];               // invalid lookups read row 0
 #pragma unroll
             for (int u = 0; u < UNR; ++u)
                 if (!GUARD || ok[u]) store_stream(out + dst[u] + lig, v[u]);
@@ -64,7 +65,7 @@ __device__ __forceinline__ void gather_wave(const u32x4* __restrict__ weights, i
             for (int c = lig; c < units; c += LG) {
                 u32x4 v[UNR];
 #pragma unroll
-                for (int u = 0; u < UNR; ++u) v[u] = weights[src[u] + c];
+                for (int u = 0; u < UNR; ++u) v[u] = src[u][c];
 #pragma unroll
                 for (int u = 0; u < UNR; ++u)
                     if (!GUARD || ok[u]) store_stream(out + dst[u] + c, v[u]);
@@ -73,14 +74,36 @@ __device__ __forceinline__ void gather_wave(const u32x4* __restrict__ weights, i
     }
 }
 
-template <int LG, bool EXACT>
-__global__ __launch_bounds__(kBlock) void gather_rows_kernel(
-    const u32x4* __restrict__ weights, int64_t R, int units,
-    const int64_t* __restrict__ rows, const int32_t* __restrict__ pos, int64_t m,
-    u32x4* __restrict__ out, int64_t n, int32_t* status)
+// Which of the two index arrays a launch reads.
+//   kBoth:     out[pos[j]]  = weights[rows[j]]     (fs_seq_gather_fwd)
+//   kToSend:   out[j]       = weights[rows[j]]     (fs_seq_gather_send, fs_replica_build)
+//   kFromRecv: out[pos[j]]  = weights[j]           (fs_seq_unbucketize)
+//   kReplica:  as kBoth, but a row with slot_of_row[row] >= 0 is read from store[slot]
+enum GatherMode { kBoth = 0, kToSend = 1, kFromRecv = 2, kReplica = 3 };
+
+struct GatherArgs {
+    const u32x4* weights;
+    int64_t R;
+    int units;
+    const int64_t* rows;
+    const int32_t* pos;
+    int64_t m;
+    const int64_t* m_dev;            // if set, only the first min(m, *m_dev) lookups are moved
+    u32x4* out;
+    int64_t n;
+    int32_t* status;
+    const u32x4* store;              // kReplica only
+    const int32_t* slot_of_row;
+    int64_t k;
+};
+
+template <int LG, bool EXACT, int MODE>
+__global__ __launch_bounds__(kBlock) void gather_rows_kernel(const GatherArgs a)
 {
     const int lane = lane_id();
     const int64_t wbase = ((int64_t)blockIdx.x * kWavesPerBlock + wave_id()) * kGatherRowsPerWave;
+    int64_t m = a.m;
+    if (a.m_dev) { const int64_t md = *a.m_dev; m = md < m ? (md < 0 ? 0 : md) : m; }
     if (wbase >= m) return;                              // wave-uniform
 
     // one coalesced load of the wave's 64 (row, position) pairs
@@ -89,30 +112,81 @@ __global__ __launch_bounds__(kBlock) void gather_rows_kernel(
     int32_t my_pos = 0;
     int my_ok = 0;
     if (jj < m) {
-        my_row = load_stream(rows + jj);
-        my_pos = load_stream(pos + jj);
+        my_row = MODE == kFromRecv ? jj : load_stream(a.rows + jj);
+        my_pos = MODE == kToSend ? (int32_t)jj : load_stream(a.pos + jj);
         // unsigned compares: one test each also catches the negative values (n < 2^31)
-        my_ok = ((uint64_t)my_row < (uint64_t)R && (uint32_t)my_pos < (uint32_t)n) ? 1 : 0;
-        if (!my_ok) { report(status, FS_DEV_BAD_ID); my_row = 0; my_pos = 0; }
+        my_ok = ((uint64_t)my_row < (uint64_t)a.R && (uint32_t)my_pos < (uint32_t)a.n) ? 1 : 0;
+        if (!my_ok) { report(a.status, FS_DEV_BAD_ID); my_row = 0; my_pos = 0; }
     }
-    if (ballot(my_ok != 0) == ~0ull) gather_wave<LG, false, EXACT>(weights, units, out, my_row, my_pos, my_ok);
-    else gather_wave<LG, true, EXACT>(weights, units, out, my_row, my_pos, my_ok);   // ragged tail or a bad index
+    const int64_t stride = EXACT ? LG : a.units;
+    const u32x4* my_src = a.weights + my_row * stride;
+    if (MODE == kReplica && my_ok) {
+        const int32_t slot = a.slot_of_row[my_row];      // cacheable: popular rows repeat
+        if (slot >= 0) {
+            if (slot < a.k) my_src = a.store + (int64_t)slot * stride;
+            else { report(a.status, FS_DEV_BAD_ID); my_ok = 0; my_src = a.weights; my_pos = 0; }
+        }
+    }
+    if (ballot(my_ok != 0) == ~0ull) gather_wave<LG, false, EXACT>(a.units, a.out, my_src, my_pos, my_ok);
+    else gather_wave<LG, true, EXACT>(a.units, a.out, my_src, my_pos, my_ok);   // ragged tail or a bad index
 }
 
-template <int LG>
-static fs_status launch_gather(const void* weights, int64_t R, int units, const int64_t* rows,
-                               const int32_t* pos, int64_t m, void* out, int64_t n,
-                               hipStream_t stream, int32_t* status)
+template <int LG, int MODE>
+static fs_status launch_gather_lg(const GatherArgs& a, const char* name, hipStream_t stream)
 {
-    const int64_t grid = (m + kGatherRowsPerBlock - 1) / kGatherRowsPerBlock;
+    const int64_t grid = (a.m + kGatherRowsPerBlock - 1) / kGatherRowsPerBlock;
     if (grid > 0x7FFFFFFF) return FS_ERR_SIZE;
-    if (units == LG)
-        FS_LAUNCH("gather_rows", (gather_rows_kernel<LG, true>), dim3((unsigned)grid), dim3(kBlock), stream,
-                  static_cast<const u32x4*>(weights), R, units, rows, pos, m, static_cast<u32x4*>(out), n, status);
+    if (a.units == LG)
+        FS_LAUNCH(name, (gather_rows_kernel<LG, true, MODE>), dim3((unsigned)grid), dim3(kBlock), stream, a);
     else
-        FS_LAUNCH("gather_rows", (gather_rows_kernel<LG, false>), dim3((unsigned)grid), dim3(kBlock), stream,
-                  static_cast<const u32x4*>(weights), R, units, rows, pos, m, static_cast<u32x4*>(out), n, status);
+        FS_LAUNCH(name, (gather_rows_kernel<LG, false, MODE>), dim3((unsigned)grid), dim3(kBlock), stream, a);
     return FS_OK;
+}
+
+template <int MODE>
+static fs_status launch_gather(const GatherArgs& a, const char* name, hipStream_t s)
+{
+    if (a.units <= 1) return launch_gather_lg<1, MODE>(a, name, s);
+    if (a.units <= 2) return launch_gather_lg<2, MODE>(a, name, s);
+    if (a.units <= 4) return launch_gather_lg<4, MODE>(a, name, s);
+    if (a.units <= 8) return launch_gather_lg<8, MODE>(a, name, s);
+    if (a.units <= 16) return launch_gather_lg<16, MODE>(a, name, s);
+    if (a.units <= 32) return launch_gather_lg<32, MODE>(a, name, s);
+    return launch_gather_lg<64, MODE>(a, name, s);
+}
+
+// Host checks shared by the entry points; fills a.units.
+static fs_status check_rows(const void* src, const void* dst, int32_t D, fs_dtype dtype, GatherArgs* a)
+{
+    const int es = dtype_bytes(dtype);
+    if (es == 0) return FS_ERR_DTYPE;
+    if (D < 1) return FS_ERR_SIZE;
+    const int64_t row_bytes = (int64_t)D * es;
+    if (row_bytes % 16 != 0) return FS_ERR_ALIGN;
+    if ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 15) return FS_ERR_ALIGN;
+    a->units = (int)(row_bytes / 16);
+    return FS_OK;
+}
+
+// slot_of_row[r] = -1 for every row
+__global__ __launch_bounds__(kBlock) void replica_clear_kernel(int32_t* __restrict__ slot_of_row, int64_t R)
+{
+    const int64_t step = (int64_t)gridDim.x * kBlock;
+    for (int64_t r = (int64_t)blockIdx.x * kBlock + threadIdx.x; r < R; r += step) slot_of_row[r] = -1;
+}
+
+// slot_of_row[sel_rows[s]] = the smallest s that names the row (as unsigned, -1 is the largest value)
+__global__ __launch_bounds__(kBlock) void replica_slots_kernel(
+    const int64_t* __restrict__ sel_rows, int64_t k, const int64_t* __restrict__ k_dev, int64_t R,
+    int32_t* __restrict__ slot_of_row, int32_t* status)
+{
+    if (k_dev) { const int64_t kd = *k_dev; k = kd < k ? (kd < 0 ? 0 : kd) : k; }
+    const int64_t step = (int64_t)gridDim.x * kBlock;
+    for (int64_t s = (int64_t)blockIdx.x * kBlock + threadIdx.x; s < k; s += step) {
+        const int64_t r = sel_rows[s];
+        if ((uint64_t)r < (uint64_t)R) atomicMin(reinterpret_cast<uint32_t*>(slot_of_row) + r, (uint32_t)s);
+        else report(status, FS_DEV_BAD_ID);
+    }
 }
 
 }  // namespace fs
@@ -123,24 +197,100 @@ extern "C" fs_status fs_seq_gather_fwd(
     void* out, int64_t n, void* stream, int32_t* dev_status)
 {
     using namespace fs;
-    const int es = dtype_bytes(dtype);
-    if (es == 0) return FS_ERR_DTYPE;
+    GatherArgs a = {};
+    const fs_status st = check_rows(weights, out, D, dtype, &a);
+    if (st == FS_ERR_DTYPE) return st;
     if (R < 1 || n < 0 || n >= (1LL << 31) || D < 1 || j0 < 0 || j0 > j1) return FS_ERR_SIZE;
-    const int64_t m = j1 - j0;
-    if (m == 0) return FS_OK;
+    if (j1 == j0) return FS_OK;
     if (!weights || !rows || !pos || !out) return FS_ERR_NULL;
-    const int64_t row_bytes = (int64_t)D * es;
-    if (row_bytes % 16 != 0) return FS_ERR_ALIGN;
-    if ((reinterpret_cast<uintptr_t>(weights) | reinterpret_cast<uintptr_t>(out)) & 15) return FS_ERR_ALIGN;
-    const int units = (int)(row_bytes / 16);
+    if (st != FS_OK) return st;
+    a.weights = static_cast<const u32x4*>(weights); a.R = R;
+    a.rows = rows + j0; a.pos = pos + j0; a.m = j1 - j0;
+    a.out = static_cast<u32x4*>(out); a.n = n; a.status = dev_status;
+    return launch_gather<kBoth>(a, "gather_rows", static_cast<hipStream_t>(stream));
+}
+
+extern "C" fs_status fs_seq_gather_send(
+    const void* weights, int64_t R, int32_t D, fs_dtype dtype,
+    const int64_t* rows, int64_t j0, int64_t j1, void* send, void* stream, int32_t* dev_status)
+{
+    using namespace fs;
+    GatherArgs a = {};
+    const fs_status st = check_rows(weights, send, D, dtype, &a);
+    if (st == FS_ERR_DTYPE) return st;
+    if (R < 1 || D < 1 || j0 < 0 || j0 > j1 || j1 - j0 >= (1LL << 31)) return FS_ERR_SIZE;
+    if (j1 == j0) return FS_OK;
+    if (!weights || !rows || !send) return FS_ERR_NULL;
+    if (st != FS_OK) return st;
+    a.weights = static_cast<const u32x4*>(weights); a.R = R;
+    a.rows = rows + j0; a.m = j1 - j0;
+    a.out = static_cast<u32x4*>(send); a.n = a.m; a.status = dev_status;
+    return launch_gather<kToSend>(a, "gather_send", static_cast<hipStream_t>(stream));
+}
+
+extern "C" fs_status fs_seq_unbucketize(
+    const void* recv, int32_t D, fs_dtype dtype, const int32_t* pos, int64_t j0, int64_t j1,
+    void* out, int64_t n, void* stream, int32_t* dev_status)
+{
+    using namespace fs;
+    GatherArgs a = {};
+    const fs_status st = check_rows(recv, out, D, dtype, &a);
+    if (st == FS_ERR_DTYPE) return st;
+    if (n < 0 || n >= (1LL << 31) || D < 1 || j0 < 0 || j0 > j1) return FS_ERR_SIZE;
+    if (j1 == j0) return FS_OK;
+    if (!recv || !pos || !out) return FS_ERR_NULL;
+    if (st != FS_OK) return st;
+    a.weights = static_cast<const u32x4*>(recv); a.R = j1 - j0;
+    a.pos = pos + j0; a.m = j1 - j0;
+    a.out = static_cast<u32x4*>(out); a.n = n; a.status = dev_status;
+    return launch_gather<kFromRecv>(a, "unbucketize", static_cast<hipStream_t>(stream));
+}
+
+extern "C" fs_status fs_replica_build(
+    const void* weights, int64_t R, int32_t D, fs_dtype dtype,
+    const int64_t* sel_rows, int64_t k, const int64_t* num_selected,
+    void* store, int32_t* slot_of_row, void* stream, int32_t* dev_status)
+{
+    using namespace fs;
+    GatherArgs a = {};
+    const fs_status st = check_rows(weights, store, D, dtype, &a);
+    if (st == FS_ERR_DTYPE) return st;
+    if (R < 1 || D < 1 || k < 0 || k >= (1LL << 31)) return FS_ERR_SIZE;
+    if (!weights || !slot_of_row || (k > 0 && (!sel_rows || !store))) return FS_ERR_NULL;
+    if (st != FS_OK) return st;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const int64_t* r = rows + j0;
-    const int32_t* p = pos + j0;
-    if (units <= 1) return launch_gather<1>(weights, R, units, r, p, m, out, n, s, dev_status);
-    if (units <= 2) return launch_gather<2>(weights, R, units, r, p, m, out, n, s, dev_status);
-    if (units <= 4) return launch_gather<4>(weights, R, units, r, p, m, out, n, s, dev_status);
-    if (units <= 8) return launch_gather<8>(weights, R, units, r, p, m, out, n, s, dev_status);
-    if (units <= 16) return launch_gather<16>(weights, R, units, r, p, m, out, n, s, dev_status);
-    if (units <= 32) return launch_gather<32>(weights, R, units, r, p, m, out, n, s, dev_status);
-    return launch_gather<64>(weights, R, units, r, p, m, out, n, s, dev_status);
+    const int64_t clear_grid = (R + kBlock - 1) / kBlock;
+    FS_LAUNCH("replica_clear", replica_clear_kernel, dim3((unsigned)(clear_grid < 8192 ? clear_grid : 8192)),
+              dim3(kBlock), s, slot_of_row, R);
+    if (k == 0) return FS_OK;
+    const int64_t slot_grid = (k + kBlock - 1) / kBlock;
+    FS_LAUNCH("replica_slots", replica_slots_kernel, dim3((unsigned)(slot_grid < 8192 ? slot_grid : 8192)),
+              dim3(kBlock), s, sel_rows, k, num_selected, R, slot_of_row, dev_status);
+    a.weights = static_cast<const u32x4*>(weights); a.R = R;
+    a.rows = sel_rows; a.m = k; a.m_dev = num_selected;
+    a.out = static_cast<u32x4*>(store); a.n = k; a.status = dev_status;
+    return launch_gather<kToSend>(a, "replica_fill", s);
+}
+
+extern "C" fs_status fs_seq_gather_fwd_replica(
+    const void* weights, int64_t R, int32_t D, fs_dtype dtype,
+    const void* store, int64_t k, const int32_t* slot_of_row,
+    const int64_t* rows, const int32_t* pos, int64_t j0, int64_t j1,
+    void* out, int64_t n, void* stream, int32_t* dev_status)
+{
+    using namespace fs;
+    GatherArgs a = {};
+    const fs_status st = check_rows(weights, out, D, dtype, &a);
+    if (st == FS_ERR_DTYPE) return st;
+    if (R < 1 || n < 0 || n >= (1LL << 31) || D < 1 || j0 < 0 || j0 > j1 || k < 0 || k >= (1LL << 31))
+        return FS_ERR_SIZE;
+    if (j1 == j0) return FS_OK;
+    if (!weights || !rows || !pos || !out || !slot_of_row || (k > 0 && !store)) return FS_ERR_NULL;
+    if (st != FS_OK) return st;
+    if (reinterpret_cast<uintptr_t>(store) & 15) return FS_ERR_ALIGN;
+    a.weights = static_cast<const u32x4*>(weights); a.R = R;
+    a.rows = rows + j0; a.pos = pos + j0; a.m = j1 - j0;
+    a.out = static_cast<u32x4*>(out); a.n = n; a.status = dev_status;
+    a.store = static_cast<const u32x4*>(store); a.slot_of_row = slot_of_row; a.k = k;
+    return launch_gather<kReplica>(a, "gather_replica", static_cast<hipStream_t>(stream));
 }

@@ -79,8 +79,9 @@ def pins(o):
     assert rc == 0 and st == 0 and np.array_equal(pos, order) and np.array_equal(rows, g[order])
     assert np.array_equal(bo, np.concatenate([[0], np.cumsum(np.bincount(dest, minlength=U))]))
     # an owner that is valid for the sharded tier but not inside a group is a fault of the group tier
-    rc, st, bo2, rows2, pos2, tc2 = o.route_bucketize([0, 1], [0, 2], 1, 1, [0, 2], np.array([entry(1, 5), entry(1, 1)], np.uint32), 8, 4, 6)
-    assert st == o.BAD_PLACEMENT and bo2.tolist() == [0, 0, 0, 0, 0, 0, 1, 2, 2] and rows2.tolist() == [1, 0]
+    # (self in group 0, so that a mutant which accepts the owner still writes inside its arrays)
+    rc, st, bo2, rows2, pos2, tc2 = o.route_bucketize([0, 1], [0, 2], 1, 1, [0, 2], np.array([entry(1, 5), entry(1, 1)], np.uint32), 8, 4, 2)
+    assert st == o.BAD_PLACEMENT and bo2.tolist() == [0, 0, 1, 2, 2, 2, 2, 2, 2] and rows2.tolist() == [1, 0]
     # gather = take
     Wt = rng.standard_normal((T * E, 8)).astype(np.float32)
     out = np.zeros((n, 8), np.float32)
