@@ -22,6 +22,8 @@ F32, F16, BF16 = 0, 1, 2
 BAD_ID, BAD_OFFSETS, BAD_PLACEMENT, COUNT_OVERFLOW, UNIQUE_OVERFLOW, POS_ORDER = 1, 2, 4, 8, 16, 32
 PLAN_ACCUMULATE, PLAN_SELECT, PLAN_TAG, PLAN_ALLOW_ZERO = 1, 2, 4, 8
 BWD_TILE = 256
+CUT_CANDIDATES, CUT_A, CUT_B, CUT_C, CUT_FLEX, CUT_N_DP, CUT_N_FLEX, CUT_SUM_ALL, CUT_SUM_DP, CUT_SUM_FLEX = range(10)
+N_CUTS = 10
 
 
 def build(force: bool = False) -> str:
@@ -198,3 +200,26 @@ def plan_replication(ids, offsets, T: int, B: int, row_base, R: int, counts: np.
         ctypes.c_int64(R), _p(counts), ctypes.c_int32(flags), ctypes.c_int64(budget_bytes),
         ctypes.c_int64(bytes_per_row), _p(sel), ctypes.byref(nsel), _p(placement), ctypes.byref(status))
     return rc, status.value, sel[:int(nsel.value)]
+
+
+class TierParams(ctypes.Structure):
+    _fields_ = [("num_samples", ctypes.c_int64), ("B", ctypes.c_int64), ("U", ctypes.c_int32), ("W", ctypes.c_int32),
+                ("dp_multiplier", ctypes.c_int32), ("granule", ctypes.c_int32), ("a2a_global", ctypes.c_int64),
+                ("a2a_intra", ctypes.c_int64), ("ar_global", ctypes.c_int64), ("ar_cross", ctypes.c_int64)]
+
+
+def plan_tiers(counts: np.ndarray, params: dict, tiers: int, cap: Optional[int] = None,
+               placement: Optional[np.ndarray] = None):
+    """Returns (rc, cuts[N_CUTS] int64, sorted_rows[n_dp + n_flex]).  placement is tagged in place."""
+    assert counts.dtype == np.uint32
+    R = counts.shape[0]
+    cap = R if cap is None else cap
+    rows = np.full(max(cap, 0) + 16, -1, dtype=np.int64)
+    cuts = np.full(N_CUTS, -1, dtype=np.int64)
+    tp = TierParams(**params)
+    status = ctypes.c_int32(0)
+    rc = lib().oracle_plan_tiers(_p(counts), ctypes.c_int64(R), ctypes.byref(tp), ctypes.c_int32(tiers), _p(rows),
+                                 ctypes.c_int64(cap), _p(cuts), _p(placement), ctypes.byref(status))
+    k = int(min(max(cuts[CUT_N_DP] + cuts[CUT_N_FLEX], 0), max(cap, 0))) if rc == 0 else 0
+    assert np.all(rows[k:] == -1), "the oracle wrote past the rows it reports"
+    return rc, cuts, rows[:k]

@@ -13,7 +13,9 @@
  *
  * Pins (tests/test_oracle_*.py): stable argsort / bincount / take / put / lexsort /
  * fp64 add.at reductions, brute force over all placements on tiny inputs,
- * hand-computed rounding cases for the summation order, invariants.
+ * hand-computed rounding cases for the summation order, invariants; for the tier
+ * planner a whole-cost-curve brute force in exact fractions, closed forms and the
+ * tier sizes and coverage columns the paper prints for its four models.
  * No function here is "parity unpinned".
  */
 #include <stdint.h>
@@ -461,5 +463,125 @@ int oracle_plan_replication(
         *num_selected = k;
         free(cand);
     }
+    return OK;
+}
+
+/*
+ * Tier planner (Sections 4.2, 4.3, 4.5; cost terms from Tables 2 and 3 with
+ * E = 1 and L = p for one row, p = count / num_samples).
+ *
+ * Per row, in units of D * dtype bytes (memory) or D * dtype bytes per unit of
+ * bandwidth (communication):
+ *   replicated (DP) instead of row-wise (RW):
+ *     memory   (dp + B p) - (1/U + 2 B p)       = dp - 1/U - B p
+ *     traffic  1/ar_global - 2 B p / a2a_global   (all-reduce in the backward pass only,
+ *                                                  all-to-all in both passes)
+ *   Flex instead of RW:
+ *     memory   (dp/W + 2 B p) - (1/U + 2 B p)   = dp/W - 1/U
+ *     traffic  2 B p / a2a_intra + (1/W)/ar_cross - 2 B p / a2a_global
+ * Everything is kept exact: memory terms are multiplied by U * num_samples,
+ * traffic comparisons are cross-multiplied; 128-bit integers hold the products.
+ *
+ * Rows are walked in descending frequency order (ties: ascending row), rows
+ * that never appeared are not candidates.
+ *   A  rows before the first one whose DP memory term is positive
+ *   B  the longest prefix whose summed DP memory terms are <= 0
+ *   C  rows whose DP traffic term is <= 0
+ *   FLEX  rows whose Flex traffic term is <= 0
+ * two tiers:   DP = first B rows (rounded down to the granule).
+ * three tiers: DP = first A rows (rounded down); then Flex rows one by one
+ *   while the memory saved by the DP rows pays for them and the row is
+ *   inside FLEX; the Flex count is rounded down to the granule.
+ */
+typedef struct {
+    int64_t num_samples;
+    int64_t B;
+    int32_t U, W, dp_multiplier, granule;
+    int64_t a2a_global, a2a_intra, ar_global, ar_cross;
+} tier_params_t;
+
+enum { CUT_CANDIDATES = 0, CUT_A = 1, CUT_B = 2, CUT_C = 3, CUT_FLEX = 4, CUT_N_DP = 5, CUT_N_FLEX = 6,
+       CUT_SUM_ALL = 7, CUT_SUM_DP = 8, CUT_SUM_FLEX = 9, N_CUTS = 10 };
+
+typedef __int128 wide_t;
+
+int oracle_plan_tiers(
+    const uint32_t* counts, int64_t R, const tier_params_t* p, int32_t tiers,
+    int64_t* sorted_rows, int64_t cap, int64_t* cuts, uint32_t* placement, int32_t* status)
+{
+    (void)status;
+    if (!p || !cuts) return ERR_NULL;
+    if (R < 1 || R >= 4294967295LL || cap < 0) return ERR_SIZE;
+    if (tiers != 2 && tiers != 3) return ERR_CONFIG;
+    if (p->num_samples < 1 || p->num_samples >= ((int64_t)1 << 40)) return ERR_CONFIG;
+    if (p->B < 1 || p->B >= ((int64_t)1 << 31)) return ERR_CONFIG;
+    if (p->U < 1 || p->U > 4096 || p->W < 1 || p->U % p->W != 0) return ERR_CONFIG;
+    if (p->dp_multiplier < 1 || p->dp_multiplier > 1024) return ERR_CONFIG;
+    if (p->granule < 1 || p->granule > (1 << 20)) return ERR_CONFIG;
+    const int64_t bw_max = (int64_t)1 << 20;
+    if (p->a2a_global < 1 || p->a2a_global >= bw_max || p->a2a_intra < 1 || p->a2a_intra >= bw_max ||
+        p->ar_global < 1 || p->ar_global >= bw_max || p->ar_cross < 1 || p->ar_cross >= bw_max)
+        return ERR_CONFIG;
+    if (!counts) return ERR_NULL;
+    if (cap > 0 && !sorted_rows) return ERR_NULL;
+
+    cand_t* cand = (cand_t*)malloc(sizeof(cand_t) * (size_t)R);
+    int64_t nc = 0;
+    for (int64_t g = 0; g < R; ++g)
+        if (counts[g] > 0) { cand[nc].count = counts[g]; cand[nc].g = g; ++nc; }
+    qsort(cand, (size_t)nc, sizeof(cand_t), by_count_desc_then_row);
+
+    const wide_t S = p->num_samples, B = p->B, U = p->U, W = p->W, dp = p->dp_multiplier;
+    const wide_t static_term = (dp * U - 1) * S;          /* (dp - 1/U) * U * S */
+    int64_t kA = nc, kB = 0, kC = 0, kF = 0;
+    int seenA = 0;
+    wide_t cum = 0;
+    for (int64_t i = 0; i < nc; ++i) {
+        const wide_t c = cand[i].count;
+        const wide_t mem = static_term - U * B * c;       /* (dp - 1/U - B p) * U * S */
+        if (!seenA && mem > 0) { kA = i; seenA = 1; }
+        cum += mem;
+        if (cum <= 0) kB = i + 1;
+        /* 1/ar_global <= 2 B p / a2a_global */
+        if ((wide_t)p->a2a_global * S <= 2 * B * c * (wide_t)p->ar_global) kC = i + 1;
+        /* 2 B p / a2a_intra + 1/(W ar_cross) <= 2 B p / a2a_global */
+        if (p->a2a_intra > p->a2a_global &&
+            S * (wide_t)p->a2a_global * (wide_t)p->a2a_intra <=
+                2 * B * c * (wide_t)(p->a2a_intra - p->a2a_global) * W * (wide_t)p->ar_cross)
+            kF = i + 1;
+    }
+
+    const int64_t gran = p->granule;
+    int64_t n_dp, n_flex = 0;
+    if (tiers == 2) {
+        n_dp = kB / gran * gran;
+    } else {
+        n_dp = kA / gran * gran;
+        wide_t saved = 0;
+        for (int64_t i = 0; i < n_dp; ++i) saved -= static_term - U * B * (wide_t)cand[i].count;
+        const wide_t flex_cost = (dp * (U / W) - 1) * S;  /* (dp/W - 1/U) * U * S */
+        wide_t spent = 0;
+        int64_t i = n_dp;
+        while (i < nc && i < kF && spent + flex_cost <= saved) { spent += flex_cost; ++i; }
+        n_flex = (i - n_dp) / gran * gran;
+    }
+
+    int64_t sum_all = 0, sum_dp = 0, sum_flex = 0;
+    for (int64_t i = 0; i < nc; ++i) {
+        sum_all += cand[i].count;
+        if (i < n_dp) sum_dp += cand[i].count;
+        else if (i < n_dp + n_flex) sum_flex += cand[i].count;
+    }
+    cuts[CUT_CANDIDATES] = nc; cuts[CUT_A] = kA; cuts[CUT_B] = kB; cuts[CUT_C] = kC; cuts[CUT_FLEX] = kF;
+    cuts[CUT_N_DP] = n_dp; cuts[CUT_N_FLEX] = n_flex;
+    cuts[CUT_SUM_ALL] = sum_all; cuts[CUT_SUM_DP] = sum_dp; cuts[CUT_SUM_FLEX] = sum_flex;
+
+    for (int64_t i = 0; i < n_dp + n_flex && i < cap; ++i) sorted_rows[i] = cand[i].g;
+    if (placement) {
+        for (int64_t i = 0; i < n_dp; ++i) placement[cand[i].g] &= 0x3FFFFFFFu;
+        for (int64_t i = n_dp; i < n_dp + n_flex; ++i)
+            placement[cand[i].g] = 0x40000000u | (uint32_t)((i - n_dp) % p->W);
+    }
+    free(cand);
     return OK;
 }

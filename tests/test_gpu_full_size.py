@@ -46,7 +46,7 @@ def _free():
     torch.cuda.empty_cache()
 
 
-def _run_config(G, cfg, check_atomic=True, bwd_rows_sample=None):
+def _run_config(G, cfg, check_atomic=True, bwd_rows_sample=None, exchange=True):
     import paper_2301_02959_amd as fs
     dev = G.DEV
     _progress(f"[{cfg.name}] generating")
@@ -96,6 +96,52 @@ def _run_config(G, cfg, check_atomic=True, bwd_rows_sample=None):
     assert oracle.seq_gather_fwd(w_s, np.arange(len(samp)), np.arange(len(samp), dtype=np.int32), 0, len(samp), ref,
                                  dtype=G.oracle_dtype(cfg.dtype)) == (0, 0)
     assert np.array_equal(fs_inputs.as_numpy_bits(out[samp_t]).view(np.uint8), ref.view(np.uint8))
+    # ---- the same lookups through the exchange halves and through a replica store of the rows the
+    # plan selects: each must reproduce `out` bit for bit (out itself was checked above); the send buffer
+    # is checked against the oracle on the sampled lookups
+    need = n * cfg.row_bytes + R * 8
+    if exchange and torch.cuda.mem_get_info()[0] > 1.2 * need:
+        _progress(f"[{cfg.name}] exchange halves + replica store")
+        send = torch.empty(n, D, dtype=cfg.torch_dtype, device=dev)
+        fs.fs_seq_gather_send(weights, rows, 0, n, send, st_t)
+        inv_pos = torch.empty(n, dtype=torch.int64, device=dev)
+        inv_pos[pos.long()] = torch.arange(n, device=dev)                  # lookup i sits at j = inv_pos[i]
+        j_s = inv_pos[samp_t].cpu().numpy()
+        ref_send = np.zeros_like(w_s)
+        assert oracle.seq_gather_send(w_s, np.arange(len(samp)), 0, len(samp), ref_send,
+                                      dtype=G.oracle_dtype(cfg.dtype)) == (0, 0)
+        assert np.array_equal(fs_inputs.as_numpy_bits(send[torch.as_tensor(j_s, device=dev)]).view(np.uint8),
+                              ref_send.view(np.uint8))
+        del inv_pos
+        out2 = torch.zeros(n, D, dtype=cfg.torch_dtype, device=dev)
+        fs.fs_seq_unbucketize(send, pos, 0, n, out2, st_t)
+        torch.cuda.synchronize()
+        for lo in range(0, n, step):
+            hi = min(n, lo + step)
+            assert torch.equal(out[lo:hi].view(ibits), out2[lo:hi].view(ibits)), (lo, hi)
+        del send
+        counts = torch.zeros(R, dtype=torch.int32, device=dev)
+        k_cap = max(1, int(0.002 * R))
+        sel = torch.zeros(k_cap, dtype=torch.int64, device=dev)
+        nsel = torch.zeros(1, dtype=torch.int64, device=dev)
+        fs.fs_plan_replication(ids, offsets, cfg.T, cfg.B, row_base, n, R, counts,
+                               fs.FS_PLAN_ACCUMULATE | fs.FS_PLAN_SELECT, k_cap * cfg.row_bytes, cfg.row_bytes,
+                               sel, nsel, None, st_t)
+        store = torch.zeros(k_cap, D, dtype=cfg.torch_dtype, device=dev)
+        slots = torch.zeros(R, dtype=torch.int32, device=dev)
+        fs.fs_replica_build(weights, sel, k_cap, nsel, store, slots, st_t)
+        out2.zero_()
+        fs.fs_seq_gather_fwd_replica(weights, store, k_cap, slots, rows, pos, 0, n, out2, st_t)
+        torch.cuda.synchronize()
+        assert int(st_t.item()) == 0
+        k = int(nsel.item())
+        assert k > 0 and int((slots >= 0).sum().item()) == k
+        assert torch.equal(store[:k].view(ibits), weights[sel[:k]].view(ibits))
+        assert torch.equal(slots[sel[:k]].long(), torch.arange(k, device=dev))
+        for lo in range(0, n, step):
+            hi = min(n, lo + step)
+            assert torch.equal(out[lo:hi].view(ibits), out2[lo:hi].view(ibits)), (lo, hi)
+        del out2, counts, sel, store, slots
     del weights, out, g_all
     _free()
 

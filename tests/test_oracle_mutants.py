@@ -37,12 +37,25 @@ MUTANTS = {
     "tie_break_descending": ("return x->g < y->g ? -1 : (x->g > y->g ? 1 : 0);\n}\n\n/*\n * Replication plan", "return x->g > y->g ? -1 : (x->g < y->g ? 1 : 0);\n}\n\n/*\n * Replication plan"),
     "budget_rounds_up": ("int64_t cap = budget_bytes / bytes_per_row;", "int64_t cap = (budget_bytes + bytes_per_row - 1) / bytes_per_row;"),
     "zeros_selected": ("if (counts[g] > 0 || (flags & PLAN_ALLOW_ZERO))", "if (1)"),
-    "tag_sets_tier2": ("placement[cand[i].g] &= 0x3FFFFFFFu;", "placement[cand[i].g] = (placement[cand[i].g] & 0x3FFFFFFFu) | 0x80000000u;"),
+    "tag_sets_tier2": ("for (int64_t i = 0; i < k; ++i) placement[cand[i].g] &= 0x3FFFFFFFu;", "for (int64_t i = 0; i < k; ++i) placement[cand[i].g] = (placement[cand[i].g] & 0x3FFFFFFFu) | 0x80000000u;"),
+    "tiers_dp_tag_keeps_tier": ("for (int64_t i = 0; i < n_dp; ++i) placement[cand[i].g] &= 0x3FFFFFFFu;", "for (int64_t i = 0; i < n_dp; ++i) placement[cand[i].g] &= 0xBFFFFFFFu;"),
     "send_indexed_by_j_not_offset": ("memcpy((char*)send + (size_t)(j - j0) * row_bytes,", "memcpy((char*)send + (size_t)(j - j0 > 0 ? j - j0 - 1 : 0) * row_bytes,"),
     "unbucketize_reads_by_pos": ("(const char*)recv + (size_t)(j - j0) * row_bytes, row_bytes);", "(const char*)recv + (size_t)(p % (j1 - j0)) * row_bytes, row_bytes);"),
     "replica_last_slot_wins": ("if (slot_of_row[r] < 0) slot_of_row[r] = (int32_t)s;", "slot_of_row[r] = (int32_t)s;"),
     "replica_store_ignored": ("else if (s < k) from = (const char*)store + (size_t)s * row_bytes;", "else if (s < k) from = (const char*)weights + (size_t)r * row_bytes;"),
     "replica_slot_is_row": ("else if (s < k) from = (const char*)store + (size_t)s * row_bytes;", "else if (s < k) from = (const char*)store + (size_t)(r % k) * row_bytes;"),
+    "tiers_dynamic_saving_doubled": ("const wide_t mem = static_term - U * B * c;", "const wide_t mem = static_term - 2 * U * B * c;"),
+    "tiers_saved_without_dynamic": ("saved -= static_term - U * B * (wide_t)cand[i].count;", "saved -= static_term - U * (wide_t)cand[i].count;"),
+    "tiers_static_without_shard": ("const wide_t static_term = (dp * U - 1) * S;", "const wide_t static_term = (dp * U) * S;"),
+    "tiers_A_excludes_neutral": ("if (!seenA && mem > 0) { kA = i; seenA = 1; }", "if (!seenA && mem >= 0) { kA = i; seenA = 1; }"),
+    "tiers_B_strict": ("if (cum <= 0) kB = i + 1;", "if (cum < 0) kB = i + 1;"),
+    "tiers_traffic_one_pass": ("if ((wide_t)p->a2a_global * S <= 2 * B * c * (wide_t)p->ar_global) kC = i + 1;", "if ((wide_t)p->a2a_global * S <= B * c * (wide_t)p->ar_global) kC = i + 1;"),
+    "tiers_flex_cost_whole_table": ("const wide_t flex_cost = (dp * (U / W) - 1) * S;", "const wide_t flex_cost = (dp * U - 1) * S;"),
+    "tiers_flex_ignores_traffic": ("while (i < nc && i < kF && spent + flex_cost <= saved)", "while (i < nc && spent + flex_cost <= saved)"),
+    "tiers_granule_rounds_up": ("n_dp = kA / gran * gran;", "n_dp = (kA + gran - 1) / gran * gran;"),
+    "tiers_flex_owner_over_all": ("(uint32_t)((i - n_dp) % p->W);", "(uint32_t)((i - n_dp) % p->U);"),
+    "tiers_flex_allreduce_whole": ("2 * B * c * (wide_t)(p->a2a_intra - p->a2a_global) * W * (wide_t)p->ar_cross)", "2 * B * c * (wide_t)(p->a2a_intra - p->a2a_global) * (wide_t)p->ar_cross)"),
+    "tiers_flex_overspends": ("spent + flex_cost <= saved) { spent += flex_cost; ++i; }", "spent <= saved) { spent += flex_cost; ++i; }"),
 }
 # a mutant that changes nothing observable would be a bad test of the tests: keep only real ones
 MUTANTS.pop("fold_right_to_left")
@@ -149,6 +162,14 @@ def pins(o):
     out_r = np.zeros((6, 8), np.float32)
     assert o.seq_gather_fwd_replica(Wt, mark, slots, look, np.arange(6, dtype=np.int32), 0, 6, out_r) == (0, 0)
     assert np.array_equal(out_r, np.stack([mark[1], Wt[5], mark[3], mark[0], mark[4], Wt[6]]))
+    # tier planner: hand cases, closed forms, the whole-curve brute force
+    import test_oracle_tiers as tt
+    tt.test_three_tier_hand_case()
+    tt.test_tags_and_rounding()
+    tt.test_closed_forms()
+    for seed in range(6):
+        tt.test_against_whole_curve_brute_force(seed, 2)
+        tt.test_against_whole_curve_brute_force(seed, 3)
 
 
 def test_pins_accept_the_real_oracle():
