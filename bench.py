@@ -265,6 +265,25 @@ def main():
                         for k, v in sorted(xrec.items())}}
         del send, store, slots
 
+        # the tier planner on the counts accumulated so far (one batch profiled steps+warmup times, so the
+        # sample count is B times that); bandwidth ratios as in the paper's Figure 3 (all-reduce = 3 x all-to-all)
+        tp = dict(num_samples=B * (args.steps + args.warmup), B=B, U=U, W=W, dp_multiplier=6, granule=32,
+                  a2a_global=1, a2a_intra=6, ar_global=3, ar_cross=2)
+        cuts = torch.zeros(fs.FS_TIER_CUTS, dtype=torch.int64, device=dev)
+        tier_rows = torch.empty(R, dtype=torch.int64, device=dev)
+        for tiers in (3, 3, 2):
+            fs.fs_prof_begin(64)
+            fs.fs_plan_tiers(counts, R, tp, tiers, tier_rows, R, cuts, None, status)
+            torch.cuda.synchronize()
+            trec = fs.fs_prof_end(64)
+        c = [int(x) for x in cuts.tolist()]
+        result["tier_plan"] = {
+            "ms": round(sum(ms for _, ms in trec), 4),
+            "kernels_ms": {k: round(sum(ms for nm, ms in trec if nm == k), 4) for k in sorted({nm for nm, _ in trec})},
+            "params": tp, "two_tier": {"candidates": c[0], "A": c[1], "B": c[2], "C": c[3], "flex_breakpoint": c[4],
+                                       "n_dp": c[5], "dp_share": round(c[8] / max(c[7], 1), 4)}}
+        del tier_rows
+
     # ---------------------------------------------------------------- CPU oracle on a bounded sample
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(args, cfg, ids, offsets, placement, weights, grad_out)

@@ -293,6 +293,70 @@ fs_status fs_plan_replication(
     void* workspace, size_t* workspace_bytes /* host */,
     void* stream, int32_t* dev_status);
 
+/*
+ * fs_plan_tiers -- the tier planner (Section 4.2: per-row costs are the cost
+ * tables of Section 3.2 with E = 1 and L = p, and the row probability at which
+ * two strategies cost the same is a breakpoint; Section 4.3: rows are walked in
+ * descending frequency order and the points A, B, C of the cost curve are where
+ * the walk crosses the breakpoints; Section 4.5: three tiers).
+ *
+ * p_i = counts[i] / num_samples.  Per row, in units of D * sizeof(dtype):
+ *   replicated (DP) instead of row-wise:  memory  dp_multiplier - 1/U - B p
+ *                                         traffic 1/ar_global - 2 B p / a2a_global
+ *   Flex instead of row-wise:             memory  dp_multiplier/W - 1/U
+ *                                         traffic 2 B p / a2a_intra + 1/(W ar_cross) - 2 B p / a2a_global
+ * Candidates are the rows with counts > 0 in (count desc, row asc) order, K of
+ * them.  All comparisons are exact (integers, cross-multiplied).
+ *   cuts[FS_CUT_CANDIDATES] = K
+ *   cuts[FS_CUT_A]     rows whose DP memory term is <= 0            (most memory saved)
+ *   cuts[FS_CUT_B]     longest prefix whose DP memory terms sum to <= 0 (memory neutral)
+ *   cuts[FS_CUT_C]     rows whose DP traffic term is <= 0           (least traffic)
+ *   cuts[FS_CUT_FLEX]  rows whose Flex traffic term is <= 0
+ *   tiers == 2:  n_dp = B rounded down to a multiple of granule, n_flex = 0
+ *   tiers == 3:  n_dp = A rounded down; n_flex = the most rows after them that
+ *                the memory saved by the n_dp rows pays for, not beyond
+ *                cuts[FS_CUT_FLEX], rounded down to a multiple of granule
+ *   cuts[FS_CUT_N_DP], cuts[FS_CUT_N_FLEX]; cuts[FS_CUT_SUM_ALL / _DP / _FLEX] =
+ *   the counts summed over all candidates / the DP tier / the Flex tier (their
+ *   ratios are the predicted share of lookups each tier serves).
+ * sorted_rows[i], i < min(cap, n_dp + n_flex): the chosen rows in that order
+ * (may be NULL with cap = 0).  placement (may be NULL): the n_dp rows get tier
+ * 0 (owner bits kept), Flex row number j gets tier 1 with owner j % W; other
+ * entries are left as they are.  cuts is device memory, FS_TIER_CUTS entries.
+ *
+ * Host faults: NULL; R < 1, R >= 2^32 - 1, cap < 0 (FS_ERR_SIZE); tiers not 2
+ * or 3, num_samples outside [1, 2^40), B outside [1, 2^31), U outside
+ * [1, FS_MAX_BUCKETS], W < 1, U % W != 0, dp_multiplier outside [1, 1024],
+ * granule outside [1, 2^20], a bandwidth outside [1, 2^20) (FS_ERR_CONFIG);
+ * workspace as everywhere.
+ */
+typedef struct fs_tier_params {
+    int64_t num_samples;   /* profiled samples behind counts (per table) */
+    int64_t B;             /* local batch size per GPU */
+    int32_t U, W;          /* GPUs, GPUs per group */
+    int32_t dp_multiplier; /* static memory of a replicated row in row sizes (Table 2: 6) */
+    int32_t granule;       /* tier sizes are multiples of this */
+    int64_t a2a_global, a2a_intra, ar_global, ar_cross;   /* bandwidths, one common unit */
+} fs_tier_params;
+
+#define FS_CUT_CANDIDATES 0
+#define FS_CUT_A 1
+#define FS_CUT_B 2
+#define FS_CUT_C 3
+#define FS_CUT_FLEX 4
+#define FS_CUT_N_DP 5
+#define FS_CUT_N_FLEX 6
+#define FS_CUT_SUM_ALL 7
+#define FS_CUT_SUM_DP 8
+#define FS_CUT_SUM_FLEX 9
+#define FS_TIER_CUTS 10
+
+fs_status fs_plan_tiers(
+    const uint32_t* counts, int64_t R, const fs_tier_params* params /* host */, int32_t tiers,
+    int64_t* sorted_rows, int64_t cap, int64_t* cuts, uint32_t* placement,
+    void* workspace, size_t* workspace_bytes /* host */,
+    void* stream, int32_t* dev_status);
+
 /* ---- helpers ---------------------------------------------------------- */
 
 /* Library version, major * 1000 + minor. */

@@ -21,13 +21,16 @@ FS_DEV_BAD_ID, FS_DEV_BAD_OFFSETS, FS_DEV_BAD_PLACEMENT = 1, 2, 4
 FS_DEV_COUNT_OVERFLOW, FS_DEV_UNIQUE_OVERFLOW, FS_DEV_POS_ORDER = 8, 16, 32
 FS_PLAN_ACCUMULATE, FS_PLAN_SELECT, FS_PLAN_TAG, FS_PLAN_ALLOW_ZERO = 1, 2, 4, 8
 FS_BWD_TILE = 256
+(FS_CUT_CANDIDATES, FS_CUT_A, FS_CUT_B, FS_CUT_C, FS_CUT_FLEX, FS_CUT_N_DP, FS_CUT_N_FLEX, FS_CUT_SUM_ALL,
+ FS_CUT_SUM_DP, FS_CUT_SUM_FLEX) = range(10)
+FS_TIER_CUTS = 10
 FS_MAX_BUCKETS = 4096
 
 STATUS_NAMES = {0: "FS_OK", 1: "FS_ERR_NULL", 2: "FS_ERR_SIZE", 3: "FS_ERR_DTYPE", 4: "FS_ERR_ALIGN",
                 5: "FS_ERR_WORKSPACE", 6: "FS_ERR_CONFIG", 7: "FS_ERR_DEVICE"}
 
 EXPORTS = ["fs_route_bucketize", "fs_seq_gather_fwd", "fs_seq_grad_bwd", "fs_plan_replication",
-           "fs_seq_gather_send", "fs_seq_unbucketize", "fs_replica_build", "fs_seq_gather_fwd_replica",
+           "fs_seq_gather_send", "fs_seq_unbucketize", "fs_replica_build", "fs_seq_gather_fwd_replica", "fs_plan_tiers",
            "fs_util_copy", "fs_version", "fs_bwd_tile", "fs_prof_begin", "fs_prof_end"]
 
 _DTYPES = {torch.float32: FS_F32, torch.float16: FS_F16, torch.bfloat16: FS_BF16}
@@ -52,7 +55,7 @@ def lib() -> ctypes.CDLL:
         _lib = ctypes.CDLL(LIB_PATH)
         for name in ("fs_route_bucketize", "fs_seq_gather_fwd", "fs_seq_grad_bwd", "fs_plan_replication",
                      "fs_seq_gather_send", "fs_seq_unbucketize", "fs_replica_build",
-                     "fs_seq_gather_fwd_replica", "fs_prof_begin", "fs_util_copy"):
+                     "fs_seq_gather_fwd_replica", "fs_plan_tiers", "fs_prof_begin", "fs_util_copy"):
             getattr(_lib, name).restype = ctypes.c_int
         _lib.fs_version.restype = ctypes.c_int32
         _lib.fs_bwd_tile.restype = ctypes.c_int32
@@ -225,6 +228,33 @@ def fs_plan_replication(ids, offsets, T: int, B: int, row_base, n: int, R: int, 
     else:
         size = ctypes.c_size_t(workspace.numel())
     return _check("fs_plan_replication", call(_ptr(workspace), ctypes.byref(size)), raise_on_error)
+
+
+class TierParams(ctypes.Structure):
+    """fs_tier_params of the C header, field for field."""
+    _fields_ = [("num_samples", ctypes.c_int64), ("B", ctypes.c_int64), ("U", ctypes.c_int32), ("W", ctypes.c_int32),
+                ("dp_multiplier", ctypes.c_int32), ("granule", ctypes.c_int32), ("a2a_global", ctypes.c_int64),
+                ("a2a_intra", ctypes.c_int64), ("ar_global", ctypes.c_int64), ("ar_cross", ctypes.c_int64)]
+
+
+def fs_plan_tiers(counts, R: int, params: dict, tiers: int, sorted_rows, cap: int, cuts, placement=None,
+                  dev_status=None, workspace: Optional[torch.Tensor] = None, raise_on_error: bool = True) -> int:
+    L = lib()
+    tp = TierParams(**params)
+
+    def call(ws_ptr, ws_size_ref):
+        return L.fs_plan_tiers(_ptr(counts), ctypes.c_int64(R), ctypes.byref(tp), ctypes.c_int32(tiers),
+                               _ptr(sorted_rows), ctypes.c_int64(cap), _ptr(cuts), _ptr(placement),
+                               ws_ptr, ws_size_ref, _stream(), _ptr(dev_status))
+
+    if workspace is None:
+        device = next((t.device for t in (counts, cuts, sorted_rows) if t is not None), "cuda")
+        workspace, size, code = _workspace(call, device)
+        if code != 0:
+            return _check("fs_plan_tiers", code, raise_on_error)
+    else:
+        size = ctypes.c_size_t(workspace.numel())
+    return _check("fs_plan_tiers", call(_ptr(workspace), ctypes.byref(size)), raise_on_error)
 
 
 def fs_util_copy(dst, src, nbytes: Optional[int] = None, raise_on_error: bool = True) -> int:

@@ -9,6 +9,9 @@
 //             a stable radix sort by key then yields (count desc, row asc); plan_emit writes the
 //             first k = min(budget / bytes_per_row, #candidates) rows, k, and the tier-0 tags.
 // The candidate count lives in device memory; the sort kernels read it there.
+//
+// fs_plan_tiers (further down) reuses the compaction and the sort and cuts the sorted rows into
+// tiers at the breakpoints of the per-row cost model.
 #include "fs_common.h"
 #include "radix_sort.h"
 
@@ -211,6 +214,207 @@ __global__ __launch_bounds__(kBlock) void plan_emit_kernel(
 
 __global__ void plan_set_flag_kernel(int32_t* flag) { *flag = 1; }
 
+// ---- tier planner -----------------------------------------------------------
+// After the same compaction and sort, rows stand in descending frequency order with
+// key = ~count.  The breakpoints are thresholds on the count (found on the host from the
+// parameters), so points A, C and the Flex breakpoint are partition points of the sorted keys;
+// point B and the Flex budget need sums of counts over prefixes, which come from one pass of
+// per-tile sums plus a scan of those.  One wave then finds every cut with 64-way searches.
+constexpr int kSumTile = 4096;                // sorted counts per tile sum
+
+typedef unsigned __int128 u128;
+typedef __int128 i128;
+
+struct TierConsts {
+    uint64_t thr_a, thr_c, thr_f;             // smallest count at or above the breakpoint (2^63: none)
+    int64_t static_term;                      // (dp U - 1) S
+    int64_t dyn_factor;                       // U B
+    int64_t flex_cost;                        // (dp U / W - 1) S
+    int32_t granule, W, tiers;
+};
+
+__global__ __launch_bounds__(kBlock) void tiers_tile_sums_kernel(
+    const uint32_t* __restrict__ keys, const int64_t* __restrict__ num_candidates, uint64_t* __restrict__ tile_sum)
+{
+    __shared__ uint64_t part[kWavesPerBlock];
+    const int64_t K = *num_candidates;
+    const int64_t base = (int64_t)blockIdx.x * kSumTile;
+    uint64_t sum = 0;
+    for (int i = threadIdx.x; i < kSumTile; i += kBlock) {
+        const int64_t k = base + i;
+        if (k < K) sum += (uint32_t)~keys[k];
+    }
+    for (int off = 32; off > 0; off >>= 1) sum += __shfl_down(sum, off);
+    if (lane_id() == 0) part[wave_id()] = sum;
+    __syncthreads();
+    if (threadIdx.x == 0) tile_sum[blockIdx.x] = part[0] + part[1] + part[2] + part[3];
+}
+
+// tile_sum[t] -> sum of the tiles before t, tile_sum[tiles] = the grand total.  One block.
+__global__ __launch_bounds__(kScanBlock) void tiers_scan_sums_kernel(uint64_t* __restrict__ tile_sum, int64_t tiles)
+{
+    __shared__ uint64_t wave_tot[kScanBlock / kWave];
+    const int lane = lane_id();
+    const int w = wave_id();
+    uint64_t carry = 0;
+    for (int64_t base = 0; base < tiles; base += kScanBlock) {
+        const int64_t k = base + threadIdx.x;
+        const uint64_t v = k < tiles ? tile_sum[k] : 0;
+        uint64_t incl = v;
+        for (int off = 1; off < kWave; off <<= 1) {
+            const uint64_t up = __shfl_up(incl, off);
+            if (lane >= off) incl += up;
+        }
+        __syncthreads();                       // wave_tot of the previous round has been read
+        if (lane == kWave - 1) wave_tot[w] = incl;
+        __syncthreads();
+        uint64_t before = 0, all = 0;
+        for (int q = 0; q < kScanBlock / kWave; ++q) {
+            const uint64_t t = wave_tot[q];
+            if (q < w) before += t;
+            all += t;
+        }
+        if (k < tiles) tile_sum[k] = carry + before + incl - v;
+        carry += all;
+    }
+    if (threadIdx.x == 0) tile_sum[tiles] = carry;
+}
+
+// First index in [lo, hi) at which pred turns false (pred holds on a prefix of the range); hi if it
+// never does.  Every lane of the wave calls it with the same bounds; 64 probes per round.
+template <typename Pred>
+__device__ __forceinline__ int64_t wave_partition_point(int64_t lo, int64_t hi, Pred pred)
+{
+    const int lane = lane_id();
+    while (lo < hi) {
+        const int64_t step = (hi - lo + kWave - 1) / kWave;
+        const int64_t probe = lo + (int64_t)(lane + 1) * step - 1;      // last index of this lane's piece
+        const bool holds = probe < hi ? pred(probe) : false;
+        const int pieces = __popcll(ballot(holds));                      // whole pieces on which pred holds
+        const int64_t new_lo = lo + (int64_t)pieces * step;
+        const int64_t first_false_probe = new_lo + step - 1;
+        hi = first_false_probe < hi ? first_false_probe : hi;
+        lo = new_lo < hi ? new_lo : hi;
+    }
+    return lo;
+}
+
+// Sum of the first k sorted counts: the scanned tile sums plus a partial tile, summed by the wave.
+__device__ __forceinline__ uint64_t prefix_count(const uint32_t* __restrict__ keys,
+                                                 const uint64_t* __restrict__ tile_sum, int64_t k)
+{
+    const int64_t t = k / kSumTile;
+    uint64_t part = 0;
+    for (int64_t i = t * kSumTile + lane_id(); i < k; i += kWave) part += (uint32_t)~keys[i];
+    for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off);
+    return tile_sum[t] + part;
+}
+
+// Summed DP memory terms of the first k rows, times U * S:  k (dp U - 1) S - U B P(k).
+__device__ __forceinline__ i128 cum_memory(const TierConsts& c, int64_t k, uint64_t prefix)
+{
+    return (i128)k * (i128)c.static_term - (i128)c.dyn_factor * (i128)prefix;
+}
+
+__global__ __launch_bounds__(kWave) void tiers_cuts_kernel(
+    const uint32_t* __restrict__ keys, const int64_t* __restrict__ num_candidates,
+    const uint64_t* __restrict__ tile_sum, const TierConsts c, int64_t* __restrict__ cuts)
+{
+    const int lane = lane_id();
+    const int64_t K = *num_candidates;
+    const int64_t tiles = (K + kSumTile - 1) / kSumTile;
+    auto at_least = [&](uint64_t thr) {
+        return wave_partition_point(0, K, [&](int64_t i) { return (uint64_t)(uint32_t)~keys[i] >= thr; });
+    };
+    const int64_t kA = at_least(c.thr_a);
+    const int64_t kC = at_least(c.thr_c);
+    const int64_t kF = at_least(c.thr_f);
+
+    // point B: the summed terms are <= 0 on a prefix of k = 0 .. K.  Tile boundaries first
+    // (k_t = min(t * tile, K), P(k_t) = tile_sum[t]), then the rows of the one tile that holds it.
+    const int64_t t_false = wave_partition_point(0, tiles + 1, [&](int64_t t) {
+        const int64_t k = t * kSumTile < K ? t * kSumTile : K;
+        return cum_memory(c, k, tile_sum[t]) <= 0;
+    });
+    int64_t kB;
+    if (t_false > tiles) {
+        kB = K;
+    } else {
+        const int64_t t0 = t_false - 1;                                  // boundary t0 holds, t0 + 1 does not
+        const int64_t first = t0 * kSumTile;
+        constexpr int kPer = kSumTile / kWave;                           // consecutive rows per lane
+        uint64_t mine = 0;
+        for (int q = 0; q < kPer; ++q) {
+            const int64_t i = first + (int64_t)lane * kPer + q;
+            if (i < K) mine += (uint32_t)~keys[i];
+        }
+        uint64_t incl = mine;
+        for (int off = 1; off < kWave; off <<= 1) {
+            const uint64_t up = __shfl_up(incl, off);
+            if (lane >= off) incl += up;
+        }
+        uint64_t run = tile_sum[t0] + incl - mine;
+        int64_t best = first;                                            // cum(first) <= 0 is known
+        for (int q = 0; q < kPer; ++q) {
+            const int64_t i = first + (int64_t)lane * kPer + q;
+            if (i < K) {
+                run += (uint32_t)~keys[i];
+                if (cum_memory(c, i + 1, run) <= 0) best = i + 1;
+            }
+        }
+        for (int off = 32; off > 0; off >>= 1) {
+            const int64_t other = __shfl_xor(best, off);
+            best = other > best ? other : best;
+        }
+        kB = best;
+    }
+
+    const int64_t gran = c.granule;
+    int64_t n_dp, n_flex = 0;
+    if (c.tiers == 2) {
+        n_dp = kB / gran * gran;
+    } else {
+        n_dp = kA / gran * gran;
+        const i128 saved = -cum_memory(c, n_dp, prefix_count(keys, tile_sum, n_dp));     // >= 0
+        int64_t room = K - n_dp;
+        if (kF - n_dp < room) room = kF > n_dp ? kF - n_dp : 0;
+        int64_t lo = 0, hi = room;                                       // most rows j with j * flex_cost <= saved
+        if (c.flex_cost > 0) {
+            while (lo < hi) {
+                const int64_t mid = lo + (hi - lo + 1) / 2;
+                if ((i128)mid * (i128)c.flex_cost <= saved) lo = mid; else hi = mid - 1;
+            }
+        } else {
+            lo = room;
+        }
+        n_flex = lo / gran * gran;
+    }
+    const uint64_t sum_dp = prefix_count(keys, tile_sum, n_dp);
+    const uint64_t sum_both = prefix_count(keys, tile_sum, n_dp + n_flex);
+    if (lane == 0) {
+        cuts[0] = K; cuts[1] = kA; cuts[2] = kB; cuts[3] = kC; cuts[4] = kF;
+        cuts[5] = n_dp; cuts[6] = n_flex;
+        cuts[7] = (int64_t)tile_sum[tiles]; cuts[8] = (int64_t)sum_dp; cuts[9] = (int64_t)(sum_both - sum_dp);
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void tiers_emit_kernel(
+    const uint32_t* __restrict__ vals, const int64_t* __restrict__ cuts, int64_t cap, int W,
+    int64_t* __restrict__ sorted_rows, uint32_t* __restrict__ placement)
+{
+    const int64_t n_dp = cuts[5];
+    const int64_t n_both = n_dp + cuts[6];
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_both; i += stride) {
+        const uint32_t g = vals[i];
+        if (i < cap) sorted_rows[i] = (int64_t)g;
+        if (placement != nullptr) {
+            if (i < n_dp) placement[g] &= FS_OWNER_MASK;
+            else placement[g] = (1u << FS_TIER_SHIFT) | (uint32_t)((i - n_dp) % W);
+        }
+    }
+}
+
 }  // namespace fs
 
 extern "C" fs_status fs_plan_replication(
@@ -280,5 +484,81 @@ extern "C" fs_status fs_plan_replication(
         FS_LAUNCH("plan_emit", plan_emit_kernel, dim3(1024), dim3(kBlock), s,
                   vals, num_cand, cap, sel_rows, num_selected, (flags & FS_PLAN_TAG) ? placement : nullptr);
     }
+    return FS_OK;
+}
+
+extern "C" fs_status fs_plan_tiers(
+    const uint32_t* counts, int64_t R, const fs_tier_params* params, int32_t tiers,
+    int64_t* sorted_rows, int64_t cap, int64_t* cuts, uint32_t* placement,
+    void* workspace, size_t* workspace_bytes, void* stream, int32_t* dev_status)
+{
+    using namespace fs;
+    (void)dev_status;
+    if (!workspace_bytes || !params) return FS_ERR_NULL;
+    if (R < 1 || R >= 4294967295LL || cap < 0) return FS_ERR_SIZE;
+    if (tiers != 2 && tiers != 3) return FS_ERR_CONFIG;
+    const fs_tier_params& p = *params;
+    if (p.num_samples < 1 || p.num_samples >= (1LL << 40) || p.B < 1 || p.B >= (1LL << 31)) return FS_ERR_CONFIG;
+    if (p.U < 1 || p.U > FS_MAX_BUCKETS || p.W < 1 || p.U % p.W != 0) return FS_ERR_CONFIG;
+    if (p.dp_multiplier < 1 || p.dp_multiplier > 1024 || p.granule < 1 || p.granule > (1 << 20)) return FS_ERR_CONFIG;
+    const int64_t bw_max = 1LL << 20;
+    if (p.a2a_global < 1 || p.a2a_global >= bw_max || p.a2a_intra < 1 || p.a2a_intra >= bw_max ||
+        p.ar_global < 1 || p.ar_global >= bw_max || p.ar_cross < 1 || p.ar_cross >= bw_max)
+        return FS_ERR_CONFIG;
+
+    const int64_t sel_tiles = (R + kSelTile - 1) / kSelTile;
+    const int64_t sum_tiles = (R + kSumTile - 1) / kSumTile;
+    Carver ws(workspace);
+    int64_t* num_cand = ws.take<int64_t>(1);
+    uint32_t* tile_count = ws.take<uint32_t>((size_t)sel_tiles);
+    uint64_t* tile_sum = ws.take<uint64_t>((size_t)sum_tiles + 1);
+    uint32_t* keys_a = ws.take<uint32_t>((size_t)R);
+    uint32_t* vals_a = ws.take<uint32_t>((size_t)R);
+    uint32_t* keys_b = ws.take<uint32_t>((size_t)R);
+    uint32_t* vals_b = ws.take<uint32_t>((size_t)R);
+    char* sort_scratch = ws.take<char>(radix_sort_scratch_bytes(R));
+    if (!workspace) { *workspace_bytes = ws.used; return FS_OK; }
+    if (*workspace_bytes < ws.used || (reinterpret_cast<uintptr_t>(workspace) & 255)) return FS_ERR_WORKSPACE;
+    if (!counts || !cuts) return FS_ERR_NULL;
+    if (cap > 0 && !sorted_rows) return FS_ERR_NULL;
+
+    // Breakpoints as thresholds on the count, exact: the smallest count c with
+    //   A:    U B c >= (dp U - 1) S                      (DP memory term <= 0)
+    //   C:    2 B ar_global c >= a2a_global S            (DP traffic term <= 0)
+    //   FLEX: 2 B (a2a_intra - a2a_global) W ar_cross c >= S a2a_global a2a_intra
+    auto ceil_div = [](u128 num, u128 den) -> uint64_t {
+        const u128 q = (num + den - 1) / den;
+        return q > (u128)1 << 62 ? (uint64_t)1 << 62 : (uint64_t)q;
+    };
+    TierConsts c;
+    c.static_term = ((int64_t)p.dp_multiplier * p.U - 1) * p.num_samples;
+    c.dyn_factor = (int64_t)p.U * p.B;
+    c.flex_cost = ((int64_t)p.dp_multiplier * (p.U / p.W) - 1) * p.num_samples;
+    c.granule = p.granule;
+    c.W = p.W;
+    c.tiers = tiers;
+    c.thr_a = ceil_div((u128)c.static_term, (u128)c.dyn_factor);
+    c.thr_c = ceil_div((u128)p.a2a_global * (u128)p.num_samples, (u128)2 * p.B * p.ar_global);
+    c.thr_f = p.a2a_intra > p.a2a_global
+                  ? ceil_div((u128)p.num_samples * p.a2a_global * p.a2a_intra,
+                             (u128)2 * p.B * (p.a2a_intra - p.a2a_global) * p.W * p.ar_cross)
+                  : (uint64_t)1 << 62;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    FS_LAUNCH("plan_mark", plan_mark_kernel, dim3((unsigned)sel_tiles), dim3(kBlock), s,
+              counts, R, 0, tile_count, keys_b, vals_b);
+    FS_LAUNCH("plan_scan", plan_scan_kernel, dim3(1), dim3(kScanBlock), s, tile_count, sel_tiles, num_cand);
+    FS_LAUNCH("plan_move", plan_move_kernel, dim3((unsigned)sel_tiles), dim3(kBlock), s,
+              tile_count, sel_tiles, num_cand, keys_b, vals_b, keys_a, vals_a);
+    uint32_t* keys = nullptr;
+    uint32_t* vals = nullptr;
+    fs_status rc = radix_sort_pairs(keys_a, vals_a, keys_b, vals_b, R, num_cand, 32, sort_scratch, s, &keys, &vals);
+    if (rc != FS_OK) return rc;
+    FS_LAUNCH("tiers_tile_sums", tiers_tile_sums_kernel, dim3((unsigned)sum_tiles), dim3(kBlock), s,
+              keys, num_cand, tile_sum);
+    FS_LAUNCH("tiers_scan_sums", tiers_scan_sums_kernel, dim3(1), dim3(kScanBlock), s, tile_sum, sum_tiles);
+    FS_LAUNCH("tiers_cuts", tiers_cuts_kernel, dim3(1), dim3(kWave), s, keys, num_cand, tile_sum, c, cuts);
+    FS_LAUNCH("tiers_emit", tiers_emit_kernel, dim3(1024), dim3(kBlock), s, vals, cuts, cap, (int)p.W,
+              sorted_rows, placement);
     return FS_OK;
 }
