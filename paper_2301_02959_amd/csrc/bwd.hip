@@ -311,6 +311,62 @@ __global__ __launch_bounds__(kBlock) void bwd_segreduce_kernel(
 #undef FS_CONSUME
 }
 
+// Moves CNT * 64/LG listed singletons: the rows' loads first, then conversion and stores.  An index
+// past the list repeats the last entry (same bytes to the same place), so nothing is predicated.
+template <int CNT, int LG, int DT, bool EXACT>
+__device__ __forceinline__ void singles_batch(
+    const u32x4* __restrict__ grad, int units, int D, const uint32_t* s_pos, const uint32_t* s_run,
+    const uint32_t* s_key, float* stage, uint32_t s, uint32_t singles, int c, bool all_fit, int64_t cap,
+    int64_t* __restrict__ uniq_rows, float* __restrict__ row_grads)
+{
+    constexpr int N = Vec<DT>::N;
+    constexpr int RPI = kWave / LG;
+    const int g = lane_id() / LG;
+    const bool lane_on = c < units;
+    const int cc = lane_on ? c : 0;
+    u32x4 x[CNT];
+    uint32_t run[CNT];
+    uint32_t at[CNT];
+#pragma unroll
+    for (int j = 0; j < CNT; ++j) {
+        const uint32_t want = s + j * RPI + g;
+        at[j] = want < singles ? want : singles - 1;
+        run[j] = s_run[at[j]];
+        x[j] = load_stream(grad + (int64_t)s_pos[at[j]] * (EXACT ? LG : units) + cc);
+    }
+    const int lig = lane_id() % LG;
+#pragma unroll
+    for (int j = 0; j < CNT; ++j) {
+        const bool fits = all_fit || (int64_t)run[j] < cap;          // the same for the whole group
+        float f[N];
+        Vec<DT>::load(x[j], f);
+        float* row = row_grads + (int64_t)run[j] * D;
+        if constexpr (N == 4) {
+            if (lane_on && fits) store_stream(reinterpret_cast<f32x4*>(row + cc * 4), f32x4{f[0], f[1], f[2], f[3]});
+        } else {
+            // 8 floats per lane: stored as they are, each 16-byte store would cover half of every
+            // 32 bytes.  Through the wave's LDS slab lane i takes floats [4i, 4i+4) of each half of
+            // the group's columns instead, and both stores are fully coalesced.
+            float* gs = stage + g * LG * 8;
+            *reinterpret_cast<f32x4*>(gs + lig * 8) = f32x4{f[0], f[1], f[2], f[3]};
+            *reinterpret_cast<f32x4*>(gs + lig * 8 + 4) = f32x4{f[4], f[5], f[6], f[7]};
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            const f32x4 lo = *reinterpret_cast<const f32x4*>(gs + lig * 4);
+            const f32x4 hi = *reinterpret_cast<const f32x4*>(gs + LG * 4 + lig * 4);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            const int slab = (c - lig) * 8;                          // first column of the group's slab
+            const int col_lo = slab + lig * 4;
+            const int col_hi = slab + LG * 4 + lig * 4;
+            if (fits && col_lo < D) store_stream(reinterpret_cast<f32x4*>(row + col_lo), lo);
+            if (fits && col_hi < D) store_stream(reinterpret_cast<f32x4*>(row + col_hi), hi);
+        }
+        if (fits && c == 0) uniq_rows[run[j]] = (int64_t)s_key[at[j]];
+    }
+}
+
 // Runs of one lookup need no sum: row_grads[u] = f32(grad_out[pos]).  They are most of the runs
 // (the cold tail of the popularity distribution) and a store in the sequential walk above stalls
 // the wave's later loads (loads and stores share one in-order counter), so this kernel converts
@@ -323,12 +379,12 @@ __global__ __launch_bounds__(kBlock) void bwd_singletons_kernel(
     const uint32_t* __restrict__ block_base, const uint32_t* __restrict__ chunk_local,
     int64_t* __restrict__ uniq_rows, float* __restrict__ row_grads, int64_t cap)
 {
-    constexpr int N = Vec<DT>::N;
     constexpr int RPI = kWave / LG;
     constexpr int UNR = 8;
     __shared__ uint32_t s_pos[kWavesPerBlock][kChunk];
     __shared__ uint32_t s_run[kWavesPerBlock][kChunk];
     __shared__ uint32_t s_key[kWavesPerBlock][kChunk];
+    __shared__ __attribute__((aligned(16))) float s_stage[kWavesPerBlock][kWave * 8];   // store transposition, per wave
     const int w = wave_id();
     const int lane = lane_id();
     const int64_t chunk = (int64_t)blockIdx.x * kWavesPerBlock + w;
@@ -363,35 +419,25 @@ __global__ __launch_bounds__(kBlock) void bwd_singletons_kernel(
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
-    const int g = lane / LG;
-    const int lig = lane % LG;
-    const int c = blockIdx.y * LG + lig;
-    const bool lane_on = c < units;
-    const int cc = lane_on ? c : 0;
+    const int c = blockIdx.y * LG + lane % LG;
     const bool all_fit = (int64_t)first_run + heads_before <= cap;
-    for (uint32_t s = 0; s < singles; s += UNR * RPI) {
-        u32x4 x[UNR];
-        uint32_t run[UNR];
-        uint32_t at[UNR];
-#pragma unroll
-        for (int j = 0; j < UNR; ++j) {                          // past the end: the last singleton again (same bytes
-            const uint32_t want = s + j * RPI + g;               // to the same place), so nothing is predicated
-            at[j] = want < singles ? want : singles - 1;
-            run[j] = s_run[w][at[j]];
-            x[j] = load_stream(grad + (int64_t)s_pos[w][at[j]] * (EXACT ? LG : units) + cc);
+    // Full batches of UNR instructions, then ONE batch of exactly as many instructions as the rest
+    // needs: padding the last batch with repeats of the last row would write that row again and
+    // again, and with ~18 singletons per chunk that is a third of the kernel's traffic.
+    uint32_t s = 0;
+    for (; s + UNR * RPI <= singles; s += UNR * RPI)
+        singles_batch<UNR, LG, DT, EXACT>(grad, units, D, s_pos[w], s_run[w], s_key[w], s_stage[w], s, singles, c, all_fit,
+                                          cap, uniq_rows, row_grads);
+    if (s < singles) {
+#define FS_TAIL(CNT) case CNT: singles_batch<CNT, LG, DT, EXACT>(grad, units, D, s_pos[w], s_run[w], s_key[w],    \
+                                                                 s_stage[w], s, singles, c, all_fit, cap, uniq_rows, \
+                                                                 row_grads); break
+        switch ((singles - s + RPI - 1) / RPI) {
+            FS_TAIL(1); FS_TAIL(2); FS_TAIL(3); FS_TAIL(4); FS_TAIL(5); FS_TAIL(6); FS_TAIL(7);
+            default: singles_batch<UNR, LG, DT, EXACT>(grad, units, D, s_pos[w], s_run[w], s_key[w], s_stage[w], s,
+                                                       singles, c, all_fit, cap, uniq_rows, row_grads);
         }
-#pragma unroll
-        for (int j = 0; j < UNR; ++j) {
-            if (lane_on && (all_fit || (int64_t)run[j] < cap)) {
-                float f[N];
-                Vec<DT>::load(x[j], f);
-                float* dst = row_grads + (int64_t)run[j] * D + cc * N;
-#pragma unroll
-                for (int q = 0; q < N; q += 4)
-                    store_stream(reinterpret_cast<f32x4*>(dst + q), f32x4{f[q], f[q + 1], f[q + 2], f[q + 3]});
-                if (c == 0) uniq_rows[run[j]] = (int64_t)s_key[w][at[j]];
-            }
-        }
+#undef FS_TAIL
     }
 }
 
