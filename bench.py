@@ -32,6 +32,9 @@ def parse():
     ap.add_argument("--config", default="c3", help="c1..c5 (c3 = the configuration the target is stated on)")
     ap.add_argument("--variant", type=int, default=0, help="backward: 0 sort/bit-exact, 1 atomic partials")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--overlap-plan", action="store_true",
+                    help="run the plan on a second stream beside the lookup path (1-2 %% faster per step, but the "
+                         "gather then shares the chip and its own duration grows)")
     ap.add_argument("--no-exchange", action="store_true", help="skip the untimed send / unbucketize / replica-store report")
     ap.add_argument("--cpu-tables", type=int, default=0, help="tables in the oracle's sample (0 = automatic)")
     ap.add_argument("--scale-rows", type=int, default=1, help="divide E by this (debugging only; reported)")
@@ -125,39 +128,67 @@ def main():
     uniq_rows = torch.zeros(max(cap_unique, 1), dtype=torch.int64, device=dev)
     row_grads = torch.empty(max(cap_unique, 1), D, dtype=torch.float32, device=dev)
 
+    # The plan (profiling histogram + top-k) neither reads nor writes anything the lookup path touches, so
+    # with --overlap-plan it runs on a second stream beside route -> gather -> backward and joins at the
+    # end of the step.  Default: everything on one stream, so that each kernel's duration is its own.
+    main_stream = torch.cuda.current_stream()
+    plan_stream = torch.cuda.Stream() if args.overlap_plan else main_stream
+
+    plan_calls = [0]
+
     def step():
-        fs.fs_plan_replication(ids, offsets, T, B, row_base, n, R, counts, plan_flags, budget_rows * row_bytes,
-                               row_bytes, sel_rows, num_selected, None, status, workspace=ws_plan)
+        plan_calls[0] += 1
+        if plan_stream is not main_stream:
+            plan_stream.wait_stream(main_stream)
+        with torch.cuda.stream(plan_stream):
+            fs.fs_plan_replication(ids, offsets, T, B, row_base, n, R, counts, plan_flags, budget_rows * row_bytes,
+                                   row_bytes, sel_rows, num_selected, None, status, workspace=ws_plan)
         fs.fs_route_bucketize(ids, offsets, T, B, row_base, placement, n, U, W, self_b, bucket_offsets, out_rows,
                               out_pos, tier_counts, status, workspace=ws_route)
         fs.fs_seq_gather_fwd(weights, out_rows, out_pos, 0, n, out, status)
         fs.fs_seq_grad_bwd(grad_out, out_rows, out_pos, 0, n, R, args.variant, uniq_rows, row_grads, cap_unique,
                            num_unique, status, workspace=ws_bwd)
+        if plan_stream is not main_stream:
+            main_stream.wait_stream(plan_stream)
 
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
 
     # ---------------------------------------------------------------- timed region
+    # HIP events bracket only the three bandwidth kernels the roofline is about (two event records per
+    # timed launch are not free: with all ~46 launches of a step timed, the step is 4 % slower).
+    roof_kernels = "gather_rows,bwd_segreduce,bwd_singletons"
     records_per_step = 64
-    fs.fs_prof_begin(records_per_step * args.steps)
+    fs.fs_prof_begin(records_per_step * args.steps, only=roof_kernels)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    records = fs.fs_prof_end(records_per_step * args.steps)
+    roof_records = fs.fs_prof_end(records_per_step * args.steps)
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     assert int(status.item()) == 0, f"device status {int(status.item())}"
     n_u = int(num_unique.item())
+
+    # the same steps once more with every launch timed, for the per-stage breakdown (not part of `value`)
+    fs.fs_prof_begin(records_per_step * args.steps)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    records = fs.fs_prof_end(records_per_step * args.steps)
 
     per_kernel = {}
     for name, ms in records:
         tot, cnt = per_kernel.get(name, (0.0, 0))
         per_kernel[name] = (tot + ms, cnt + 1)
     kernel_ms = {k: v[0] / args.steps for k, v in per_kernel.items()}           # per step (summed launches)
-    kernel_avg = {k: v[0] / v[1] for k, v in per_kernel.items()}                # per launch
+    roof = {}
+    for name, ms in roof_records:
+        tot, cnt = roof.get(name, (0.0, 0))
+        roof[name] = (tot + ms, cnt + 1)
+    kernel_avg = {k: v[0] / v[1] for k, v in roof.items()}                      # per launch, from the timed region
     stage_ms = {
         "plan": sum(v for k, v in kernel_ms.items() if k.startswith("plan_")),
         "route": sum(v for k, v in kernel_ms.items() if k.startswith("route_")),
@@ -204,6 +235,7 @@ def main():
         "config": {"workload": f"{cfg.name}: {T} tables x {cfg.E} rows x D={D} {cfg.dtype}, batch {B}, "
                                f"{cfg.length_law} lengths, Zipf({cfg.alpha}), {U} buckets (W={W})",
                    "lookups": n, "distinct_rows": n_u, "single_lookup_rows": n_1, "bwd_variant": args.variant,
+                   "schedule": "plan on a second stream beside route, gather, backward" if args.overlap_plan else "one stream",
                    "tier_counts": [int(x) for x in tier_counts.tolist()], "scale_rows": args.scale_rows},
         "roofline": roofline,
         "stage_ms": {k: round(v, 4) for k, v in stage_ms.items()},
@@ -265,9 +297,10 @@ def main():
                         for k, v in sorted(xrec.items())}}
         del send, store, slots
 
-        # the tier planner on the counts accumulated so far (one batch profiled steps+warmup times, so the
-        # sample count is B times that); bandwidth ratios as in the paper's Figure 3 (all-reduce = 3 x all-to-all)
-        tp = dict(num_samples=B * (args.steps + args.warmup), B=B, U=U, W=W, dp_multiplier=6, granule=32,
+        # the tier planner on the counts accumulated so far (the one batch, profiled once per step run so
+        # far, so the sample count is B times that); bandwidth ratios as in the paper's Figure 3
+        # (all-reduce = 3 x all-to-all)
+        tp = dict(num_samples=B * plan_calls[0], B=B, U=U, W=W, dp_multiplier=6, granule=32,
                   a2a_global=1, a2a_intra=6, ar_global=3, ar_cross=2)
         cuts = torch.zeros(fs.FS_TIER_CUTS, dtype=torch.int64, device=dev)
         tier_rows = torch.empty(R, dtype=torch.int64, device=dev)

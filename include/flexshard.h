@@ -382,6 +382,10 @@ fs_status fs_util_copy(void* dst, const void* src, int64_t bytes, void* stream);
  * timing off.  Not thread-safe; for benchmarks only.
  */
 fs_status fs_prof_begin(int32_t max_records);
+/* Restricts the timing to the kernels named in a comma-separated list ("gather_rows,bwd_segreduce");
+ * NULL or "" = every kernel again.  The names are those fs_prof_end reports.  Each timed launch
+ * costs two event records on its stream, so a benchmark that needs a few kernels only names them. */
+fs_status fs_prof_only(const char* names /* host */);
 int32_t fs_prof_end(char* names /* host, cap*48 */, float* ms /* host */, int32_t cap);
 
 #ifdef __cplusplus

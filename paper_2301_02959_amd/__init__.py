@@ -31,7 +31,7 @@ STATUS_NAMES = {0: "FS_OK", 1: "FS_ERR_NULL", 2: "FS_ERR_SIZE", 3: "FS_ERR_DTYPE
 
 EXPORTS = ["fs_route_bucketize", "fs_seq_gather_fwd", "fs_seq_grad_bwd", "fs_plan_replication",
            "fs_seq_gather_send", "fs_seq_unbucketize", "fs_replica_build", "fs_seq_gather_fwd_replica", "fs_plan_tiers",
-           "fs_util_copy", "fs_version", "fs_bwd_tile", "fs_prof_begin", "fs_prof_end"]
+           "fs_util_copy", "fs_version", "fs_bwd_tile", "fs_prof_begin", "fs_prof_only", "fs_prof_end"]
 
 _DTYPES = {torch.float32: FS_F32, torch.float16: FS_F16, torch.bfloat16: FS_BF16}
 
@@ -55,7 +55,7 @@ def lib() -> ctypes.CDLL:
         _lib = ctypes.CDLL(LIB_PATH)
         for name in ("fs_route_bucketize", "fs_seq_gather_fwd", "fs_seq_grad_bwd", "fs_plan_replication",
                      "fs_seq_gather_send", "fs_seq_unbucketize", "fs_replica_build",
-                     "fs_seq_gather_fwd_replica", "fs_plan_tiers", "fs_prof_begin", "fs_util_copy"):
+                     "fs_seq_gather_fwd_replica", "fs_plan_tiers", "fs_prof_begin", "fs_prof_only", "fs_util_copy"):
             getattr(_lib, name).restype = ctypes.c_int
         _lib.fs_version.restype = ctypes.c_int32
         _lib.fs_bwd_tile.restype = ctypes.c_int32
@@ -271,7 +271,9 @@ def fs_bwd_tile() -> int:
     return int(lib().fs_bwd_tile())
 
 
-def fs_prof_begin(max_records: int = 4096) -> None:
+def fs_prof_begin(max_records: int = 4096, only: Optional[str] = None) -> None:
+    """Times every later launch, or only the kernels named in `only` (comma-separated)."""
+    _check("fs_prof_only", lib().fs_prof_only((only or "").encode()), True)
     _check("fs_prof_begin", lib().fs_prof_begin(ctypes.c_int32(max_records)), True)
 
 

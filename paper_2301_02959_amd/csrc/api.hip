@@ -1,6 +1,7 @@
 // Version helpers and the opt-in per-kernel timing hooks.
 #include <string.h>
 
+#include <string>
 #include <vector>
 
 #include "fs_common.h"
@@ -17,22 +18,33 @@ struct Record {
 };
 std::vector<Record> g_records;
 std::vector<Record> g_pool;     // events created by fs_prof_begin, not yet used
+std::string g_only;             // ",name,name," or empty = every kernel
+bool g_open = false;            // the last prof_pre took a record, prof_post closes it
+
+bool selected(const char* name)
+{
+    if (g_only.empty()) return true;
+    return g_only.find("," + std::string(name) + ",") != std::string::npos;
+}
 }  // namespace
 
 void prof_pre(const char* name, hipStream_t stream)
 {
-    if (g_pool.empty()) return;
+    g_open = false;
+    if (g_pool.empty() || !selected(name)) return;
     Record r = g_pool.back();
     g_pool.pop_back();
     r.name = name;
     (void)hipEventRecord(r.start, stream);
     g_records.push_back(r);
+    g_open = true;
 }
 
 void prof_post(hipStream_t stream)
 {
-    if (g_records.empty()) return;
+    if (!g_open) return;
     (void)hipEventRecord(g_records.back().stop, stream);
+    g_open = false;
 }
 
 // Plain copy: each thread moves 4 x 16 bytes, a block one contiguous 16 KB piece.
@@ -87,10 +99,19 @@ extern "C" fs_status fs_prof_begin(int32_t max_records)
     return FS_OK;
 }
 
+extern "C" fs_status fs_prof_only(const char* names)
+{
+    using namespace fs;
+    g_only.clear();
+    if (names != nullptr && names[0] != '\0') g_only = "," + std::string(names) + ",";
+    return FS_OK;
+}
+
 extern "C" int32_t fs_prof_end(char* names, float* ms, int32_t cap)
 {
     using namespace fs;
     g_prof_on = false;
+    g_open = false;
     int32_t taken = 0;
     for (Record& r : g_records) {
         float t = -1.0f;
