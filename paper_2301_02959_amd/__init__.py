@@ -271,9 +271,14 @@ def fs_bwd_tile() -> int:
     return int(lib().fs_bwd_tile())
 
 
+def fs_prof_only(names: Optional[str]) -> None:
+    """Restricts the timing to the kernels named (comma-separated); None or "" = every kernel."""
+    _check("fs_prof_only", lib().fs_prof_only((names or "").encode()), True)
+
+
 def fs_prof_begin(max_records: int = 4096, only: Optional[str] = None) -> None:
     """Times every later launch, or only the kernels named in `only` (comma-separated)."""
-    _check("fs_prof_only", lib().fs_prof_only((only or "").encode()), True)
+    fs_prof_only(only)
     _check("fs_prof_begin", lib().fs_prof_begin(ctypes.c_int32(max_records)), True)
 
 
