@@ -243,6 +243,12 @@ def main():
         "input_gen_s": round(t_gen, 1),
     }
 
+    # what the tiers of this batch mean for the row exchange (the paper's headline quantity, its Section 6.2)
+    _, traffic_report = fs.fs_tier_traffic(tier_counts.tolist(), D, cfg.row_bytes // D)
+    result["row_exchange"] = {"bytes_if_all_sharded": int(traffic_report[0]), "global_all_to_all_bytes": int(traffic_report[1]),
+                              "intra_group_all_to_all_bytes": int(traffic_report[2]),
+                              "global_all_to_all_avoided": round(traffic_report[3], 4)}
+
     # ---------------------------------------------------------------- the box's plain-copy bandwidth, for context
     copy_bytes = min(out.numel() * out.element_size(), grad_out.numel() * grad_out.element_size()) // 16 * 16
     if copy_bytes > 0:

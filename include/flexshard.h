@@ -357,6 +357,53 @@ fs_status fs_plan_tiers(
     void* workspace, size_t* workspace_bytes /* host */,
     void* stream, int32_t* dev_status);
 
+/*
+ * fs_cost_model -- the analytical per-GPU costs of one sequence embedding
+ * table in one training iteration under a uniform strategy (Section 3.2: the
+ * six metrics; the memory-cost and communication-cost tables, cell by cell).
+ * Host arithmetic in double precision, no GPU work.
+ *   out[FS_COST_STATIC_MEMORY]   bytes
+ *   out[FS_COST_INPUT_DIST]      ids to communicate before the lookups
+ *   out[FS_COST_ROWS_ACCESSED]   row elements looked up on this GPU
+ *   out[FS_COST_DYNAMIC_MEMORY]  bytes (each pass)
+ *   out[FS_COST_DYNAMIC_COMM]    bytes / bandwidth (each pass)
+ *   out[FS_COST_STATIC_COMM]     bytes / bandwidth (backward pass only)
+ * Cells the tables mark "N/A" are 0.  With E = 1 and L = p the same cells are
+ * the per-row costs of Section 4.2.
+ * Faults: NULL; a parameter that is not positive (E, L: negative), NaN, or an
+ * unknown strategy (FS_ERR_CONFIG).
+ *
+ * fs_tier_traffic -- what the tiers of a routed batch mean for the row
+ * exchange (Section 6.2 reports it as the reduction of the global all-to-all):
+ * from tier_counts[3] as fs_route_bucketize writes them (copied to the host),
+ *   out[0] bytes one direction of one pass would move if every row were sharded,
+ *   out[1] bytes left in the global all-to-all (tier 2),
+ *   out[2] bytes in the intra-group all-to-all (tier 1),
+ *   out[3] share of the global all-to-all avoided, (tier 0 + tier 1) / all.
+ */
+typedef struct fs_cost_params {
+    double E, D, dtype_bytes, L;          /* rows, dimension, bytes per scalar, average length */
+    double W, N, B;                       /* GPUs per node, nodes (U = N * W), local batch */
+    double a2a_global, a2a_intra, ar_global, ar_cross;   /* bytes per second */
+    double dp_multiplier;                 /* static memory of a replicated row in row sizes (6) */
+} fs_cost_params;
+
+#define FS_STRATEGY_RW 0
+#define FS_STRATEGY_CW 1
+#define FS_STRATEGY_DP 2
+#define FS_STRATEGY_FLEX 3
+#define FS_COST_STATIC_MEMORY 0
+#define FS_COST_INPUT_DIST 1
+#define FS_COST_ROWS_ACCESSED 2
+#define FS_COST_DYNAMIC_MEMORY 3
+#define FS_COST_DYNAMIC_COMM 4
+#define FS_COST_STATIC_COMM 5
+#define FS_COST_METRICS 6
+
+fs_status fs_cost_model(const fs_cost_params* params /* host */, int32_t strategy, double* out /* host, 6 */);
+fs_status fs_tier_traffic(const int64_t* tier_counts /* host, 3 */, int32_t D, int32_t dtype_bytes,
+                          double* out /* host, 4 */);
+
 /* ---- helpers ---------------------------------------------------------- */
 
 /* Library version, major * 1000 + minor. */

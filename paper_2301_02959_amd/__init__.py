@@ -31,7 +31,7 @@ STATUS_NAMES = {0: "FS_OK", 1: "FS_ERR_NULL", 2: "FS_ERR_SIZE", 3: "FS_ERR_DTYPE
 
 EXPORTS = ["fs_route_bucketize", "fs_seq_gather_fwd", "fs_seq_grad_bwd", "fs_plan_replication",
            "fs_seq_gather_send", "fs_seq_unbucketize", "fs_replica_build", "fs_seq_gather_fwd_replica", "fs_plan_tiers",
-           "fs_util_copy", "fs_version", "fs_bwd_tile", "fs_prof_begin", "fs_prof_only", "fs_prof_end"]
+           "fs_cost_model", "fs_tier_traffic", "fs_util_copy", "fs_version", "fs_bwd_tile", "fs_prof_begin", "fs_prof_only", "fs_prof_end"]
 
 _DTYPES = {torch.float32: FS_F32, torch.float16: FS_F16, torch.bfloat16: FS_BF16}
 
@@ -55,7 +55,8 @@ def lib() -> ctypes.CDLL:
         _lib = ctypes.CDLL(LIB_PATH)
         for name in ("fs_route_bucketize", "fs_seq_gather_fwd", "fs_seq_grad_bwd", "fs_plan_replication",
                      "fs_seq_gather_send", "fs_seq_unbucketize", "fs_replica_build",
-                     "fs_seq_gather_fwd_replica", "fs_plan_tiers", "fs_prof_begin", "fs_prof_only", "fs_util_copy"):
+                     "fs_seq_gather_fwd_replica", "fs_plan_tiers", "fs_cost_model", "fs_tier_traffic", "fs_prof_begin", "fs_prof_only",
+                     "fs_util_copy"):
             getattr(_lib, name).restype = ctypes.c_int
         _lib.fs_version.restype = ctypes.c_int32
         _lib.fs_bwd_tile.restype = ctypes.c_int32
@@ -255,6 +256,31 @@ def fs_plan_tiers(counts, R: int, params: dict, tiers: int, sorted_rows, cap: in
     else:
         size = ctypes.c_size_t(workspace.numel())
     return _check("fs_plan_tiers", call(_ptr(workspace), ctypes.byref(size)), raise_on_error)
+
+
+class CostParams(ctypes.Structure):
+    """fs_cost_params of the C header, field for field."""
+    _fields_ = [(k, ctypes.c_double) for k in ("E", "D", "dtype_bytes", "L", "W", "N", "B", "a2a_global", "a2a_intra",
+                                               "ar_global", "ar_cross", "dp_multiplier")]
+
+
+FS_STRATEGY_RW, FS_STRATEGY_CW, FS_STRATEGY_DP, FS_STRATEGY_FLEX = 0, 1, 2, 3
+
+
+def fs_cost_model(params: dict, strategy: int, raise_on_error: bool = True):
+    """Returns (code, [static memory, input dist, rows accessed, dynamic memory, dynamic comm, static comm])."""
+    cp = CostParams(**{k: float(v) for k, v in params.items()})
+    out = (ctypes.c_double * 6)()
+    code = lib().fs_cost_model(ctypes.byref(cp), ctypes.c_int32(strategy), out)
+    return _check("fs_cost_model", code, raise_on_error), list(out)
+
+
+def fs_tier_traffic(tier_counts, D: int, dtype_bytes: int, raise_on_error: bool = True):
+    """tier_counts: three host integers.  Returns (code, [all sharded, global left, intra-group, share avoided])."""
+    tc = (ctypes.c_int64 * 3)(*[int(x) for x in tier_counts])
+    out = (ctypes.c_double * 4)()
+    code = lib().fs_tier_traffic(tc, ctypes.c_int32(D), ctypes.c_int32(dtype_bytes), out)
+    return _check("fs_tier_traffic", code, raise_on_error), list(out)
 
 
 def fs_util_copy(dst, src, nbytes: Optional[int] = None, raise_on_error: bool = True) -> int:
