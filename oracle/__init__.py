@@ -22,6 +22,7 @@ F32, F16, BF16 = 0, 1, 2
 BAD_ID, BAD_OFFSETS, BAD_PLACEMENT, COUNT_OVERFLOW, UNIQUE_OVERFLOW, POS_ORDER = 1, 2, 4, 8, 16, 32
 PLAN_ACCUMULATE, PLAN_SELECT, PLAN_TAG, PLAN_ALLOW_ZERO = 1, 2, 4, 8
 BWD_TILE = 256
+OPT_SGD, OPT_ADAGRAD_ROWWISE, OPT_ADAGRAD = 0, 1, 2
 CUT_CANDIDATES, CUT_A, CUT_B, CUT_C, CUT_FLEX, CUT_N_DP, CUT_N_FLEX, CUT_SUM_ALL, CUT_SUM_DP, CUT_SUM_FLEX = range(10)
 N_CUTS = 10
 
@@ -30,7 +31,7 @@ def build(force: bool = False) -> str:
     """Compile the oracle with gcc; -ffp-contract=off keeps every add unfused."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         cmd = ["gcc", "-std=c11", "-O2", "-ffp-contract=off", "-fno-fast-math", "-Wall", "-Wextra",
-               "-shared", "-fPIC", _SRC, "-o", _LIB]
+               "-shared", "-fPIC", _SRC, "-o", _LIB, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -223,3 +224,21 @@ def plan_tiers(counts: np.ndarray, params: dict, tiers: int, cap: Optional[int] 
     k = int(min(max(cuts[CUT_N_DP] + cuts[CUT_N_FLEX], 0), max(cap, 0))) if rc == 0 else 0
     assert np.all(rows[k:] == -1), "the oracle wrote past the rows it reports"
     return rc, cuts, rows[:k]
+
+
+def sparse_update(weights: np.ndarray, uniq_rows, row_grads: np.ndarray, optimizer: int, lr: float, eps: float,
+                  state: Optional[np.ndarray] = None, store: Optional[np.ndarray] = None, slot_of_row=None,
+                  dtype: Optional[int] = None) -> Tuple[int, int]:
+    """One optimizer step on the rows named by uniq_rows; weights, state and store change in place."""
+    code = _dtype_code(weights, dtype)
+    rows = _i64(uniq_rows)
+    R, D = weights.shape
+    assert row_grads.dtype == np.float32 and (state is None or state.dtype == np.float32)
+    slots = None if slot_of_row is None else np.ascontiguousarray(slot_of_row, dtype=np.int32)
+    k = 0 if store is None else store.shape[0]
+    status = ctypes.c_int32(0)
+    rc = lib().oracle_sparse_update(
+        _p(weights), ctypes.c_int64(R), ctypes.c_int32(D), ctypes.c_int(code), _p(rows), _p(row_grads),
+        ctypes.c_int64(rows.shape[0]), ctypes.c_int32(optimizer), ctypes.c_float(lr), ctypes.c_float(eps), _p(state),
+        _p(store), _p(slots), ctypes.c_int64(k), ctypes.byref(status))
+    return rc, status.value

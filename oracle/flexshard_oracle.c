@@ -19,6 +19,7 @@
  * No function here is "parity unpinned".
  */
 #include <stdint.h>
+#include <math.h>
 #include <stdlib.h>
 #include <string.h>
 
@@ -583,5 +584,101 @@ int oracle_plan_tiers(
             placement[cand[i].g] = 0x40000000u | (uint32_t)((i - n_dp) % p->W);
     }
     free(cand);
+    return OK;
+}
+
+/*
+ * Sparse optimizer step on the deduplicated gradients (the step that follows
+ * the backward of Section 3.2; the replicated strategy's static-memory factor
+ * of the memory-cost table is this optimizer and gradient state).  Textbook
+ * rules, in double precision, the new weight rounded once to the table's type
+ * (round to nearest even):
+ *   SGD              w -= lr g
+ *   Adagrad          s += g^2 (per element);          w -= lr g / (sqrt(s) + eps)
+ *   row-wise Adagrad s_r += mean over the row of g^2; w -= lr g / (sqrt(s_r) + eps)
+ * state is float32 (read, updated in double, rounded back).  A row that has a
+ * slot in the replica store gets the same new values there.
+ */
+enum { OPT_SGD = 0, OPT_ADAGRAD_ROWWISE = 1, OPT_ADAGRAD = 2 };
+
+/* x rounded to a binary format with `mant` explicit mantissa bits and minimum normal exponent
+ * emin (value 2^emin), ties to even; returns the sign, biased exponent and mantissa fields packed
+ * for a 16-bit format with `ebits` exponent bits. */
+static uint16_t round_to_16(double x, int mant, int ebits)
+{
+    const int bias = (1 << (ebits - 1)) - 1;
+    const int emin = 1 - bias;
+    uint16_t sign = (uint16_t)(signbit(x) ? 0x8000u : 0u);
+    if (isnan(x)) return (uint16_t)(sign | (((1u << ebits) - 1u) << mant) | (1u << (mant - 1)));
+    double a = fabs(x);
+    if (isinf(a)) return (uint16_t)(sign | (((1u << ebits) - 1u) << mant));
+    if (a == 0.0) return sign;
+    int e;
+    (void)frexp(a, &e);               /* a = f * 2^e, f in [0.5, 1)  ->  a in [2^(e-1), 2^e) */
+    int exp = e - 1;                  /* a = 1.xxx * 2^exp */
+    if (exp < emin) exp = emin;       /* subnormal range: fixed quantum 2^(emin - mant) */
+    double quantum = ldexp(1.0, exp - mant);
+    double q = nearbyint(a / quantum);          /* ties to even in the default rounding mode */
+    /* q is in [0, 2^(mant+1)]; fields follow from the integer */
+    uint32_t qi = (uint32_t)q;
+    uint32_t field;
+    if (qi < (1u << mant)) field = qi;                                   /* subnormal (or zero) */
+    else field = ((uint32_t)(exp - emin + 1) << mant) + (qi - (1u << mant));  /* a carry runs into the exponent */
+    if (field >= (((1u << ebits) - 1u) << mant)) field = ((1u << ebits) - 1u) << mant;   /* overflow -> infinity */
+    return (uint16_t)(sign | field);
+}
+
+static void store_elem(void* base, size_t index, int dtype, double x)
+{
+    if (dtype == DT_F32) ((float*)base)[index] = (float)x;
+    else if (dtype == DT_F16) ((uint16_t*)base)[index] = round_to_16(x, 10, 5);
+    else ((uint16_t*)base)[index] = round_to_16(x, 7, 8);
+}
+
+int oracle_sparse_update(
+    void* weights, int64_t R, int32_t D, int dtype,
+    const int64_t* uniq_rows, const float* row_grads, int64_t n_u,
+    int32_t optimizer, float lr, float eps, float* state,
+    void* store, const int32_t* slot_of_row, int64_t k, int32_t* status)
+{
+    int es = elem_size(dtype);
+    if (!es) return ERR_DTYPE;
+    if (R < 1 || D < 1 || n_u < 0 || k < 0) return ERR_SIZE;
+    if (optimizer != OPT_SGD && optimizer != OPT_ADAGRAD_ROWWISE && optimizer != OPT_ADAGRAD) return ERR_CONFIG;
+    if (!weights || (n_u > 0 && (!uniq_rows || !row_grads))) return ERR_NULL;
+    if (optimizer != OPT_SGD && !state) return ERR_NULL;
+    if ((store != NULL) != (slot_of_row != NULL)) return ERR_NULL;
+    if (((size_t)D * (size_t)es) % 16 != 0) return ERR_ALIGN;
+    for (int64_t u = 0; u < n_u; ++u) {
+        int64_t r = uniq_rows[u];
+        if (r < 0 || r >= R) { flag(status, DEV_BAD_ID); continue; }
+        const float* g = row_grads + (size_t)u * (size_t)D;
+        double row_state = 0.0;
+        if (optimizer == OPT_ADAGRAD_ROWWISE) {
+            double sq = 0.0;
+            for (int32_t d = 0; d < D; ++d) sq += (double)g[d] * (double)g[d];
+            row_state = (double)state[r] + sq / (double)D;
+            state[r] = (float)row_state;
+        }
+        int32_t slot = slot_of_row ? slot_of_row[r] : -1;
+        if (slot >= k) { flag(status, DEV_BAD_ID); slot = -1; }
+        for (int32_t d = 0; d < D; ++d) {
+            size_t at = (size_t)r * (size_t)D + (size_t)d;
+            double w = (double)load_elem(weights, at, dtype);
+            double gd = (double)g[d];
+            double step;
+            if (optimizer == OPT_SGD) {
+                step = (double)lr * gd;
+            } else if (optimizer == OPT_ADAGRAD) {
+                double s = (double)state[at] + gd * gd;
+                state[at] = (float)s;
+                step = (double)lr * gd / (sqrt(s) + (double)eps);
+            } else {
+                step = (double)lr * gd / (sqrt(row_state) + (double)eps);
+            }
+            store_elem(weights, at, dtype, w - step);
+            if (slot >= 0) store_elem(store, (size_t)slot * (size_t)D + (size_t)d, dtype, w - step);
+        }
+    }
     return OK;
 }

@@ -56,6 +56,15 @@ MUTANTS = {
     "tiers_flex_owner_over_all": ("(uint32_t)((i - n_dp) % p->W);", "(uint32_t)((i - n_dp) % p->U);"),
     "tiers_flex_allreduce_whole": ("2 * B * c * (wide_t)(p->a2a_intra - p->a2a_global) * W * (wide_t)p->ar_cross)", "2 * B * c * (wide_t)(p->a2a_intra - p->a2a_global) * (wide_t)p->ar_cross)"),
     "tiers_flex_overspends": ("spent + flex_cost <= saved) { spent += flex_cost; ++i; }", "spent <= saved) { spent += flex_cost; ++i; }"),
+    "update_sgd_adds": ("store_elem(weights, at, dtype, w - step);", "store_elem(weights, at, dtype, w + step);"),
+    "update_adagrad_eps_inside_root": ("step = (double)lr * gd / (sqrt(s) + (double)eps);", "step = (double)lr * gd / sqrt(s + (double)eps);"),
+    "update_adagrad_state_not_squared": ("double s = (double)state[at] + gd * gd;", "double s = (double)state[at] + fabs(gd);"),
+    "update_rowwise_sum_not_mean": ("row_state = (double)state[r] + sq / (double)D;", "row_state = (double)state[r] + sq;"),
+    "update_rowwise_old_state": ("step = (double)lr * gd / (sqrt(row_state) + (double)eps);", "step = (double)lr * gd / (sqrt((double)state[r] - 0.0) + (double)eps); (void)row_state;"),
+    "update_store_not_mirrored": ("if (slot >= 0) store_elem(store, (size_t)slot * (size_t)D + (size_t)d, dtype, w - step);", "if (slot >= 0) store_elem(store, (size_t)slot * (size_t)D + (size_t)d, dtype, w);"),
+    "update_round_through_float": ("else ((uint16_t*)base)[index] = round_to_16(x, 7, 8);", "else ((uint16_t*)base)[index] = round_to_16((double)(float)x, 7, 8);"),
+    "update_round_truncates": ("double q = nearbyint(a / quantum);", "double q = floor(a / quantum);"),
+    "update_subnormals_flushed": ("if (exp < emin) exp = emin;", "if (exp < emin) return sign;"),
 }
 # a mutant that changes nothing observable would be a bad test of the tests: keep only real ones
 MUTANTS.pop("fold_right_to_left")
@@ -170,6 +179,13 @@ def pins(o):
     for seed in range(6):
         tt.test_against_whole_curve_brute_force(seed, 2)
         tt.test_against_whole_curve_brute_force(seed, 3)
+    # sparse optimizer step: torch.optim in float64, the row-wise rule by hand, rounding against numpy
+    import test_oracle_update as tu
+    tu.test_float32_table_follows_torch_optim("sgd", o.OPT_SGD)
+    tu.test_float32_table_follows_torch_optim("adagrad", o.OPT_ADAGRAD)
+    tu.test_rowwise_by_hand_and_against_elementwise()
+    tu.test_rounding_to_16_bit_types_is_numpy_s()
+    tu.test_store_mirror_faults_and_edges()
 
 
 def test_pins_accept_the_real_oracle():
@@ -184,7 +200,7 @@ def test_pins_reject_mutant(name, tmp_path):
     src = tmp_path / "mutant.c"
     src.write_text(text.replace(old, new))
     lib = tmp_path / "libmutant.so"
-    subprocess.run(["gcc", "-std=c11", "-O2", "-ffp-contract=off", "-shared", "-fPIC", str(src), "-o", str(lib)], check=True)
+    subprocess.run(["gcc", "-std=c11", "-O2", "-ffp-contract=off", "-shared", "-fPIC", str(src), "-o", str(lib), "-lm"], check=True)
     with Lib(str(lib)) as o:
         with pytest.raises(AssertionError):
             pins(o)
