@@ -301,7 +301,21 @@ def main():
                             **({"GBps": round(xalg[k] / (v * 1e-3) / 1e9, 1),
                                 "frac": round(xalg[k] / (v * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)} if k in xalg else {})}
                         for k, v in sorted(xrec.items())}}
-        del send, store, slots
+        # the optimizer step that follows the backward: row-wise Adagrad on the deduplicated gradients,
+        # mirrored into the replica store (lr = 0 keeps the table's bits for the legs below; the traffic is the same)
+        opt_state = torch.zeros(R, dtype=torch.float32, device=dev)
+        for i in range(2 + reps):
+            if i == 2:
+                fs.fs_prof_begin(4 * reps)
+            fs.fs_sparse_update(weights, uniq_rows, row_grads, cap_unique, num_unique, fs.FS_OPT_ADAGRAD_ROWWISE, 0.0,
+                                1e-8, opt_state, store, slots, budget_rows, status)
+        torch.cuda.synchronize()
+        upd_ms = sum(ms for _, ms in fs.fs_prof_end(4 * reps)) / reps
+        upd_bytes = n_u * (D * 4 + 2 * row_bytes + 16)
+        result["exchange_path"]["kernels"]["sparse_update"] = {
+            "ms": round(upd_ms, 4), "GBps": round(upd_bytes / (upd_ms * 1e-3) / 1e9, 1),
+            "frac": round(upd_bytes / (upd_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4), "rule": "row-wise Adagrad"}
+        del send, store, slots, opt_state
 
         # the tier planner on the counts accumulated so far (the one batch, profiled once per step run so
         # far, so the sample count is B times that); bandwidth ratios as in the paper's Figure 3

@@ -358,6 +358,42 @@ fs_status fs_plan_tiers(
     void* stream, int32_t* dev_status);
 
 /*
+ * fs_sparse_update -- one optimizer step on the rows fs_seq_grad_bwd produced
+ * gradients for (the step that follows the backward pass of Section 3.2; the
+ * replicated strategy's static-memory factor in the memory-cost table is this
+ * optimizer state and gradient memory).
+ *
+ *   for u < min(cap_unique, *num_unique) (cap_unique if num_unique == NULL), r = uniq_rows[u], g = row_grads[u, :]:
+ *     FS_OPT_SGD              w[r, :] -= lr g
+ *     FS_OPT_ADAGRAD          state[r, :] += g^2;            w[r, :] -= lr g / (sqrt(state[r, :]) + eps)
+ *     FS_OPT_ADAGRAD_ROWWISE  state[r] += mean over the row of g^2;  w[r, :] -= lr g / (sqrt(state[r]) + eps)
+ *   weights[R, D] in `dtype`, updated in place; state is float32, [R, D] or [R]
+ *   (unused and may be NULL for SGD).  If store / slot_of_row (both or neither;
+ *   as fs_replica_build wrote them) are given, a row with a slot gets its new
+ *   values there as well.
+ * Arithmetic: float32, one IEEE operation at a time, the new weight rounded
+ * once to `dtype` (nearest even).  Against the same rules in double precision:
+ * within one unit in the last place of `dtype`; state within 1e-6 relative.
+ * uniq_rows must not name a row twice (true of fs_seq_grad_bwd's output):
+ * duplicates race.
+ * Data faults: uniq_rows[u] outside [0, R) is skipped, a slot >= k is not
+ * mirrored (both FS_DEV_BAD_ID).
+ * Host faults: NULL; R < 1, D < 1, cap_unique < 0, k < 0 (FS_ERR_SIZE); unknown
+ * optimizer (FS_ERR_CONFIG); D * sizeof(dtype) not a multiple of 16 or a
+ * pointer not 16-byte aligned (FS_ERR_ALIGN).
+ */
+#define FS_OPT_SGD 0
+#define FS_OPT_ADAGRAD_ROWWISE 1
+#define FS_OPT_ADAGRAD 2
+
+fs_status fs_sparse_update(
+    void* weights, int64_t R, int32_t D, fs_dtype dtype,
+    const int64_t* uniq_rows, const float* row_grads, int64_t cap_unique, const int64_t* num_unique,
+    int32_t optimizer, float lr, float eps, float* state,
+    void* store, const int32_t* slot_of_row, int64_t k,
+    void* stream, int32_t* dev_status);
+
+/*
  * fs_cost_model -- the analytical per-GPU costs of one sequence embedding
  * table in one training iteration under a uniform strategy (Section 3.2: the
  * six metrics; the memory-cost and communication-cost tables, cell by cell).

@@ -21,6 +21,7 @@ FS_DEV_BAD_ID, FS_DEV_BAD_OFFSETS, FS_DEV_BAD_PLACEMENT = 1, 2, 4
 FS_DEV_COUNT_OVERFLOW, FS_DEV_UNIQUE_OVERFLOW, FS_DEV_POS_ORDER = 8, 16, 32
 FS_PLAN_ACCUMULATE, FS_PLAN_SELECT, FS_PLAN_TAG, FS_PLAN_ALLOW_ZERO = 1, 2, 4, 8
 FS_BWD_TILE = 256
+FS_OPT_SGD, FS_OPT_ADAGRAD_ROWWISE, FS_OPT_ADAGRAD = 0, 1, 2
 (FS_CUT_CANDIDATES, FS_CUT_A, FS_CUT_B, FS_CUT_C, FS_CUT_FLEX, FS_CUT_N_DP, FS_CUT_N_FLEX, FS_CUT_SUM_ALL,
  FS_CUT_SUM_DP, FS_CUT_SUM_FLEX) = range(10)
 FS_TIER_CUTS = 10
@@ -31,7 +32,7 @@ STATUS_NAMES = {0: "FS_OK", 1: "FS_ERR_NULL", 2: "FS_ERR_SIZE", 3: "FS_ERR_DTYPE
 
 EXPORTS = ["fs_route_bucketize", "fs_seq_gather_fwd", "fs_seq_grad_bwd", "fs_plan_replication",
            "fs_seq_gather_send", "fs_seq_unbucketize", "fs_replica_build", "fs_seq_gather_fwd_replica", "fs_plan_tiers",
-           "fs_cost_model", "fs_tier_traffic", "fs_util_copy", "fs_version", "fs_bwd_tile", "fs_prof_begin", "fs_prof_only", "fs_prof_end"]
+           "fs_cost_model", "fs_tier_traffic", "fs_sparse_update", "fs_util_copy", "fs_version", "fs_bwd_tile", "fs_prof_begin", "fs_prof_only", "fs_prof_end"]
 
 _DTYPES = {torch.float32: FS_F32, torch.float16: FS_F16, torch.bfloat16: FS_BF16}
 
@@ -55,7 +56,7 @@ def lib() -> ctypes.CDLL:
         _lib = ctypes.CDLL(LIB_PATH)
         for name in ("fs_route_bucketize", "fs_seq_gather_fwd", "fs_seq_grad_bwd", "fs_plan_replication",
                      "fs_seq_gather_send", "fs_seq_unbucketize", "fs_replica_build",
-                     "fs_seq_gather_fwd_replica", "fs_plan_tiers", "fs_cost_model", "fs_tier_traffic", "fs_prof_begin", "fs_prof_only",
+                     "fs_seq_gather_fwd_replica", "fs_plan_tiers", "fs_cost_model", "fs_tier_traffic", "fs_sparse_update", "fs_prof_begin", "fs_prof_only",
                      "fs_util_copy"):
             getattr(_lib, name).restype = ctypes.c_int
         _lib.fs_version.restype = ctypes.c_int32
@@ -256,6 +257,20 @@ def fs_plan_tiers(counts, R: int, params: dict, tiers: int, sorted_rows, cap: in
     else:
         size = ctypes.c_size_t(workspace.numel())
     return _check("fs_plan_tiers", call(_ptr(workspace), ctypes.byref(size)), raise_on_error)
+
+
+def fs_sparse_update(weights, uniq_rows, row_grads, cap_unique: int, num_unique, optimizer: int, lr: float, eps: float,
+                     state=None, store=None, slot_of_row=None, k: int = 0, dev_status=None,
+                     raise_on_error: bool = True, R: Optional[int] = None, D: Optional[int] = None,
+                     dtype: Optional[int] = None) -> int:
+    R = weights.shape[0] if R is None else R
+    D = weights.shape[1] if D is None else D
+    dtype = _DTYPES[weights.dtype] if dtype is None else dtype
+    code = lib().fs_sparse_update(
+        _ptr(weights), ctypes.c_int64(R), ctypes.c_int32(D), ctypes.c_int(dtype), _ptr(uniq_rows), _ptr(row_grads),
+        ctypes.c_int64(cap_unique), _ptr(num_unique), ctypes.c_int32(optimizer), ctypes.c_float(lr), ctypes.c_float(eps),
+        _ptr(state), _ptr(store), _ptr(slot_of_row), ctypes.c_int64(k), _stream(), _ptr(dev_status))
+    return _check("fs_sparse_update", code, raise_on_error)
 
 
 class CostParams(ctypes.Structure):

@@ -1,0 +1,326 @@
+// fs_sparse_update: one optimizer step on the rows a backward pass produced gradients for.
+//
+//   SGD               w -= lr g
+//   Adagrad           s += g^2 per element;           w -= lr g / (sqrt(s) + eps)
+//   row-wise Adagrad  s_r += mean of g^2 over the row; w -= lr g / (sqrt(s_r) + eps)
+//
+// HBM-bound read-modify-write of scattered rows: per row one fp32 gradient row in, the table row
+// in and out, the state in and out.  The layout is the gather's: a wave owns 64 consecutive
+// entries of uniq_rows, reads them with one coalesced load, hands them to groups of LG lanes with
+// ds_bpermute; a group moves one row per instruction (16 bytes of the table row per lane, i.e. 4
+// or 8 elements, and the 4 or 8 matching fp32 gradients and state values), UNR rows in flight.
+// The row-wise rule needs the row's sum of squares: a butterfly over the group's lanes.
+// Arithmetic is fp32, one IEEE operation at a time (no fused multiply-add, correctly rounded
+// division and square root); the new weight is rounded once to the table's type, to nearest even.
+// Rows longer than 64 pieces (1 KB) take a slower path: one wave per row, piece by piece.
+#include "fs_common.h"
+
+namespace fs {
+
+typedef _Float16 h16x8 __attribute__((ext_vector_type(8)));
+
+struct UpdateArgs {
+    u32x4* weights;
+    int64_t R;
+    int units;                       // 16-byte pieces per table row
+    int D;
+    const int64_t* uniq_rows;
+    const float* row_grads;
+    int64_t cap;
+    const int64_t* num_unique;       // device; only the first min(cap, *num_unique) entries are applied
+    float lr, eps;
+    float* state;
+    u32x4* store;                    // replica store, or nullptr
+    const int32_t* slot_of_row;
+    int64_t k;
+    int32_t* status;
+};
+
+template <int DT>
+struct Elems {
+    static constexpr int N = DT == FS_F32 ? 4 : 8;
+    static __device__ __forceinline__ void unpack(const u32x4& x, float* f)
+    {
+        if constexpr (DT == FS_F32) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) f[i] = __uint_as_float(x[i]);
+        } else if constexpr (DT == FS_F16) {
+            const h16x8 h = __builtin_bit_cast(h16x8, x);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) f[i] = (float)h[i];
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                f[2 * i] = __uint_as_float(x[i] << 16);
+                f[2 * i + 1] = __uint_as_float(x[i] & 0xFFFF0000u);
+            }
+        }
+    }
+    static __device__ __forceinline__ uint32_t bf16_bits(float v)     // round to nearest even
+    {
+        const uint32_t b = __float_as_uint(v);
+        if ((b & 0x7FFFFFFFu) > 0x7F800000u) return (b >> 16) | 0x40u;          // NaN stays NaN
+        return (b + 0x7FFFu + ((b >> 16) & 1u)) >> 16;
+    }
+    static __device__ __forceinline__ u32x4 pack(const float* f)
+    {
+        u32x4 x;
+        if constexpr (DT == FS_F32) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) x[i] = __float_as_uint(f[i]);
+        } else if constexpr (DT == FS_F16) {
+            h16x8 h;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) h[i] = (_Float16)f[i];                  // v_cvt_f16_f32: nearest even
+            x = __builtin_bit_cast(u32x4, h);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) x[i] = bf16_bits(f[2 * i]) | (bf16_bits(f[2 * i + 1]) << 16);
+        }
+        return x;
+    }
+};
+
+// The new values of one lane's N elements.  s_row: the row-wise state after this step.
+template <int N, int OPT>
+__device__ __forceinline__ void apply_rule(float* w, const float* g, float* s, float s_row, float lr, float eps)
+{
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        const float lg = lr * g[i];
+        if constexpr (OPT == FS_OPT_SGD) {
+            w[i] = w[i] - lg;
+        } else if constexpr (OPT == FS_OPT_ADAGRAD) {
+            s[i] = s[i] + g[i] * g[i];
+            w[i] = w[i] - lg / (sqrtf(s[i]) + eps);
+        } else {
+            w[i] = w[i] - lg / (sqrtf(s_row) + eps);
+        }
+    }
+}
+
+template <int LG, int DT, int OPT, bool EXACT>
+__global__ __launch_bounds__(kBlock) void sparse_update_kernel(const UpdateArgs a)
+{
+    constexpr int N = Elems<DT>::N;
+    constexpr int RPI = kWave / LG;
+    constexpr int UNR = LG >= 32 ? 4 : (LG >= 8 ? 2 : 1);          // row instructions in flight (2 and 8 are slower)
+    const int lane = lane_id();
+    const int64_t wbase = ((int64_t)blockIdx.x * kWavesPerBlock + wave_id()) * kWave;
+    int64_t m = a.cap;
+    if (a.num_unique) { const int64_t nu = *a.num_unique; m = nu < m ? (nu < 0 ? 0 : nu) : m; }
+    if (wbase >= m) return;                                          // wave-uniform
+
+    const int64_t jj = wbase + lane;
+    int64_t my_row = 0;
+    int my_ok = 0, my_slot = -1;
+    if (jj < m) {
+        my_row = a.uniq_rows[jj];
+        my_ok = (uint64_t)my_row < (uint64_t)a.R ? 1 : 0;
+        if (!my_ok) { report(a.status, FS_DEV_BAD_ID); my_row = 0; }
+        else if (a.store != nullptr) {
+            my_slot = a.slot_of_row[my_row];
+            if (my_slot >= a.k) { report(a.status, FS_DEV_BAD_ID); my_slot = -1; }
+        }
+    }
+    const int g = lane / LG;
+    const int lig = lane % LG;
+    const bool lane_on = lig < a.units;                              // units <= LG on this path
+    const int cc = lane_on ? lig : 0;
+    const int64_t stride = EXACT ? LG : a.units;
+#pragma unroll 1
+    for (int s0 = 0; s0 < kWave; s0 += UNR * RPI) {
+        int64_t r[UNR], u[UNR];
+        int ok[UNR], sl[UNR];
+#pragma unroll
+        for (int j = 0; j < UNR; ++j) {
+            const int from = s0 + j * RPI + g;
+            r[j] = __shfl(my_row, from);
+            ok[j] = __shfl(my_ok, from);
+            sl[j] = __shfl(my_slot, from);
+            u[j] = ok[j] ? wbase + from : wbase;                     // an entry that is skipped reads entry wbase
+        }
+        u32x4 wx[UNR];
+        f32x4 ga[UNR], gb[UNR], sa[UNR], sb[UNR];
+        float srow[UNR];
+#pragma unroll
+        for (int j = 0; j < UNR; ++j) {
+            wx[j] = a.weights[r[j] * stride + cc];
+            const float* gp = a.row_grads + u[j] * a.D + cc * N;
+            ga[j] = load_stream(reinterpret_cast<const f32x4*>(gp));
+            if constexpr (N == 8) gb[j] = load_stream(reinterpret_cast<const f32x4*>(gp + 4));
+            if constexpr (OPT == FS_OPT_ADAGRAD) {
+                const float* sp = a.state + r[j] * a.D + cc * N;
+                sa[j] = *reinterpret_cast<const f32x4*>(sp);
+                if constexpr (N == 8) sb[j] = *reinterpret_cast<const f32x4*>(sp + 4);
+            }
+            if constexpr (OPT == FS_OPT_ADAGRAD_ROWWISE) srow[j] = a.state[r[j]];
+        }
+#pragma unroll
+        for (int j = 0; j < UNR; ++j) {
+            float w[N], gf[N], sf[N];
+            Elems<DT>::unpack(wx[j], w);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                gf[i] = ga[j][i];
+                if constexpr (N == 8) gf[4 + i] = gb[j][i];
+                if constexpr (OPT == FS_OPT_ADAGRAD) {
+                    sf[i] = sa[j][i];
+                    if constexpr (N == 8) sf[4 + i] = sb[j][i];
+                }
+            }
+            float s_row = 0.0f;
+            if constexpr (OPT == FS_OPT_ADAGRAD_ROWWISE) {
+                float sq = 0.0f;
+                if (lane_on) {
+#pragma unroll
+                    for (int i = 0; i < N; ++i) sq = sq + gf[i] * gf[i];
+                }
+#pragma unroll
+                for (int off = 1; off < LG; off <<= 1) sq = sq + __shfl_xor(sq, off);
+                s_row = srow[j] + sq / (float)a.D;
+            }
+            apply_rule<N, OPT>(w, gf, sf, s_row, a.lr, a.eps);
+            if (ok[j] && lane_on) {
+                const u32x4 out = Elems<DT>::pack(w);
+                a.weights[r[j] * stride + cc] = out;
+                if (sl[j] >= 0) a.store[(int64_t)sl[j] * stride + cc] = out;
+                if constexpr (OPT == FS_OPT_ADAGRAD) {
+                    float* sp = a.state + r[j] * a.D + cc * N;
+                    *reinterpret_cast<f32x4*>(sp) = f32x4{sf[0], sf[1], sf[2], sf[3]};
+                    if constexpr (N == 8) *reinterpret_cast<f32x4*>(sp + 4) = f32x4{sf[4], sf[5], sf[6], sf[7]};
+                }
+                if constexpr (OPT == FS_OPT_ADAGRAD_ROWWISE) {
+                    if (lig == 0) a.state[r[j]] = s_row;
+                }
+            }
+        }
+    }
+}
+
+// Rows of more than 64 pieces: one wave per entry, the row piece by piece (64 pieces a round); the
+// row-wise rule reads the gradient row twice (sum of squares first).
+template <int DT, int OPT>
+__global__ __launch_bounds__(kBlock) void sparse_update_long_kernel(const UpdateArgs a)
+{
+    constexpr int N = Elems<DT>::N;
+    const int lane = lane_id();
+    const int64_t u = (int64_t)blockIdx.x * kWavesPerBlock + wave_id();
+    int64_t m = a.cap;
+    if (a.num_unique) { const int64_t nu = *a.num_unique; m = nu < m ? (nu < 0 ? 0 : nu) : m; }
+    if (u >= m) return;                                              // wave-uniform
+    const int64_t r = a.uniq_rows[u];
+    if ((uint64_t)r >= (uint64_t)a.R) { if (lane == 0) report(a.status, FS_DEV_BAD_ID); return; }
+    int slot = -1;
+    if (a.store != nullptr) {
+        slot = a.slot_of_row[r];
+        if (slot >= a.k) { if (lane == 0) report(a.status, FS_DEV_BAD_ID); slot = -1; }
+    }
+    float s_row = 0.0f;
+    if constexpr (OPT == FS_OPT_ADAGRAD_ROWWISE) {
+        float sq = 0.0f;
+        for (int c = lane; c < a.units; c += kWave) {
+            const float* gp = a.row_grads + u * a.D + c * N;
+#pragma unroll
+            for (int i = 0; i < N; ++i) sq = sq + gp[i] * gp[i];
+        }
+#pragma unroll
+        for (int off = 1; off < kWave; off <<= 1) sq = sq + __shfl_xor(sq, off);
+        s_row = a.state[r] + sq / (float)a.D;
+    }
+    for (int c = lane; c < a.units; c += kWave) {
+        float w[N], gf[N], sf[N];
+        Elems<DT>::unpack(a.weights[r * a.units + c], w);
+        const float* gp = a.row_grads + u * a.D + c * N;
+        float* sp = a.state + r * a.D + c * N;
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            gf[i] = gp[i];
+            if constexpr (OPT == FS_OPT_ADAGRAD) sf[i] = sp[i];
+        }
+        apply_rule<N, OPT>(w, gf, sf, s_row, a.lr, a.eps);
+        const u32x4 out = Elems<DT>::pack(w);
+        a.weights[r * a.units + c] = out;
+        if (slot >= 0) a.store[(int64_t)slot * a.units + c] = out;
+        if constexpr (OPT == FS_OPT_ADAGRAD) {
+#pragma unroll
+            for (int i = 0; i < N; ++i) sp[i] = sf[i];
+        }
+    }
+    if constexpr (OPT == FS_OPT_ADAGRAD_ROWWISE) {
+        __builtin_amdgcn_wave_barrier();                             // every lane has read state[r] above
+        if (lane == 0) a.state[r] = s_row;
+    }
+}
+
+template <int LG, int DT, int OPT>
+static fs_status launch_update_lg(const UpdateArgs& a, hipStream_t stream)
+{
+    const int64_t grid = (a.cap + kBlock - 1) / kBlock;              // 64 entries per wave
+    if (grid > 0x7FFFFFFF) return FS_ERR_SIZE;
+    if (a.units == LG)
+        FS_LAUNCH("sparse_update", (sparse_update_kernel<LG, DT, OPT, true>), dim3((unsigned)grid), dim3(kBlock), stream, a);
+    else
+        FS_LAUNCH("sparse_update", (sparse_update_kernel<LG, DT, OPT, false>), dim3((unsigned)grid), dim3(kBlock), stream, a);
+    return FS_OK;
+}
+
+template <int DT, int OPT>
+static fs_status launch_update(const UpdateArgs& a, hipStream_t stream)
+{
+    if (a.units > kWave) {
+        const int64_t grid = (a.cap + kWavesPerBlock - 1) / kWavesPerBlock;
+        if (grid > 0x7FFFFFFF) return FS_ERR_SIZE;
+        FS_LAUNCH("sparse_update_long", (sparse_update_long_kernel<DT, OPT>), dim3((unsigned)grid), dim3(kBlock), stream, a);
+        return FS_OK;
+    }
+    if (a.units <= 1) return launch_update_lg<1, DT, OPT>(a, stream);
+    if (a.units <= 2) return launch_update_lg<2, DT, OPT>(a, stream);
+    if (a.units <= 4) return launch_update_lg<4, DT, OPT>(a, stream);
+    if (a.units <= 8) return launch_update_lg<8, DT, OPT>(a, stream);
+    if (a.units <= 16) return launch_update_lg<16, DT, OPT>(a, stream);
+    if (a.units <= 32) return launch_update_lg<32, DT, OPT>(a, stream);
+    return launch_update_lg<64, DT, OPT>(a, stream);
+}
+
+template <int DT>
+static fs_status launch_update_opt(const UpdateArgs& a, int optimizer, hipStream_t stream)
+{
+    if (optimizer == FS_OPT_SGD) return launch_update<DT, FS_OPT_SGD>(a, stream);
+    if (optimizer == FS_OPT_ADAGRAD) return launch_update<DT, FS_OPT_ADAGRAD>(a, stream);
+    return launch_update<DT, FS_OPT_ADAGRAD_ROWWISE>(a, stream);
+}
+
+}  // namespace fs
+
+extern "C" fs_status fs_sparse_update(
+    void* weights, int64_t R, int32_t D, fs_dtype dtype,
+    const int64_t* uniq_rows, const float* row_grads, int64_t cap_unique, const int64_t* num_unique,
+    int32_t optimizer, float lr, float eps, float* state,
+    void* store, const int32_t* slot_of_row, int64_t k,
+    void* stream, int32_t* dev_status)
+{
+    using namespace fs;
+    const int es = dtype_bytes(dtype);
+    if (es == 0) return FS_ERR_DTYPE;
+    if (R < 1 || D < 1 || cap_unique < 0 || k < 0 || k >= (1LL << 31)) return FS_ERR_SIZE;
+    if (optimizer != FS_OPT_SGD && optimizer != FS_OPT_ADAGRAD && optimizer != FS_OPT_ADAGRAD_ROWWISE) return FS_ERR_CONFIG;
+    if (!weights || (cap_unique > 0 && (!uniq_rows || !row_grads))) return FS_ERR_NULL;
+    if (optimizer != FS_OPT_SGD && !state) return FS_ERR_NULL;
+    if ((store != nullptr) != (slot_of_row != nullptr)) return FS_ERR_NULL;
+    const int64_t row_bytes = (int64_t)D * es;
+    if (row_bytes % 16 != 0) return FS_ERR_ALIGN;
+    if ((reinterpret_cast<uintptr_t>(weights) | reinterpret_cast<uintptr_t>(row_grads) |
+         reinterpret_cast<uintptr_t>(store) | reinterpret_cast<uintptr_t>(state)) & 15)
+        return FS_ERR_ALIGN;
+    if (cap_unique == 0) return FS_OK;
+    UpdateArgs a;
+    a.weights = static_cast<u32x4*>(weights); a.R = R; a.units = (int)(row_bytes / 16); a.D = D;
+    a.uniq_rows = uniq_rows; a.row_grads = row_grads; a.cap = cap_unique; a.num_unique = num_unique;
+    a.lr = lr; a.eps = eps; a.state = state;
+    a.store = static_cast<u32x4*>(store); a.slot_of_row = slot_of_row; a.k = k; a.status = dev_status;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (dtype == FS_F32) return launch_update_opt<FS_F32>(a, optimizer, s);
+    if (dtype == FS_F16) return launch_update_opt<FS_F16>(a, optimizer, s);
+    return launch_update_opt<FS_BF16>(a, optimizer, s);
+}
