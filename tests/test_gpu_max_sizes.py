@@ -1,0 +1,144 @@
+"""The largest batch the interface admits, n = 2^31 - 1 lookups, through route + bucketize, gather
+and backward on one GPU: every index that could overflow 32 bits does so here if it is going to.
+
+The oracle cannot walk 2.1 billion lookups in test time, so the results are checked through
+properties that determine them completely:
+  route     bucket_offsets = running sum of the destinations' bincount; inside a bucket the positions
+            ascend; every (row, position) pair is a lookup of the batch with that destination
+            (together: the stable counting sort);
+  gather    out[i] = weights[g_i], compared in full;
+  backward  integer-valued gradients, so every summation order gives the same exact fp32 sums: the
+            rows and their sums must equal an int64 index_add of the same lookups.
+"""
+import os
+import time
+
+import numpy as np
+import pytest
+import torch
+
+from helpers import entry
+
+pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
+
+N_MAX = (1 << 31) - 1
+
+
+def _progress(msg):
+    print(msg, flush=True)
+    d = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+    if os.path.isdir(d):
+        try:
+            with open(os.path.join(d, "full_size_progress.log"), "a") as f:
+                f.write(f"{time.strftime('%H:%M:%S')} {msg}\n")
+        except OSError:
+            pass
+
+
+def test_two_billion_lookups():
+    import paper_2301_02959_amd as fs
+    dev = "cuda:0"
+    free_b, _ = torch.cuda.mem_get_info()
+    if free_b < 200e9:
+        pytest.skip(f"needs ~200 GB of free HBM, {free_b / 1e9:.0f} GB free")
+    n, R, D, U, W, self_ = N_MAX, 1 << 20, 4, 16, 4, 5
+    T, B = 2, 1 << 15
+    E = R // T
+    gen = torch.Generator(device=dev).manual_seed(7)
+    _progress(f"[max] generating {n} lookups")
+    # segment lengths: equal, the remainder on the last one; ids uniform inside each table
+    S = T * B
+    lengths = torch.full((S,), n // S, dtype=torch.int64, device=dev)
+    lengths[-1] += n - int(lengths.sum())
+    offsets = torch.zeros(S + 1, dtype=torch.int64, device=dev)
+    offsets[1:] = torch.cumsum(lengths, 0)
+    assert int(offsets[-1]) == n
+    ids = torch.randint(0, E, (n,), dtype=torch.int64, device=dev, generator=gen)
+    row_base = torch.tensor([0, E, 2 * E], dtype=torch.int64, device=dev)
+    tier = torch.randint(0, 3, (R,), dtype=torch.int64, device=dev, generator=gen)
+    owner = torch.where(tier == 2, torch.randint(0, U, (R,), device=dev, generator=gen),
+                        torch.randint(0, W, (R,), device=dev, generator=gen))
+    placement = ((tier << 30) | owner).to(torch.int32)          # bit 31 set for tier 2: same 32 bits
+    dest_of_row = torch.where(tier == 0, self_, torch.where(tier == 1, (self_ // W) * W + owner, owner)).to(torch.int16)
+    first_of_table1 = int(offsets[B])                            # lookups before it belong to table 0
+
+    # ---------------------------------------------------------------- route
+    _progress("[max] route")
+    bo = torch.zeros(U + 1, dtype=torch.int64, device=dev)
+    rows = torch.empty(n, dtype=torch.int64, device=dev)
+    pos = torch.empty(n, dtype=torch.int32, device=dev)
+    tc = torch.zeros(3, dtype=torch.int64, device=dev)
+    st = torch.zeros(1, dtype=torch.int32, device=dev)
+    assert fs.fs_route_bucketize(ids, offsets, T, B, row_base, placement, n, U, W, self_, bo, rows, pos, tc, st) == 0
+    torch.cuda.synchronize()
+    assert int(st.item()) == 0
+    _progress("[max] route: properties")
+    step = 1 << 27
+    counts = torch.zeros(U, dtype=torch.int64, device=dev)
+    tiers = torch.zeros(3, dtype=torch.int64, device=dev)
+    for lo in range(0, n, step):
+        hi = min(n, lo + step)
+        g = ids[lo:hi] + torch.where(torch.arange(lo, hi, device=dev) >= first_of_table1, E, 0)
+        counts += torch.bincount(dest_of_row[g].long(), minlength=U)
+        tiers += torch.bincount(tier[g], minlength=3)
+    assert torch.equal(bo[1:] - bo[:-1], counts) and int(bo[0]) == 0 and int(bo[-1]) == n
+    assert torch.equal(tc, tiers)
+    bo_h = bo.cpu().tolist()
+    bucket_start = torch.zeros(n + 1, dtype=torch.bool, device=dev)
+    bucket_start[torch.as_tensor(bo_h, device=dev)] = True
+    for lo in range(0, n, step):
+        hi = min(n, lo + step)
+        p = pos[lo:hi].long()
+        g = ids[p] + torch.where(p >= first_of_table1, E, 0)
+        assert torch.equal(rows[lo:hi], g), lo                                    # the pair is a lookup of the batch
+        b_of_j = torch.bucketize(torch.arange(lo, hi, device=dev), bo[1:], right=True)
+        assert torch.equal(dest_of_row[g].long(), b_of_j), lo                      # in the bucket of its destination
+        if hi - lo > 1:
+            asc = p[1:] > p[:-1]
+            assert torch.all(asc | bucket_start[lo + 1:hi]), lo                    # ascending inside a bucket
+        if lo > 0:
+            assert int(pos[lo]) > int(pos[lo - 1]) or bool(bucket_start[lo])
+    del bucket_start, counts
+    torch.cuda.empty_cache()
+
+    # ---------------------------------------------------------------- gather (16-byte rows)
+    _progress("[max] gather")
+    weights = torch.randn(R, D, device=dev, generator=gen)
+    out = torch.empty(n, D, dtype=torch.float32, device=dev)
+    assert fs.fs_seq_gather_fwd(weights, rows, pos, 0, n, out, st) == 0
+    torch.cuda.synchronize()
+    assert int(st.item()) == 0
+    _progress("[max] gather: full compare")
+    w_bits, out_bits = weights.view(torch.int32), out.view(torch.int32)
+    small = 1 << 24                      # torch's row gather refuses 2^27 indices in one call
+    for lo in range(0, n, small):
+        hi = min(n, lo + small)
+        g = ids[lo:hi] + torch.where(torch.arange(lo, hi, device=dev) >= first_of_table1, E, 0)
+        ref = torch.index_select(w_bits, 0, g)
+        assert not bool((out_bits[lo:hi] != ref).any()), lo
+    del out, weights, ids, w_bits, out_bits, ref
+    torch.cuda.empty_cache()
+
+    # ---------------------------------------------------------------- backward, integer-valued gradients
+    _progress("[max] backward")
+    grad = torch.randint(-2, 3, (n, D), device=dev, generator=gen, dtype=torch.int8).float()
+    uniq = torch.empty(R, dtype=torch.int64, device=dev)
+    rg = torch.empty(R, D, dtype=torch.float32, device=dev)
+    nu = torch.zeros(1, dtype=torch.int64, device=dev)
+    assert fs.fs_seq_grad_bwd(grad, rows, pos, 0, n, R, 0, uniq, rg, R, nu, st) == 0
+    torch.cuda.synchronize()
+    assert int(st.item()) == 0
+    _progress("[max] backward: exact sums")
+    want = torch.zeros(R, D, dtype=torch.int64, device=dev)
+    seen = torch.zeros(R, dtype=torch.int64, device=dev)
+    for lo in range(0, n, small):
+        hi = min(n, lo + small)
+        r = rows[lo:hi]
+        want.index_add_(0, r, torch.index_select(grad, 0, pos[lo:hi].long()).long())
+        seen += torch.bincount(r, minlength=R)
+    present = torch.nonzero(seen > 0).flatten()
+    k = int(nu.item())
+    assert k == present.numel() and torch.equal(uniq[:k], present)
+    assert int(want.abs().max()) < (1 << 24)                                       # every sum is an exact fp32 integer
+    assert torch.equal(rg[:k].long(), want[present]) and torch.equal(rg[:k], rg[:k].round())
+    _progress("[max] done")
