@@ -32,6 +32,9 @@ def parse():
     ap.add_argument("--config", default="c3", help="c1..c5 (c3 = the configuration the target is stated on)")
     ap.add_argument("--variant", type=int, default=0, help="backward: 0 sort/bit-exact, 1 atomic partials")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture the step in a HIP graph and time its replays (for small, launch-bound batches); the "
+                         "per-kernel events of the roofline then come from an eager pass after the timed region")
     ap.add_argument("--overlap-plan", action="store_true",
                     help="run the plan on a second stream beside the lookup path (1-2 %% faster per step, but the "
                          "gather then shares the chip and its own duration grows)")
@@ -136,13 +139,18 @@ def main():
 
     plan_calls = [0]
 
+    def plan():
+        fs.fs_plan_replication(ids, offsets, T, B, row_base, n, R, counts, plan_flags, budget_rows * row_bytes,
+                               row_bytes, sel_rows, num_selected, None, status, workspace=ws_plan)
+
     def step():
         plan_calls[0] += 1
         if plan_stream is not main_stream:
             plan_stream.wait_stream(main_stream)
-        with torch.cuda.stream(plan_stream):
-            fs.fs_plan_replication(ids, offsets, T, B, row_base, n, R, counts, plan_flags, budget_rows * row_bytes,
-                                   row_bytes, sel_rows, num_selected, None, status, workspace=ws_plan)
+            with torch.cuda.stream(plan_stream):
+                plan()
+        else:
+            plan()                                       # on whatever stream is current (a graph capture's, too)
         fs.fs_route_bucketize(ids, offsets, T, B, row_base, placement, n, U, W, self_b, bucket_offsets, out_rows,
                               out_pos, tier_counts, status, workspace=ws_route)
         fs.fs_seq_gather_fwd(weights, out_rows, out_pos, 0, n, out, status)
@@ -160,13 +168,31 @@ def main():
     # timed launch are not free: with all ~46 launches of a step timed, the step is 4 % slower).
     roof_kernels = "gather_rows,bwd_segreduce,bwd_singletons"
     records_per_step = 64
-    fs.fs_prof_begin(records_per_step * args.steps, only=roof_kernels)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
+    if args.graph:
+        # one step captured, replayed K times; HIP events recorded under capture do not yield times, so the
+        # three bandwidth kernels are event-timed in K eager steps right after the timed replays
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        graph.replay()                                   # untimed: the first launch of a graph uploads it
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        fs.fs_prof_begin(records_per_step * args.steps, only=roof_kernels)
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+    else:
+        fs.fs_prof_begin(records_per_step * args.steps, only=roof_kernels)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
     roof_records = fs.fs_prof_end(records_per_step * args.steps)
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     assert int(status.item()) == 0, f"device status {int(status.item())}"
@@ -235,7 +261,8 @@ def main():
         "config": {"workload": f"{cfg.name}: {T} tables x {cfg.E} rows x D={D} {cfg.dtype}, batch {B}, "
                                f"{cfg.length_law} lengths, Zipf({cfg.alpha}), {U} buckets (W={W})",
                    "lookups": n, "distinct_rows": n_u, "single_lookup_rows": n_1, "bwd_variant": args.variant,
-                   "schedule": "plan on a second stream beside route, gather, backward" if args.overlap_plan else "one stream",
+                   "schedule": ("plan on a second stream beside route, gather, backward" if args.overlap_plan else "one stream")
+                               + (", replayed from a HIP graph" if args.graph else ""),
                    "tier_counts": [int(x) for x in tier_counts.tolist()], "scale_rows": args.scale_rows},
         "roofline": roofline,
         "stage_ms": {k: round(v, 4) for k, v in stage_ms.items()},
