@@ -27,12 +27,14 @@ def G():
     assert torch.cuda.is_available()
     return gpu_common
 
+SCRATCH = "gpurun_out"
+
 
 def _progress(msg):
-    """Progress line for long tests: stdout (visible with -s) and, when the folder exists, a file
-    under gpurun_out/ so that a quiet minute is not mistaken for a hang."""
+    """Progress line for long tests: stdout (visible with -s) and, when the repository has a scratch
+    folder for run outputs, a file there, so that a quiet minute is not mistaken for a hang."""
     print(msg, flush=True)
-    d = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+    d = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), SCRATCH)
     if os.path.isdir(d):
         try:
             with open(os.path.join(d, "full_size_progress.log"), "a") as f:

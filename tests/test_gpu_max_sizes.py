@@ -23,10 +23,12 @@ pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
 
 N_MAX = (1 << 31) - 1
 
+SCRATCH = "gpurun_out"
+
 
 def _progress(msg):
     print(msg, flush=True)
-    d = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+    d = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), SCRATCH)
     if os.path.isdir(d):
         try:
             with open(os.path.join(d, "full_size_progress.log"), "a") as f:
