@@ -381,10 +381,10 @@ def cpu_baseline(args, cfg, ids, offsets, placement, weights, grad_out):
 
     B, E, D = cfg.B, cfg.E, cfg.D
     tables = args.cpu_tables
-    if tables <= 0:                                   # aim at ~8M lookups (about 5-10 s of one core)
+    if tables <= 0:                                   # aim at ~16M lookups (about 10 s of one core)
         per_table = max(1, int(offsets[B].item()))
-        tables = max(1, min(cfg.T, -(-8_000_000 // per_table)))
-        while tables > 1 and tables * E * cfg.row_bytes > 24e9:      # keep the host copy of the table modest
+        tables = max(1, min(cfg.T, -(-16_000_000 // per_table)))
+        while tables > 1 and tables * E * cfg.row_bytes > 48e9:      # keep the host copy of the table modest
             tables -= 1
     n_s = int(offsets[tables * B].item())
     ids_h = ids[:n_s].cpu().numpy()

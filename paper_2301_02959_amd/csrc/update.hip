@@ -7,8 +7,9 @@
 // HBM-bound read-modify-write of scattered rows: per row one fp32 gradient row in, the table row
 // in and out, the state in and out.  The layout is the gather's: a wave owns 64 consecutive
 // entries of uniq_rows, reads them with one coalesced load, hands them to groups of LG lanes with
-// ds_bpermute; a group moves one row per instruction (16 bytes of the table row per lane, i.e. 4
-// or 8 elements, and the 4 or 8 matching fp32 gradients and state values), UNR rows in flight.
+// ds_bpermute; a group moves one row per instruction (4 or 8 elements of the table row per lane and
+// the matching fp32 gradients and state values, laid out so that every load is coalesced), UNR rows
+// in flight.
 // The row-wise rule needs the row's sum of squares: a butterfly over the group's lanes.
 // Arithmetic is fp32, one IEEE operation at a time (no fused multiply-add, correctly rounded
 // division and square root); the new weight is rounded once to the table's type, to nearest even.
@@ -99,12 +100,68 @@ __device__ __forceinline__ void apply_rule(float* w, const float* g, float* s, f
     }
 }
 
+// Four consecutive elements of a table row: 16 bytes of fp32, 8 bytes of a 16-bit type.
+template <int DT>
+struct Quad {
+    typedef u32x4 type;
+    static __device__ __forceinline__ void unpack(const type& x, float* f)
+    {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) f[i] = __uint_as_float(x[i]);
+    }
+    static __device__ __forceinline__ type pack(const float* f)
+    {
+        return type{__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]), __float_as_uint(f[3])};
+    }
+};
+template <>
+struct Quad<FS_F16> {
+    typedef u32x2 type;
+    typedef _Float16 h16x4 __attribute__((ext_vector_type(4)));
+    static __device__ __forceinline__ void unpack(const type& x, float* f)
+    {
+        const h16x4 h = __builtin_bit_cast(h16x4, x);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) f[i] = (float)h[i];
+    }
+    static __device__ __forceinline__ type pack(const float* f)
+    {
+        h16x4 h;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) h[i] = (_Float16)f[i];                      // v_cvt_f16_f32: nearest even
+        return __builtin_bit_cast(type, h);
+    }
+};
+template <>
+struct Quad<FS_BF16> {
+    typedef u32x2 type;
+    static __device__ __forceinline__ void unpack(const type& x, float* f)
+    {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            f[2 * i] = __uint_as_float(x[i] << 16);
+            f[2 * i + 1] = __uint_as_float(x[i] & 0xFFFF0000u);
+        }
+    }
+    static __device__ __forceinline__ type pack(const float* f)
+    {
+        return type{Elems<FS_BF16>::bf16_bits(f[0]) | (Elems<FS_BF16>::bf16_bits(f[1]) << 16),
+                    Elems<FS_BF16>::bf16_bits(f[2]) | (Elems<FS_BF16>::bf16_bits(f[3]) << 16)};
+    }
+};
+
+// A group of LG lanes owns a row of up to LG * N elements, in quads of 4 elements: lane i takes quad
+// i of every run of LG quads (one run for fp32 tables, two for 16-bit tables), so that the fp32
+// gradient and state loads of a group are one contiguous 16 * LG bytes per instruction and the table
+// loads one contiguous 16 * LG (fp32) or 8 * LG (16-bit) bytes.
 template <int LG, int DT, int OPT, bool EXACT>
 __global__ __launch_bounds__(kBlock) void sparse_update_kernel(const UpdateArgs a)
 {
     constexpr int N = Elems<DT>::N;
+    constexpr int P = N / 4;                                         // quads per lane
     constexpr int RPI = kWave / LG;
     constexpr int UNR = LG >= 32 ? 4 : (LG >= 8 ? 2 : 1);          // row instructions in flight (2 and 8 are slower)
+    typedef typename Quad<DT>::type quad_t;
     const int lane = lane_id();
     const int64_t wbase = ((int64_t)blockIdx.x * kWavesPerBlock + wave_id()) * kWave;
     int64_t m = a.cap;
@@ -125,9 +182,18 @@ __global__ __launch_bounds__(kBlock) void sparse_update_kernel(const UpdateArgs 
     }
     const int g = lane / LG;
     const int lig = lane % LG;
-    const bool lane_on = lig < a.units;                              // units <= LG on this path
-    const int cc = lane_on ? lig : 0;
-    const int64_t stride = EXACT ? LG : a.units;
+    const int64_t D = EXACT ? LG * N : a.D;                          // elements per row
+    int col[P];                                                      // first element of the lane's quads
+    bool on[P];
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+        const int c = (p * LG + lig) * 4;
+        on[p] = c < D;                                               // rows shorter than LG * N elements leave quads idle
+        col[p] = on[p] ? c : 0;
+    }
+    const quad_t* wq = reinterpret_cast<const quad_t*>(a.weights);   // a quad is element index / 4
+    quad_t* wq_out = reinterpret_cast<quad_t*>(a.weights);
+    quad_t* store_out = reinterpret_cast<quad_t*>(a.store);
 #pragma unroll 1
     for (int s0 = 0; s0 < kWave; s0 += UNR * RPI) {
         int64_t r[UNR], u[UNR];
@@ -140,59 +206,56 @@ __global__ __launch_bounds__(kBlock) void sparse_update_kernel(const UpdateArgs 
             sl[j] = __shfl(my_slot, from);
             u[j] = ok[j] ? wbase + from : wbase;                     // an entry that is skipped reads entry wbase
         }
-        u32x4 wx[UNR];
-        f32x4 ga[UNR], gb[UNR], sa[UNR], sb[UNR];
+        quad_t wx[UNR][P];
+        f32x4 gx[UNR][P], sx[UNR][P];
         float srow[UNR];
 #pragma unroll
         for (int j = 0; j < UNR; ++j) {
-            wx[j] = a.weights[r[j] * stride + cc];
-            const float* gp = a.row_grads + u[j] * a.D + cc * N;
-            ga[j] = load_stream(reinterpret_cast<const f32x4*>(gp));
-            if constexpr (N == 8) gb[j] = load_stream(reinterpret_cast<const f32x4*>(gp + 4));
-            if constexpr (OPT == FS_OPT_ADAGRAD) {
-                const float* sp = a.state + r[j] * a.D + cc * N;
-                sa[j] = *reinterpret_cast<const f32x4*>(sp);
-                if constexpr (N == 8) sb[j] = *reinterpret_cast<const f32x4*>(sp + 4);
+#pragma unroll
+            for (int p = 0; p < P; ++p) {
+                wx[j][p] = wq[(r[j] * D + col[p]) >> 2];
+                gx[j][p] = load_stream(reinterpret_cast<const f32x4*>(a.row_grads + u[j] * D + col[p]));
+                if constexpr (OPT == FS_OPT_ADAGRAD)
+                    sx[j][p] = *reinterpret_cast<const f32x4*>(a.state + r[j] * D + col[p]);
             }
             if constexpr (OPT == FS_OPT_ADAGRAD_ROWWISE) srow[j] = a.state[r[j]];
         }
 #pragma unroll
         for (int j = 0; j < UNR; ++j) {
-            float w[N], gf[N], sf[N];
-            Elems<DT>::unpack(wx[j], w);
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                gf[i] = ga[j][i];
-                if constexpr (N == 8) gf[4 + i] = gb[j][i];
-                if constexpr (OPT == FS_OPT_ADAGRAD) {
-                    sf[i] = sa[j][i];
-                    if constexpr (N == 8) sf[4 + i] = sb[j][i];
-                }
-            }
             float s_row = 0.0f;
             if constexpr (OPT == FS_OPT_ADAGRAD_ROWWISE) {
                 float sq = 0.0f;
-                if (lane_on) {
 #pragma unroll
-                    for (int i = 0; i < N; ++i) sq = sq + gf[i] * gf[i];
+                for (int p = 0; p < P; ++p) {
+                    if (on[p]) {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) sq = sq + gx[j][p][i] * gx[j][p][i];
+                    }
                 }
 #pragma unroll
                 for (int off = 1; off < LG; off <<= 1) sq = sq + __shfl_xor(sq, off);
                 s_row = srow[j] + sq / (float)a.D;
             }
-            apply_rule<N, OPT>(w, gf, sf, s_row, a.lr, a.eps);
-            if (ok[j] && lane_on) {
-                const u32x4 out = Elems<DT>::pack(w);
-                a.weights[r[j] * stride + cc] = out;
-                if (sl[j] >= 0) a.store[(int64_t)sl[j] * stride + cc] = out;
-                if constexpr (OPT == FS_OPT_ADAGRAD) {
-                    float* sp = a.state + r[j] * a.D + cc * N;
-                    *reinterpret_cast<f32x4*>(sp) = f32x4{sf[0], sf[1], sf[2], sf[3]};
-                    if constexpr (N == 8) *reinterpret_cast<f32x4*>(sp + 4) = f32x4{sf[4], sf[5], sf[6], sf[7]};
+#pragma unroll
+            for (int p = 0; p < P; ++p) {
+                float w[4], gf[4], sf[4];
+                Quad<DT>::unpack(wx[j][p], w);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    gf[i] = gx[j][p][i];
+                    if constexpr (OPT == FS_OPT_ADAGRAD) sf[i] = sx[j][p][i];
                 }
-                if constexpr (OPT == FS_OPT_ADAGRAD_ROWWISE) {
-                    if (lig == 0) a.state[r[j]] = s_row;
+                apply_rule<4, OPT>(w, gf, sf, s_row, a.lr, a.eps);
+                if (ok[j] && on[p]) {
+                    const quad_t out = Quad<DT>::pack(w);
+                    wq_out[(r[j] * D + col[p]) >> 2] = out;
+                    if (sl[j] >= 0) store_out[((int64_t)sl[j] * D + col[p]) >> 2] = out;
+                    if constexpr (OPT == FS_OPT_ADAGRAD)
+                        *reinterpret_cast<f32x4*>(a.state + r[j] * D + col[p]) = f32x4{sf[0], sf[1], sf[2], sf[3]};
                 }
+            }
+            if constexpr (OPT == FS_OPT_ADAGRAD_ROWWISE) {
+                if (ok[j] && lig == 0) a.state[r[j]] = s_row;
             }
         }
     }
