@@ -47,21 +47,15 @@ void prof_post(hipStream_t stream)
     g_open = false;
 }
 
-// Plain copy: each thread moves 4 x 16 bytes, a block one contiguous 16 KB piece.
+// Plain copy: one 16-byte load and one 16-byte store per thread, a block one contiguous 4 KB piece.
+// Of the layouts tried (1 to 32 pieces per thread, strided or contiguous per wave, temporal or
+// non-temporal) this is the fastest on this chip, 6.3 TB/s read + write against 4.9-5.9 TB/s for the
+// others: many short-lived waves keep the reads and the writes inside a narrow moving window.
 __global__ __launch_bounds__(kBlock) void util_copy_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst,
                                                            int64_t n16)
 {
-    const int64_t base = (int64_t)blockIdx.x * kBlock * 4 + threadIdx.x;
-    if (base + 3 * kBlock < n16) {               // whole piece in range: unpredicated, 4 loads in flight
-        u32x4 v[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) v[u] = src[base + u * kBlock];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) dst[base + u * kBlock] = v[u];
-    } else {
-        for (int u = 0; u < 4; ++u)
-            if (base + u * kBlock < n16) dst[base + u * kBlock] = src[base + u * kBlock];
-    }
+    const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (i < n16) dst[i] = src[i];
 }
 
 }  // namespace fs
@@ -74,7 +68,7 @@ extern "C" fs_status fs_util_copy(void* dst, const void* src, int64_t bytes, voi
     if (!dst || !src) return FS_ERR_NULL;
     if ((bytes & 15) || ((reinterpret_cast<uintptr_t>(dst) | reinterpret_cast<uintptr_t>(src)) & 15)) return FS_ERR_ALIGN;
     const int64_t n16 = bytes / 16;
-    const int64_t grid = (n16 + kBlock * 4 - 1) / (kBlock * 4);
+    const int64_t grid = (n16 + kBlock - 1) / kBlock;
     if (grid > 0x7FFFFFFF) return FS_ERR_SIZE;
     FS_LAUNCH("util_copy", util_copy_kernel, dim3((unsigned)grid), dim3(kBlock), static_cast<hipStream_t>(stream),
               static_cast<const u32x4*>(src), static_cast<u32x4*>(dst), n16);
