@@ -1,6 +1,7 @@
 // fs_seq_gather_fwd: out[pos[j], :] = weights[rows[j], :] for j in [j0, j1), and its relatives
-// (fs_seq_gather_send, fs_seq_unbucketize, fs_replica_build, fs_seq_gather_fwd_replica), which
-// run the same kernel with one index array replaced by j itself or with a second row source.
+// fs_seq_gather_send, fs_replica_build and fs_seq_gather_fwd_replica, which run the same kernel
+// with the position replaced by j itself or with a second row source; fs_seq_unbucketize, whose row
+// loads do not wait for an index, has a kernel of its own.
 //
 // HBM-bound bit copy.  A wave owns 64 consecutive lookups: it fetches their 64 row
 // indices and 64 positions with ONE coalesced load each (a per-row index load in
@@ -77,9 +78,9 @@ __device__ __forceinline__ void gather_wave(int units, u32x4* __restrict__ out,
 // Which of the two index arrays a launch reads.
 //   kBoth:     out[pos[j]]  = weights[rows[j]]     (fs_seq_gather_fwd)
 //   kToSend:   out[j]       = weights[rows[j]]     (fs_seq_gather_send, fs_replica_build)
-//   kFromRecv: out[pos[j]]  = weights[j]           (fs_seq_unbucketize)
+//   (fs_seq_unbucketize, out[pos[j]] = recv[j], has a kernel of its own further down)
 //   kReplica:  as kBoth, but a row with slot_of_row[row] >= 0 is read from store[slot]
-enum GatherMode { kBoth = 0, kToSend = 1, kFromRecv = 2, kReplica = 3 };
+enum GatherMode { kBoth = 0, kToSend = 1, kReplica = 3 };
 
 struct GatherArgs {
     const u32x4* weights;
@@ -112,7 +113,7 @@ __global__ __launch_bounds__(kBlock) void gather_rows_kernel(const GatherArgs a)
     int32_t my_pos = 0;
     int my_ok = 0;
     if (jj < m) {
-        my_row = MODE == kFromRecv ? jj : load_stream(a.rows + jj);
+        my_row = load_stream(a.rows + jj);
         my_pos = MODE == kToSend ? (int32_t)jj : load_stream(a.pos + jj);
         // unsigned compares: one test each also catches the negative values (n < 2^31)
         my_ok = ((uint64_t)my_row < (uint64_t)a.R && (uint32_t)my_pos < (uint32_t)a.n) ? 1 : 0;
@@ -129,6 +130,46 @@ __global__ __launch_bounds__(kBlock) void gather_rows_kernel(const GatherArgs a)
     }
     if (ballot(my_ok != 0) == ~0ull) gather_wave<LG, false, EXACT>(a.units, a.out, my_src, my_pos, my_ok);
     else gather_wave<LG, true, EXACT>(a.units, a.out, my_src, my_pos, my_ok);   // ragged tail or a bad index
+}
+
+// fs_seq_unbucketize has no index in front of its row loads (row j of recv is row j), only in front
+// of its stores, so it can take the shape of the fastest plain copy: one 16-byte piece per lane and
+// instruction, waves that live for one instruction's worth of rows (64/LG of them), the position
+// load in flight together with the row load.
+template <int LG>
+__global__ __launch_bounds__(kBlock) void unbucketize_rows_kernel(const GatherArgs a)
+{
+    constexpr int RPI = kWave / LG;
+    const int64_t j = ((int64_t)blockIdx.x * kBlock + threadIdx.x) / LG;     // lookup of this lane's group
+    const int lig = threadIdx.x % LG;
+    (void)RPI;
+    if (j >= a.m) return;
+    const int32_t p = load_stream(a.pos + j);
+    for (int c = lig; c < a.units; c += LG) {
+        const u32x4 v = load_stream(a.weights + j * a.units + c);
+        if ((uint32_t)p < (uint32_t)a.n) store_stream(a.out + (int64_t)p * a.units + c, v);
+    }
+    if ((uint32_t)p >= (uint32_t)a.n && lig == 0) report(a.status, FS_DEV_BAD_ID);
+}
+
+template <int LG>
+static fs_status launch_unbucketize_lg(const GatherArgs& a, hipStream_t stream)
+{
+    const int64_t grid = (a.m * LG + kBlock - 1) / kBlock;
+    if (grid > 0x7FFFFFFF) return FS_ERR_SIZE;
+    FS_LAUNCH("unbucketize", unbucketize_rows_kernel<LG>, dim3((unsigned)grid), dim3(kBlock), stream, a);
+    return FS_OK;
+}
+
+static fs_status launch_unbucketize(const GatherArgs& a, hipStream_t s)
+{
+    if (a.units <= 1) return launch_unbucketize_lg<1>(a, s);
+    if (a.units <= 2) return launch_unbucketize_lg<2>(a, s);
+    if (a.units <= 4) return launch_unbucketize_lg<4>(a, s);
+    if (a.units <= 8) return launch_unbucketize_lg<8>(a, s);
+    if (a.units <= 16) return launch_unbucketize_lg<16>(a, s);
+    if (a.units <= 32) return launch_unbucketize_lg<32>(a, s);
+    return launch_unbucketize_lg<64>(a, s);
 }
 
 template <int LG, int MODE>
@@ -243,7 +284,7 @@ extern "C" fs_status fs_seq_unbucketize(
     a.weights = static_cast<const u32x4*>(recv); a.R = j1 - j0;
     a.pos = pos + j0; a.m = j1 - j0;
     a.out = static_cast<u32x4*>(out); a.n = n; a.status = dev_status;
-    return launch_gather<kFromRecv>(a, "unbucketize", static_cast<hipStream_t>(stream));
+    return launch_unbucketize(a, static_cast<hipStream_t>(stream));
 }
 
 extern "C" fs_status fs_replica_build(
