@@ -60,8 +60,26 @@ inline int bits_for(uint64_t max_value)   // number of bits needed to write max_
     return b;
 }
 
+// Workgroup b runs on XCD b % 8.  A kernel whose workgroup b takes tile xcd_striped_tile(b, stripe)
+// gives every XCD `stripe` consecutive tiles at a time; its grid is xcd_striped_grid(tiles, stripe)
+// workgroups, and those whose tile is >= tiles have nothing to do.
+constexpr int kXcds = 8;
+
+inline int64_t xcd_striped_grid(int64_t tiles, int stripe)
+{
+    const int64_t round = (int64_t)kXcds * stripe;
+    return (tiles + round - 1) / round * round;
+}
+
 #ifdef __HIPCC__
 // ---- device helpers ---------------------------------------------------------
+__device__ __forceinline__ int64_t xcd_striped_tile(unsigned block, int stripe)
+{
+    const int64_t x = block % kXcds;
+    const int64_t k = block / kXcds;
+    return (k / stripe) * (int64_t)(kXcds * stripe) + x * stripe + (k % stripe);
+}
+
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
 __device__ __forceinline__ int wave_id() { return threadIdx.x >> 6; }
 

@@ -118,27 +118,13 @@ struct GatherArgs {
 // heavier skew, nothing on a mid-size batch, and loses 1 % where cold reads dominate (72 M lookups
 // over 164 GB).  Stripes rather than eighths, because the j order is bucket-major: its tail, the other
 // buckets' cold rows, would otherwise all land on the last XCD.
-constexpr int kXcds = 8;
 constexpr int kXcdStripe = 32;
-
-__device__ __forceinline__ int64_t xcd_striped_tile(unsigned block)
-{
-    const int64_t x = block % kXcds;
-    const int64_t k = block / kXcds;
-    return (k / kXcdStripe) * (int64_t)(kXcds * kXcdStripe) + x * kXcdStripe + (k % kXcdStripe);
-}
-
-inline int64_t xcd_striped_grid(int64_t tiles)            // tiles rounded up to whole rounds of stripes
-{
-    const int64_t round = (int64_t)kXcds * kXcdStripe;
-    return (tiles + round - 1) / round * round;
-}
 
 template <int LG, bool EXACT, int MODE>
 __global__ __launch_bounds__(kBlock) void gather_rows_kernel(const GatherArgs a)
 {
     const int lane = lane_id();
-    const int64_t wbase = (xcd_striped_tile(blockIdx.x) * kWavesPerBlock + wave_id()) * kGatherRowsPerWave;
+    const int64_t wbase = (xcd_striped_tile(blockIdx.x, kXcdStripe) * kWavesPerBlock + wave_id()) * kGatherRowsPerWave;
     int64_t m = a.m;
     if (a.m_dev) { const int64_t md = *a.m_dev; m = md < m ? (md < 0 ? 0 : md) : m; }
     if (wbase >= m) return;                              // wave-uniform
@@ -211,7 +197,7 @@ static fs_status launch_unbucketize(const GatherArgs& a, hipStream_t s)
 template <int LG, int MODE>
 static fs_status launch_gather_lg(const GatherArgs& a, const char* name, hipStream_t stream)
 {
-    const int64_t grid = xcd_striped_grid((a.m + kGatherRowsPerBlock - 1) / kGatherRowsPerBlock);
+    const int64_t grid = xcd_striped_grid((a.m + kGatherRowsPerBlock - 1) / kGatherRowsPerBlock, kXcdStripe);
     if (grid > 0x7FFFFFFF) return FS_ERR_SIZE;
     if (a.units == LG)
         FS_LAUNCH(name, (gather_rows_kernel<LG, true, MODE>), dim3((unsigned)grid), dim3(kBlock), stream, a);
