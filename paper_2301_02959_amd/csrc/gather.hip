@@ -158,11 +158,14 @@ __global__ __launch_bounds__(kBlock) void gather_rows_kernel(const GatherArgs a)
 // of its stores, so it can take the shape of the fastest plain copy: one 16-byte piece per lane and
 // instruction, waves that live for one instruction's worth of rows (64/LG of them), the position
 // load in flight together with the row load.
+constexpr int kUnbucketizeStripe = 1024;
+
 template <int LG>
 __global__ __launch_bounds__(kBlock) void unbucketize_rows_kernel(const GatherArgs a)
 {
     constexpr int RPI = kWave / LG;
-    const int64_t j = ((int64_t)blockIdx.x * kBlock + threadIdx.x) / LG;     // lookup of this lane's group
+    // workgroups in stripes per XCD, as in the gather: 1024 of them write 4 MB of 512-byte rows (2.64 -> 2.53 ms)
+    const int64_t j = (xcd_striped_tile(blockIdx.x, kUnbucketizeStripe) * kBlock + threadIdx.x) / LG;   // this group's lookup
     const int lig = threadIdx.x % LG;
     (void)RPI;
     if (j >= a.m) return;
@@ -177,7 +180,7 @@ __global__ __launch_bounds__(kBlock) void unbucketize_rows_kernel(const GatherAr
 template <int LG>
 static fs_status launch_unbucketize_lg(const GatherArgs& a, hipStream_t stream)
 {
-    const int64_t grid = (a.m * LG + kBlock - 1) / kBlock;
+    const int64_t grid = xcd_striped_grid((a.m * LG + kBlock - 1) / kBlock, kUnbucketizeStripe);
     if (grid > 0x7FFFFFFF) return FS_ERR_SIZE;
     FS_LAUNCH("unbucketize", unbucketize_rows_kernel<LG>, dim3((unsigned)grid), dim3(kBlock), stream, a);
     return FS_OK;
