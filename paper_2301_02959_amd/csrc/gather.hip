@@ -103,6 +103,7 @@ struct GatherArgs {
     u32x4* out;
     int64_t n;
     int32_t* status;
+    int stripe;                      // workgroups per XCD stripe (1: tiles in launch order)
     const u32x4* store;              // kReplica only
     const int32_t* slot_of_row;
     int64_t k;
@@ -124,7 +125,7 @@ template <int LG, bool EXACT, int MODE>
 __global__ __launch_bounds__(kBlock) void gather_rows_kernel(const GatherArgs a)
 {
     const int lane = lane_id();
-    const int64_t wbase = (xcd_striped_tile(blockIdx.x, kXcdStripe) * kWavesPerBlock + wave_id()) * kGatherRowsPerWave;
+    const int64_t wbase = (xcd_striped_tile(blockIdx.x, a.stripe) * kWavesPerBlock + wave_id()) * kGatherRowsPerWave;
     int64_t m = a.m;
     if (a.m_dev) { const int64_t md = *a.m_dev; m = md < m ? (md < 0 ? 0 : md) : m; }
     if (wbase >= m) return;                              // wave-uniform
@@ -165,7 +166,7 @@ __global__ __launch_bounds__(kBlock) void unbucketize_rows_kernel(const GatherAr
 {
     constexpr int RPI = kWave / LG;
     // workgroups in stripes per XCD, as in the gather: 1024 of them write 4 MB of 512-byte rows (2.64 -> 2.53 ms)
-    const int64_t j = (xcd_striped_tile(blockIdx.x, kUnbucketizeStripe) * kBlock + threadIdx.x) / LG;   // this group's lookup
+    const int64_t j = (xcd_striped_tile(blockIdx.x, a.stripe) * kBlock + threadIdx.x) / LG;   // this group's lookup
     const int lig = threadIdx.x % LG;
     (void)RPI;
     if (j >= a.m) return;
@@ -178,9 +179,12 @@ __global__ __launch_bounds__(kBlock) void unbucketize_rows_kernel(const GatherAr
 }
 
 template <int LG>
-static fs_status launch_unbucketize_lg(const GatherArgs& a, hipStream_t stream)
+static fs_status launch_unbucketize_lg(const GatherArgs& a_in, hipStream_t stream)
 {
-    const int64_t grid = xcd_striped_grid((a.m * LG + kBlock - 1) / kBlock, kUnbucketizeStripe);
+    GatherArgs a = a_in;
+    const int64_t tiles = (a.m * LG + kBlock - 1) / kBlock;
+    a.stripe = tiles >= (int64_t)kXcds * kUnbucketizeStripe ? kUnbucketizeStripe : 1;
+    const int64_t grid = xcd_striped_grid(tiles, a.stripe);
     if (grid > 0x7FFFFFFF) return FS_ERR_SIZE;
     FS_LAUNCH("unbucketize", unbucketize_rows_kernel<LG>, dim3((unsigned)grid), dim3(kBlock), stream, a);
     return FS_OK;
@@ -198,9 +202,12 @@ static fs_status launch_unbucketize(const GatherArgs& a, hipStream_t s)
 }
 
 template <int LG, int MODE>
-static fs_status launch_gather_lg(const GatherArgs& a, const char* name, hipStream_t stream)
+static fs_status launch_gather_lg(const GatherArgs& a_in, const char* name, hipStream_t stream)
 {
-    const int64_t grid = xcd_striped_grid((a.m + kGatherRowsPerBlock - 1) / kGatherRowsPerBlock, kXcdStripe);
+    GatherArgs a = a_in;
+    const int64_t tiles = (a.m + kGatherRowsPerBlock - 1) / kGatherRowsPerBlock;
+    a.stripe = tiles >= (int64_t)kXcds * kXcdStripe ? kXcdStripe : 1;        // small launches are not padded
+    const int64_t grid = xcd_striped_grid(tiles, a.stripe);
     if (grid > 0x7FFFFFFF) return FS_ERR_SIZE;
     if (a.units == LG)
         FS_LAUNCH(name, (gather_rows_kernel<LG, true, MODE>), dim3((unsigned)grid), dim3(kBlock), stream, a);
