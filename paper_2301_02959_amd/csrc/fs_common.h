@@ -73,6 +73,12 @@ inline int64_t xcd_striped_grid(int64_t tiles, int stripe)
 
 #ifdef __HIPCC__
 // ---- device helpers ---------------------------------------------------------
+__device__ __forceinline__ int64_t xcd_striped_grid_dev(int64_t tiles, int stripe)
+{
+    const int64_t round = (int64_t)kXcds * stripe;
+    return (tiles + round - 1) / round * round;
+}
+
 __device__ __forceinline__ int64_t xcd_striped_tile(unsigned block, int stripe)
 {
     const int64_t x = block % kXcds;

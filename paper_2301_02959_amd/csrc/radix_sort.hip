@@ -17,6 +17,7 @@ namespace fs {
 
 constexpr int kSortWaveSpan = kWave * kSortItems;
 constexpr int kSortMaxBins = 1 << kSortMaxDigitBits;
+constexpr int kSortStripe = 16;              // tiles per XCD stripe in the scatter
 constexpr int64_t kSortMaxGrid = 8192;       // 32 blocks per CU: fills the chip, cheap when most are idle
 
 __device__ __forceinline__ int64_t sort_count_of(const int64_t* m_dev, int64_t m_max)
@@ -174,7 +175,14 @@ __global__ __launch_bounds__(kBlock) void sort_scatter_kernel(
     constexpr int kBinsPerThread = kSortMaxBins / kBlock;       // 4
     int32_t faults = 0;
 
-    for (int64_t tile = blockIdx.x; tile < used; tile += gridDim.x) {
+    // Tiles in stripes per XCD (the grid is a multiple of 8, so a block stays on its XCD over the
+    // grid stride): consecutive tiles write neighbouring runs of every digit's region, a few tens of
+    // bytes each, and one XCD's L2 then merges what four XCDs would write into one 128-byte line
+    // piece by piece (scatter 0.343 -> 0.327 ms per step on 15.7 M pairs).
+    const int64_t padded = xcd_striped_grid_dev(used, kSortStripe);
+    for (int64_t v = blockIdx.x; v < padded; v += gridDim.x) {
+        const int64_t tile = xcd_striped_tile((unsigned)v, kSortStripe);
+        if (tile >= used) continue;                              // block-uniform
         const int64_t base = tile * kSortTile;
         const int64_t wbase = base + (int64_t)w * kSortWaveSpan;
         for (int b = lane; b < bins; b += kWave) wave_hist[w][b] = 0;
@@ -311,7 +319,8 @@ fs_status radix_sort_pairs(uint32_t* keys_a, uint32_t* vals_a, uint32_t* keys_b,
 
     // blocks walk the tiles with a grid stride: when the pair count lives on the device the grid
     // is sized for m_max, and idle blocks would otherwise dominate a small sort
-    const unsigned grid = (unsigned)(tiles < kSortMaxGrid ? tiles : kSortMaxGrid);
+    const int64_t padded_tiles = xcd_striped_grid(tiles, kSortStripe);       // a multiple of 8
+    const unsigned grid = (unsigned)(padded_tiles < kSortMaxGrid ? padded_tiles : kSortMaxGrid);
     const int passes = (key_bits + kSortMaxDigitBits - 1) / kSortMaxDigitBits;
     int shift = 0;
     const bool from_rows = src.rows != nullptr;

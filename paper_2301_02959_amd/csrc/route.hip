@@ -22,6 +22,7 @@ namespace fs {
 constexpr int kRouteItems = 8;                        // lookups per thread
 constexpr int kRouteTile = kBlock * kRouteItems;      // lookups per block
 constexpr int kRouteWaveSpan = kWave * kRouteItems;   // consecutive lookups per wave
+constexpr int kRouteStripe = 32;                      // tiles per XCD stripe in the scatter
 
 __global__ __launch_bounds__(kBlock) void route_prepare_kernel(
     const int64_t* __restrict__ offsets, int64_t S, int64_t n, int32_t* status)
@@ -159,7 +160,10 @@ __global__ __launch_bounds__(kBlock) void route_scatter_kernel(
     uint32_t* bucket_base = lds;                                        // [U] first output index of the tile in bucket b
     uint16_t* wave_hist = reinterpret_cast<uint16_t*>(lds + U);         // [waves][U]
     __shared__ uint32_t scan_part[kBlock];
-    const int64_t tile = blockIdx.x;
+    // tiles in stripes per XCD: consecutive tiles write neighbouring pieces of every bucket's range,
+    // which one XCD's L2 merges into whole lines (0.082 -> 0.073 ms on 15.7 M lookups)
+    const int64_t tile = xcd_striped_tile(blockIdx.x, kRouteStripe);
+    if (tile >= tiles) return;                                          // block-uniform, before any barrier
     const int64_t base = tile * kRouteTile;
     const int w = wave_id();
     const int lane = lane_id();
@@ -285,7 +289,8 @@ extern "C" fs_status fs_route_bucketize(
                        ids, offsets, (int)T, (int64_t)B, row_base, placement, n, (int)U, (int)W, (int)self,
                        dest_bits, dest_tmp, g_tmp, tile_hist, tiles, dev_status);
         FS_LAUNCH("route_scan", route_scan_kernel, dim3((unsigned)U + 3), dim3(kBlock), s, tile_hist, tiles, totals);
-        FS_LAUNCH_SMEM("route_scatter", route_scatter_kernel, dim3((unsigned)tiles), dim3(kBlock),
+        const unsigned scatter_grid = (unsigned)xcd_striped_grid(tiles, kRouteStripe);
+        FS_LAUNCH_SMEM("route_scatter", route_scatter_kernel, dim3(scatter_grid), dim3(kBlock),
                        (size_t)U * sizeof(uint32_t) + (size_t)kWavesPerBlock * U * sizeof(uint16_t), s,
                        dest_tmp, g_tmp, n, (int)U, dest_bits, tile_hist, tiles, totals, out_rows, out_pos);
     }
