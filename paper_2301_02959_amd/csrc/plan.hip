@@ -20,7 +20,8 @@ namespace fs {
 constexpr int kHistSpan = 32768;          // ids per block
 constexpr int kHistSlots = 4096;          // LDS cache entries
 constexpr int kHistSlotBits = 12;
-constexpr int kSelTile = kBlock * 8;      // rows per block in the compaction
+constexpr int kSelTile = kBlock * 32;     // rows per block in the compaction (fewer, larger tiles: the one-block
+                                          // scan of the tile counts is what they cost)
 
 __device__ __forceinline__ void add_saturating(uint32_t* p, uint32_t v, int32_t* faults)
 {
@@ -107,7 +108,7 @@ __global__ __launch_bounds__(kHistBlock) void plan_histogram_kernel(
 }
 
 // ---- selection --------------------------------------------------------------
-// Reads counts once: the candidates of a 2048-row tile are packed, in row order, at the tile's
+// Reads counts once: the candidates of a 8192-row tile are packed, in row order, at the tile's
 // own place in a staging buffer (keys/vals at [tile * 2048 + i]) and counted.
 __global__ __launch_bounds__(kBlock) void plan_mark_kernel(
     const uint32_t* __restrict__ counts, int64_t R, int allow_zero, uint32_t* __restrict__ tile_count,
