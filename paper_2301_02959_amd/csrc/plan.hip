@@ -109,7 +109,7 @@ __global__ __launch_bounds__(kHistBlock) void plan_histogram_kernel(
 
 // ---- selection --------------------------------------------------------------
 // Reads counts once: the candidates of a 8192-row tile are packed, in row order, at the tile's
-// own place in a staging buffer (keys/vals at [tile * 2048 + i]) and counted.
+// own place in a staging buffer (keys/vals at [tile * 8192 + i]) and counted.
 __global__ __launch_bounds__(kBlock) void plan_mark_kernel(
     const uint32_t* __restrict__ counts, int64_t R, int allow_zero, uint32_t* __restrict__ tile_count,
     uint32_t* __restrict__ stage_keys, uint32_t* __restrict__ stage_vals)
