@@ -28,10 +28,7 @@ namespace fs {
 constexpr int kChunk = FS_BWD_TILE;
 constexpr int kChunksPerBlock = 64;          // bwd_count_heads: chunks per block
 constexpr int kSinglesSplit = 4;             // bwd_singletons: waves per chunk (divides kChunk / 64)
-#ifndef FS_BWD_UNROLL
-#define FS_BWD_UNROLL 8
-#endif
-constexpr int kBwdUnroll = FS_BWD_UNROLL;
+constexpr int kBwdUnroll = 8;               // rows a group keeps in flight
 constexpr uint32_t kNoKey = 0xFFFFFFFFu;     // never a row: R < 2^32 - 1
 
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
@@ -448,40 +445,45 @@ __global__ __launch_bounds__(kBlock) void bwd_singletons_kernel(
     }
 }
 
-// Does a run that starts in `chunk` go on into chunk + 1?  Returns its key through *key.
-__device__ __forceinline__ bool run_spills_from(const uint32_t* __restrict__ keys, int64_t m, int64_t chunk, uint32_t* key)
-{
-    const int64_t k0 = chunk * kChunk;
-    const int64_t k1 = k0 + kChunk;
-    if (k1 >= m) return false;
-    const uint32_t last = keys[k1 - 1];
-    if (keys[k1] != last) return false;
-    // the run's first lookup must lie in this chunk
-    if (k0 > 0 && keys[k0] == last && keys[k0 - 1] == last) return false;
-    *key = last;
-    return true;
-}
-
-// One wave per chunk; a wave whose chunk starts a spilling run adds the carries of the chunks
-// the run goes on into, left to right.
+// One wave per chunk; a wave whose chunk starts a spilling run (one that goes on into the next
+// chunk) adds the carries of the chunks the run goes on into, left to right.
 __global__ __launch_bounds__(kBlock) void bwd_fold_kernel(
     const uint32_t* __restrict__ keys, int64_t m, int64_t chunks,
     const uint32_t* __restrict__ block_base, const uint32_t* __restrict__ chunk_local,
     float* __restrict__ row_grads, int D, int64_t cap, const float* __restrict__ carry)
 {
     const int64_t chunk = (int64_t)blockIdx.x * kWavesPerBlock + wave_id();
-    if (chunk >= chunks) return;
-    uint32_t key;
-    if (!run_spills_from(keys, m, chunk, &key)) return;
+    const int64_t k0 = chunk * kChunk;
+    const int64_t k1 = k0 + kChunk;
+    if (k1 >= m) return;                                             // nothing follows this chunk
+    // Every index the decision needs, loaded in one round: a wave's time here is a chain of
+    // dependent loads, and there are as many waves as chunks.
+    const uint32_t key = keys[k1 - 1];
+    const uint32_t next = keys[k1];
+    const uint32_t head = keys[k0];
+    const uint32_t before = k0 > 0 ? keys[k0 - 1] : kNoKey;
+    const bool has_far = chunk + 2 < chunks;                         // then (chunk + 2) * kChunk < m
+    const uint32_t far = keys[has_far ? k1 + kChunk : k1];
     const int64_t u = (int64_t)runs_before(block_base, chunk_local, chunk + 1, chunks) - 1;
+    if (next != key) return;                                         // the chunk's last run ends with it
+    if (head == key && before == key) return;                        // the run started in an earlier chunk
     if (u >= cap) return;
-    // first sorted index past the run
-    int64_t lo = (chunk + 1) * kChunk, hi = m;
-    while (lo < hi) {
-        const int64_t mid = lo + ((hi - lo) >> 1);
-        if (keys[mid] == key) lo = mid + 1; else hi = mid;
+    // The last chunk whose first lookup still belongs to the run.  Most spilling runs end in the
+    // very next chunk, so the search gallops from there (1, 2, 4 .. chunks ahead) and then bisects:
+    // no further load for a short run instead of log2(m) dependent ones.
+    int64_t lo = chunk + 1, step = 1;                                // chunk lo starts inside the run
+    bool go_on = has_far && far == key;
+    while (go_on) {
+        lo += step;
+        step <<= 1;
+        go_on = lo + step < chunks && keys[(lo + step) * kChunk] == key;
     }
-    const int64_t last_chunk = (lo - 1) / kChunk;
+    int64_t hi = lo + step < chunks ? lo + step : chunks;            // chunk hi does not (or does not exist)
+    while (hi - lo > 1) {
+        const int64_t mid = lo + ((hi - lo) >> 1);
+        if (keys[mid * kChunk] == key) lo = mid; else hi = mid;
+    }
+    const int64_t last_chunk = lo;
     constexpr int kAhead = 32;                   // carries in flight: the longest run's chain is latency-bound
     for (int col = lane_id() * 4; col < D; col += kWave * 4) {
         f32x4 acc = *reinterpret_cast<const f32x4*>(row_grads + u * D + col);

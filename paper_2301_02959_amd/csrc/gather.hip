@@ -59,19 +59,10 @@ __device__ __forceinline__ void gather_wave(int units, u32x4* __restrict__ out,
         if (EXACT) {
             u32x4 v[UNR];
 #pragma unroll
-#ifdef FS_EXP_NOLOAD
-            for (int u = 0; u < UNR; ++u) v[u] = u32x4{(uint32_t)(uintptr_t)src[u], 1u, 2u, 3u};
-#else
             for (int u = 0; u < UNR; ++u) v[u] = src[u][lig];               // invalid lookups read row 0
-#endif
 #pragma unroll
-#ifdef FS_EXP_NOSTORE
-            for (int u = 0; u < UNR; ++u)
-                if ((!GUARD || ok[u]) && v[u][0] == 0x12345678u) store_stream(out + dst[u] + lig, v[u]);
-#else
             for (int u = 0; u < UNR; ++u)
                 if (!GUARD || ok[u]) store_stream(out + dst[u] + lig, v[u]);
-#endif
         } else {
             for (int c = lig; c < units; c += LG) {
                 u32x4 v[UNR];
@@ -164,11 +155,9 @@ constexpr int kUnbucketizeStripe = 1024;
 template <int LG>
 __global__ __launch_bounds__(kBlock) void unbucketize_rows_kernel(const GatherArgs a)
 {
-    constexpr int RPI = kWave / LG;
     // workgroups in stripes per XCD, as in the gather: 1024 of them write 4 MB of 512-byte rows (2.64 -> 2.53 ms)
     const int64_t j = (xcd_striped_tile(blockIdx.x, a.stripe) * kBlock + threadIdx.x) / LG;   // this group's lookup
     const int lig = threadIdx.x % LG;
-    (void)RPI;
     if (j >= a.m) return;
     const int32_t p = load_stream(a.pos + j);
     for (int c = lig; c < a.units; c += LG) {
