@@ -73,10 +73,10 @@ __global__ __launch_bounds__(kBlock) void sort_count_kernel(
     Reader in, int64_t m_max, const int64_t* __restrict__ m_dev,
     int shift, uint32_t* __restrict__ tile_hist /* [tiles][bins] */)
 {
-    __shared__ uint32_t hist[kSortMaxBins];
+    constexpr int bins = 1 << NBITS;
+    __shared__ uint32_t hist[bins];
     const int64_t m = sort_count_of(m_dev, m_max);
     const int64_t used = (m + kSortTile - 1) / kSortTile;      // tiles that hold pairs (m may live on the device)
-    constexpr int bins = 1 << NBITS;
     constexpr uint32_t mask = (uint32_t)bins - 1u;
     for (int64_t tile = blockIdx.x; tile < used; tile += gridDim.x) {
         const int64_t base = tile * kSortTile;
@@ -160,19 +160,19 @@ __global__ __launch_bounds__(kBlock) void sort_scatter_kernel(
     const uint32_t* __restrict__ tile_hist /* scanned */, const uint32_t* __restrict__ chunk_sums /* scanned */,
     const uint32_t* __restrict__ totals, uint32_t* __restrict__ keys_out, uint32_t* __restrict__ vals_out, int32_t* status)
 {
-    __shared__ uint32_t out_base[kSortMaxBins];                 // global index of the tile's first pair of a digit,
+    constexpr int bins = 1 << NBITS;
+    __shared__ uint32_t out_base[bins];                         // global index of the tile's first pair of a digit,
                                                                 // minus the digit's first index inside the tile
-    __shared__ uint16_t wave_hist[kWavesPerBlock][kSortMaxBins];
+    __shared__ uint16_t wave_hist[kWavesPerBlock][bins];
     __shared__ uint32_t s_key[kSortTile];
     __shared__ uint32_t s_val[kSortTile];
     __shared__ uint32_t wave_sums[16];
     const int64_t m = sort_count_of(m_dev, m_max);
     const int64_t used = (m + kSortTile - 1) / kSortTile;
-    constexpr int bins = 1 << NBITS;
     constexpr uint32_t mask = (uint32_t)bins - 1u;
     const int w = wave_id();
     const int lane = lane_id();
-    constexpr int kBinsPerThread = kSortMaxBins / kBlock;       // 4
+    constexpr int kBinsPerThread = (bins + kBlock - 1) / kBlock;
     int32_t faults = 0;
 
     // Tiles in stripes per XCD (the grid is a multiple of 8, so a block stays on its XCD over the
