@@ -112,7 +112,9 @@ enum {
  * tier_counts[3] (may be NULL) = lookups per tier, overwritten.
  *
  * Data faults: an id outside [0, E_t) is routed as row row_base[t]
- * (FS_DEV_BAD_ID); tier 3, owner >= U (tier 2) or owner >= W (tier 1) is
+ * (FS_DEV_BAD_ID); a row_base that is not ascending, or row_base[T] outside
+ * [1, 2^32 - 1): the lookups it takes out of [0, row_base[T]) are routed as
+ * row 0 (FS_DEV_BAD_ID); tier 3, owner >= U (tier 2) or owner >= W (tier 1) is
  * routed to `self` (FS_DEV_BAD_PLACEMENT; tier 3 is counted under tier 0);
  * bad offsets set FS_DEV_BAD_OFFSETS and leave the outputs unspecified but
  * written in bounds.
@@ -274,6 +276,9 @@ fs_status fs_seq_grad_bwd(
  *   flags & FS_PLAN_TAG         (with SELECT) the tier bits of placement[g]
  *                               are set to 0 for the k selected rows.
  * Pointers a flag does not use may be NULL.
+ * Data faults: an id outside its table is counted as the table's first row,
+ * a row_base that takes a lookup outside [0, R) drops it (both FS_DEV_BAD_ID);
+ * bad offsets (FS_DEV_BAD_OFFSETS) count nothing.
  * Host faults: NULL; n, R, T, B as above; budget_bytes < 0 or
  * bytes_per_row < 1 (FS_ERR_SIZE); unknown flag bits, TAG without SELECT
  * (FS_ERR_CONFIG).

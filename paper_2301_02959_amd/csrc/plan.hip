@@ -57,7 +57,7 @@ constexpr int kHistBlock = 1024;          // 16 waves per span: a span per 256 t
 
 __global__ __launch_bounds__(kHistBlock) void plan_histogram_kernel(
     const int64_t* __restrict__ ids, const int64_t* __restrict__ offsets, int T, int64_t B,
-    const int64_t* __restrict__ row_base, int64_t n, uint32_t* __restrict__ counts,
+    const int64_t* __restrict__ row_base, int64_t n, int64_t R, uint32_t* __restrict__ counts,
     const int32_t* __restrict__ ok_flag, int32_t* status)
 {
     __shared__ uint32_t tags[kHistSlots];      // row + 1, 0 = free
@@ -81,6 +81,7 @@ __global__ __launch_bounds__(kHistBlock) void plan_histogram_kernel(
         const int64_t first = row_base[t];
         const int64_t rows_t = row_base[t + 1] - first;
         if (id < 0 || id >= rows_t) { faults |= FS_DEV_BAD_ID; id = 0; }
+        if ((uint64_t)(first + id) >= (uint64_t)R) { faults |= FS_DEV_BAD_ID; return; }   // row_base does not fit R
         const uint32_t g = (uint32_t)(first + id);
         const uint32_t slot = (g * 2654435761u) >> (32 - kHistSlotBits);
         uint32_t tag = tags[slot];
@@ -467,7 +468,7 @@ extern "C" fs_status fs_plan_replication(
         if (n > 0) {
             const int64_t blocks = (n + kHistSpan - 1) / kHistSpan;
             FS_LAUNCH("plan_histogram", plan_histogram_kernel, dim3((unsigned)blocks), dim3(kHistBlock), s,
-                      ids, offsets, (int)T, (int64_t)B, row_base, n, counts, ok_flag, dev_status);
+                      ids, offsets, (int)T, (int64_t)B, row_base, n, R, counts, ok_flag, dev_status);
         }
     }
     if (sel) {

@@ -70,7 +70,9 @@ __global__ __launch_bounds__(kBlock) void route_remap_kernel(
     const int t_lo = tile_tables[0];
     const int t_hi = tile_tables[1];
     const int group_base = (self / W) * W;
-    int32_t faults = 0;
+    const int64_t R_all = row_base[T];                // rows of all tables; g must stay below it (and below 2^32 - 1)
+    const bool rows_ok = R_all >= 1 && R_all < 4294967295LL;
+    int32_t faults = rows_ok ? 0 : FS_DEV_BAD_ID;
     unsigned int tiers[3] = {0, 0, 0};
 
 #pragma unroll 2
@@ -85,8 +87,9 @@ __global__ __launch_bounds__(kBlock) void route_remap_kernel(
             const int64_t rows_t = row_base[t + 1] - first;
             int64_t id = load_stream(ids + i);
             if (id < 0 || id >= rows_t) { faults |= FS_DEV_BAD_ID; id = 0; }
-            const int64_t g = first + id;
-            const uint32_t e = placement[g];
+            int64_t g = first + id;
+            if ((uint64_t)g >= (uint64_t)R_all) { faults |= FS_DEV_BAD_ID; g = 0; }   // row_base not ascending
+            const uint32_t e = rows_ok ? placement[g] : 0u;
             const uint32_t tier = e >> FS_TIER_SHIFT;
             const uint32_t owner = e & FS_OWNER_MASK;
             if (tier == FS_TIER_GLOBAL) {

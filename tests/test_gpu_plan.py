@@ -122,3 +122,18 @@ def test_saturation_faults_and_one_call_does_all(G):
     assert hip_plan(G, None, None, 1, 1, None, 4, z, S, 1, 0)[0] == 2
     assert hip_plan(G, None, None, 1, 1, None, 4, z, S | TAG, 1, 1)[0] == 1
     assert hip_plan(G, None, None, 1, 1, None, 4, z, 0)[0] == 0
+
+
+def test_histogram_row_base_beyond_R_drops_the_lookup(G):
+    """row_base that does not fit R: the lookups it takes outside [0, R) are dropped and reported."""
+    import paper_2301_02959_amd as fs
+    T, B, R = 2, 3, 60
+    ids = np.array([1, 2, 3, 4, 5, 6, 7, 8], dtype=np.int64)
+    offsets = np.array([0, 2, 3, 4, 6, 7, 8], dtype=np.int64)     # table 0: ids[0:4], table 1: ids[4:8]
+    row_base = np.array([0, 58, 70], dtype=np.int64)              # table 1 claims rows 58 .. 69, R is 60
+    counts = np.zeros(R, dtype=np.uint32)
+    rc, st, got, _, _ = hip_plan(G, ids, offsets, T, B, row_base, R, counts, A)
+    assert rc == 0 and st & fs.FS_DEV_BAD_ID
+    want = np.zeros(R, dtype=np.uint32)
+    want[[1, 2, 3, 4]] = 1                                        # table 0
+    assert np.array_equal(got, want)                              # 58 + 5 .. 58 + 8 are all >= 60: dropped

@@ -179,3 +179,23 @@ def test_route_then_gather_c1_end_to_end(G):
     mine = torch.zeros(b["n"], dtype=torch.bool)
     mine[pos[lo:hi].cpu().long()] = True
     assert torch.equal(out.cpu()[mine], Wt[b["ids"]][mine]) and torch.all(out.cpu()[~mine] == 5.0)
+
+
+def test_route_row_base_out_of_order_stays_in_bounds(G):
+    """A row_base that is not ascending takes lookups out of [0, row_base[T]): they are routed as row 0
+    and reported, every output stays in range."""
+    import paper_2301_02959_amd as fs
+    rng = np.random.default_rng(77)
+    T, B, U, W = 2, 40, 8, 4
+    ids, offsets, _, n = random_jagged(rng, T, B, 50, 30)
+    row_base = np.array([0, 100, 50], dtype=np.int64)            # table 1 would start past the end
+    pl = random_placement(rng, 50, U, W)                          # row_base[T] = 50 placement entries
+    rc, st, bo, rows, pos, tc = G.hip_route(G.to_dev(ids, torch.int64), G.to_dev(offsets, torch.int64), T, B,
+                                            G.to_dev(row_base, torch.int64), G.placement_dev(pl), U, W, 3, n=n)
+    assert rc == 0 and st & fs.FS_DEV_BAD_ID
+    rows = rows.cpu().numpy(); pos = pos.cpu().numpy(); bo = bo.cpu().numpy()
+    assert rows.min() >= 0 and rows.max() < 50
+    assert np.array_equal(np.sort(pos), np.arange(n))
+    assert bo[0] == 0 and bo[-1] == n and np.all(np.diff(bo) >= 0)
+    second = np.arange(n) >= offsets[B]                           # lookups of table 1
+    assert np.all(rows[np.isin(pos, np.nonzero(second)[0])] == 0)
