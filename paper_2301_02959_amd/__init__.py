@@ -65,10 +65,23 @@ def lib() -> ctypes.CDLL:
     return _lib
 
 
-def _ptr(t: Optional[torch.Tensor]) -> ctypes.c_void_p:
+_I64 = (torch.int64,)
+_I32 = (torch.int32,)
+_U32 = (torch.int32, torch.uint32)          # 32-bit words: torch code usually holds them as int32
+_F32 = (torch.float32,)
+_ROWS = (torch.float32, torch.float16, torch.bfloat16)
+
+
+def _ptr(t: Optional[torch.Tensor], dtypes: Optional[tuple] = None) -> ctypes.c_void_p:
+    """Device pointer of a contiguous CUDA tensor (None -> NULL); `dtypes`: the element types the C side reads."""
     if t is None:
         return ctypes.c_void_p(0)
-    assert t.is_contiguous(), "tensors must be contiguous"
+    if not t.is_cuda:
+        raise TypeError("the library takes device memory: got a tensor on " + str(t.device))
+    if not t.is_contiguous():
+        raise TypeError("tensors must be contiguous")
+    if dtypes is not None and t.dtype not in dtypes:
+        raise TypeError(f"expected a tensor of {' or '.join(str(d) for d in dtypes)}, got {t.dtype}")
     return ctypes.c_void_p(t.data_ptr())
 
 
@@ -99,10 +112,10 @@ def fs_route_bucketize(ids, offsets, T: int, B: int, row_base, placement, n: int
 
     def call(ws_ptr, ws_size_ref):
         return L.fs_route_bucketize(
-            _ptr(ids), _ptr(offsets), ctypes.c_int32(T), ctypes.c_int32(B), _ptr(row_base), _ptr(placement),
+            _ptr(ids, _I64), _ptr(offsets, _I64), ctypes.c_int32(T), ctypes.c_int32(B), _ptr(row_base, _I64), _ptr(placement, _U32),
             ctypes.c_int64(n), ctypes.c_int32(U), ctypes.c_int32(W), ctypes.c_int32(self_),
-            _ptr(bucket_offsets), _ptr(out_rows), _ptr(out_pos), _ptr(tier_counts),
-            ws_ptr, ws_size_ref, _stream(), _ptr(dev_status))
+            _ptr(bucket_offsets, _I64), _ptr(out_rows, _I64), _ptr(out_pos, _I32), _ptr(tier_counts, _I64),
+            ws_ptr, ws_size_ref, _stream(), _ptr(dev_status, _I32))
 
     if workspace is None:
         workspace, size, code = _workspace(call, offsets.device)
@@ -131,8 +144,8 @@ def fs_seq_gather_fwd(weights, rows, pos, j0: int, j1: int, out, dev_status=None
     n = out.shape[0] if n is None else n
     dtype = _DTYPES[weights.dtype] if dtype is None else dtype
     code = lib().fs_seq_gather_fwd(
-        _ptr(weights), ctypes.c_int64(R), ctypes.c_int32(D), ctypes.c_int(dtype), _ptr(rows), _ptr(pos),
-        ctypes.c_int64(j0), ctypes.c_int64(j1), _ptr(out), ctypes.c_int64(n), _stream(), _ptr(dev_status))
+        _ptr(weights, _ROWS), ctypes.c_int64(R), ctypes.c_int32(D), ctypes.c_int(dtype), _ptr(rows, _I64), _ptr(pos, _I32),
+        ctypes.c_int64(j0), ctypes.c_int64(j1), _ptr(out, _ROWS), ctypes.c_int64(n), _stream(), _ptr(dev_status, _I32))
     return _check("fs_seq_gather_fwd", code, raise_on_error)
 
 
@@ -142,8 +155,8 @@ def fs_seq_gather_send(weights, rows, j0: int, j1: int, send, dev_status=None, r
     D = weights.shape[1] if D is None else D
     dtype = _DTYPES[weights.dtype] if dtype is None else dtype
     code = lib().fs_seq_gather_send(
-        _ptr(weights), ctypes.c_int64(R), ctypes.c_int32(D), ctypes.c_int(dtype), _ptr(rows),
-        ctypes.c_int64(j0), ctypes.c_int64(j1), _ptr(send), _stream(), _ptr(dev_status))
+        _ptr(weights, _ROWS), ctypes.c_int64(R), ctypes.c_int32(D), ctypes.c_int(dtype), _ptr(rows, _I64),
+        ctypes.c_int64(j0), ctypes.c_int64(j1), _ptr(send, _ROWS), _stream(), _ptr(dev_status, _I32))
     return _check("fs_seq_gather_send", code, raise_on_error)
 
 
@@ -153,8 +166,8 @@ def fs_seq_unbucketize(recv, pos, j0: int, j1: int, out, dev_status=None, raise_
     n = out.shape[0] if n is None else n
     dtype = _DTYPES[recv.dtype] if dtype is None else dtype
     code = lib().fs_seq_unbucketize(
-        _ptr(recv), ctypes.c_int32(D), ctypes.c_int(dtype), _ptr(pos), ctypes.c_int64(j0), ctypes.c_int64(j1),
-        _ptr(out), ctypes.c_int64(n), _stream(), _ptr(dev_status))
+        _ptr(recv, _ROWS), ctypes.c_int32(D), ctypes.c_int(dtype), _ptr(pos, _I32), ctypes.c_int64(j0), ctypes.c_int64(j1),
+        _ptr(out, _ROWS), ctypes.c_int64(n), _stream(), _ptr(dev_status, _I32))
     return _check("fs_seq_unbucketize", code, raise_on_error)
 
 
@@ -165,8 +178,8 @@ def fs_replica_build(weights, sel_rows, k: int, num_selected, store, slot_of_row
     D = weights.shape[1] if D is None else D
     dtype = _DTYPES[weights.dtype] if dtype is None else dtype
     code = lib().fs_replica_build(
-        _ptr(weights), ctypes.c_int64(R), ctypes.c_int32(D), ctypes.c_int(dtype), _ptr(sel_rows),
-        ctypes.c_int64(k), _ptr(num_selected), _ptr(store), _ptr(slot_of_row), _stream(), _ptr(dev_status))
+        _ptr(weights, _ROWS), ctypes.c_int64(R), ctypes.c_int32(D), ctypes.c_int(dtype), _ptr(sel_rows, _I64),
+        ctypes.c_int64(k), _ptr(num_selected, _I64), _ptr(store, _ROWS), _ptr(slot_of_row, _I32), _stream(), _ptr(dev_status, _I32))
     return _check("fs_replica_build", code, raise_on_error)
 
 
@@ -179,9 +192,9 @@ def fs_seq_gather_fwd_replica(weights, store, k: int, slot_of_row, rows, pos, j0
     n = out.shape[0] if n is None else n
     dtype = _DTYPES[weights.dtype] if dtype is None else dtype
     code = lib().fs_seq_gather_fwd_replica(
-        _ptr(weights), ctypes.c_int64(R), ctypes.c_int32(D), ctypes.c_int(dtype), _ptr(store), ctypes.c_int64(k),
-        _ptr(slot_of_row), _ptr(rows), _ptr(pos), ctypes.c_int64(j0), ctypes.c_int64(j1), _ptr(out),
-        ctypes.c_int64(n), _stream(), _ptr(dev_status))
+        _ptr(weights, _ROWS), ctypes.c_int64(R), ctypes.c_int32(D), ctypes.c_int(dtype), _ptr(store, _ROWS), ctypes.c_int64(k),
+        _ptr(slot_of_row, _I32), _ptr(rows, _I64), _ptr(pos, _I32), ctypes.c_int64(j0), ctypes.c_int64(j1), _ptr(out, _ROWS),
+        ctypes.c_int64(n), _stream(), _ptr(dev_status, _I32))
     return _check("fs_seq_gather_fwd_replica", code, raise_on_error)
 
 
@@ -196,10 +209,10 @@ def fs_seq_grad_bwd(grad_out, rows, pos, j0: int, j1: int, R: int, variant: int,
 
     def call(ws_ptr, ws_size_ref):
         return L.fs_seq_grad_bwd(
-            _ptr(grad_out), ctypes.c_int64(n), ctypes.c_int32(D), ctypes.c_int(dtype), _ptr(rows), _ptr(pos),
+            _ptr(grad_out, _ROWS), ctypes.c_int64(n), ctypes.c_int32(D), ctypes.c_int(dtype), _ptr(rows, _I64), _ptr(pos, _I32),
             ctypes.c_int64(j0), ctypes.c_int64(j1), ctypes.c_int64(R), ctypes.c_int32(variant),
-            _ptr(uniq_rows), _ptr(row_grads), ctypes.c_int64(cap_unique), _ptr(num_unique),
-            ws_ptr, ws_size_ref, _stream(), _ptr(dev_status))
+            _ptr(uniq_rows, _I64), _ptr(row_grads, _F32), ctypes.c_int64(cap_unique), _ptr(num_unique, _I64),
+            ws_ptr, ws_size_ref, _stream(), _ptr(dev_status, _I32))
 
     if workspace is None:
         workspace, size, code = _workspace(call, grad_out.device)
@@ -218,10 +231,10 @@ def fs_plan_replication(ids, offsets, T: int, B: int, row_base, n: int, R: int, 
 
     def call(ws_ptr, ws_size_ref):
         return L.fs_plan_replication(
-            _ptr(ids), _ptr(offsets), ctypes.c_int32(T), ctypes.c_int32(B), _ptr(row_base), ctypes.c_int64(n),
-            ctypes.c_int64(R), _ptr(counts), ctypes.c_int32(flags), ctypes.c_int64(budget_bytes),
-            ctypes.c_int64(bytes_per_row), _ptr(sel_rows), _ptr(num_selected), _ptr(placement),
-            ws_ptr, ws_size_ref, _stream(), _ptr(dev_status))
+            _ptr(ids, _I64), _ptr(offsets, _I64), ctypes.c_int32(T), ctypes.c_int32(B), _ptr(row_base, _I64), ctypes.c_int64(n),
+            ctypes.c_int64(R), _ptr(counts, _U32), ctypes.c_int32(flags), ctypes.c_int64(budget_bytes),
+            ctypes.c_int64(bytes_per_row), _ptr(sel_rows, _I64), _ptr(num_selected, _I64), _ptr(placement, _U32),
+            ws_ptr, ws_size_ref, _stream(), _ptr(dev_status, _I32))
 
     if workspace is None:
         workspace, size, code = _workspace(call, counts.device)
@@ -245,9 +258,9 @@ def fs_plan_tiers(counts, R: int, params: dict, tiers: int, sorted_rows, cap: in
     tp = TierParams(**params)
 
     def call(ws_ptr, ws_size_ref):
-        return L.fs_plan_tiers(_ptr(counts), ctypes.c_int64(R), ctypes.byref(tp), ctypes.c_int32(tiers),
-                               _ptr(sorted_rows), ctypes.c_int64(cap), _ptr(cuts), _ptr(placement),
-                               ws_ptr, ws_size_ref, _stream(), _ptr(dev_status))
+        return L.fs_plan_tiers(_ptr(counts, _U32), ctypes.c_int64(R), ctypes.byref(tp), ctypes.c_int32(tiers),
+                               _ptr(sorted_rows, _I64), ctypes.c_int64(cap), _ptr(cuts, _I64), _ptr(placement, _U32),
+                               ws_ptr, ws_size_ref, _stream(), _ptr(dev_status, _I32))
 
     if workspace is None:
         device = next((t.device for t in (counts, cuts, sorted_rows) if t is not None), "cuda")
@@ -267,9 +280,9 @@ def fs_sparse_update(weights, uniq_rows, row_grads, cap_unique: int, num_unique,
     D = weights.shape[1] if D is None else D
     dtype = _DTYPES[weights.dtype] if dtype is None else dtype
     code = lib().fs_sparse_update(
-        _ptr(weights), ctypes.c_int64(R), ctypes.c_int32(D), ctypes.c_int(dtype), _ptr(uniq_rows), _ptr(row_grads),
-        ctypes.c_int64(cap_unique), _ptr(num_unique), ctypes.c_int32(optimizer), ctypes.c_float(lr), ctypes.c_float(eps),
-        _ptr(state), _ptr(store), _ptr(slot_of_row), ctypes.c_int64(k), _stream(), _ptr(dev_status))
+        _ptr(weights, _ROWS), ctypes.c_int64(R), ctypes.c_int32(D), ctypes.c_int(dtype), _ptr(uniq_rows, _I64), _ptr(row_grads, _F32),
+        ctypes.c_int64(cap_unique), _ptr(num_unique, _I64), ctypes.c_int32(optimizer), ctypes.c_float(lr), ctypes.c_float(eps),
+        _ptr(state, _F32), _ptr(store, _ROWS), _ptr(slot_of_row, _I32), ctypes.c_int64(k), _stream(), _ptr(dev_status, _I32))
     return _check("fs_sparse_update", code, raise_on_error)
 
 

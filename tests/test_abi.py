@@ -47,3 +47,16 @@ def test_oracle_and_library_constants_agree_by_value():
                                   fs.FS_DEV_COUNT_OVERFLOW, fs.FS_DEV_UNIQUE_OVERFLOW, fs.FS_DEV_POS_ORDER)
     assert oracle.BWD_TILE == fs.FS_BWD_TILE
     assert (oracle.F32, oracle.F16, oracle.BF16) == (fs.FS_F32, fs.FS_F16, fs.FS_BF16)
+
+
+@pytest.mark.skipif(not os.path.exists(LIB), reason="library not built (run __graft_entry__.build())")
+def test_binding_refuses_host_tensors_and_wrong_element_types():
+    """The binding passes device pointers through: a host tensor or a wrong element type never reaches the library."""
+    import torch
+    import paper_2301_02959_amd as fs
+    host = torch.zeros(64, dtype=torch.uint8)
+    with pytest.raises(TypeError):
+        fs.fs_util_copy(host, host)
+    w = torch.zeros(4, 8)
+    with pytest.raises(TypeError):
+        fs.fs_seq_gather_fwd(w, torch.zeros(1, dtype=torch.int64), torch.zeros(1, dtype=torch.int32), 0, 1, w.clone())
