@@ -296,7 +296,7 @@ __global__ __launch_bounds__(kBlock) void sparse_update_long_kernel(const Update
     }
     for (int c = lane; c < a.units; c += kWave) {
         float w[N], gf[N], sf[N];
-        Elems<DT>::unpack(a.weights[r * a.units + c], w);
+        Elems<DT>::unpack(load_stream(a.weights + r * a.units + c), w);    // read and written once: non-temporal
         const float* gp = a.row_grads + u * a.D + c * N;
         float* sp = a.state + r * a.D + c * N;
 #pragma unroll
@@ -306,7 +306,7 @@ __global__ __launch_bounds__(kBlock) void sparse_update_long_kernel(const Update
         }
         apply_rule<N, OPT>(w, gf, sf, s_row, a.lr, a.eps);
         const u32x4 out = Elems<DT>::pack(w);
-        a.weights[r * a.units + c] = out;
+        store_stream(a.weights + r * a.units + c, out);
         if (slot >= 0) a.store[(int64_t)slot * a.units + c] = out;
         if constexpr (OPT == FS_OPT_ADAGRAD) {
 #pragma unroll
