@@ -292,7 +292,13 @@ __device__ __forceinline__ int64_t wave_partition_point(int64_t lo, int64_t hi, 
         const int64_t step = (hi - lo + kWave - 1) / kWave;
         const int64_t probe = lo + (int64_t)(lane + 1) * step - 1;      // last index of this lane's piece
         const bool holds = probe < hi ? pred(probe) : false;
-        const int pieces = __popcll(ballot(holds));                      // whole pieces on which pred holds
+        int pieces = __popcll(ballot(holds));                            // whole pieces on which pred holds
+        // The count is the same in every lane, and left to itself the compiler does the two bound updates
+        // below in scalar registers, where (hipcc of ROCm 7.2, gfx950) the second of two back-to-back
+        // 64-bit compare-and-selects reuses the first one's condition bit: lo then takes hi's branch
+        // whenever the probe past new_lo lies outside the range.  Held in a vector register the count
+        // makes them vector selects.
+        asm volatile("" : "+v"(pieces));
         const int64_t new_lo = lo + (int64_t)pieces * step;
         const int64_t first_false_probe = new_lo + step - 1;
         hi = first_false_probe < hi ? first_false_probe : hi;

@@ -185,3 +185,25 @@ def test_c3_profile_of_one_batch(G):
         assert int(st.item()) == 0
         assert tc.tolist() == [int(cuts[fs.FS_CUT_SUM_DP]), int(cuts[fs.FS_CUT_SUM_FLEX]),
                                n - int(cuts[fs.FS_CUT_SUM_DP]) - int(cuts[fs.FS_CUT_SUM_FLEX])]
+
+
+def test_breakpoints_at_every_position(G):
+    """Points A and C on every index of the sorted candidates in turn (all of them for short lists, both ends and a
+    stride for long ones): the 64-way searches must land exactly there, whatever the list length is modulo 64."""
+    p = params(num_samples=100, B=4, U=4, W=2, dp_multiplier=6, granule=1,
+               a2a_global=30, a2a_intra=40, ar_global=1, ar_cross=20)
+    # smallest count at or above the breakpoint: A ceil(23 * 100 / 16) = 144, C ceil(30 * 100 / 8) = 375
+    rng = np.random.default_rng(5)
+    for K in (1, 2, 63, 64, 65, 66, 127, 128, 129, 381, 4095, 4096, 4097):
+        where = range(K + 1) if K <= 129 else sorted(set(range(0, 70)) | set(range(K - 70, K + 1)) | set(range(0, K + 1, 97)))
+        perm = rng.permutation(K)
+        for F in where:
+            for low, high in ((100, 200), (200, 400)):            # A at F (C nowhere); C at F (A everywhere)
+                counts = np.full(K, low, np.uint32)
+                counts[perm[:F]] = high
+                rc, cuts = both(G, counts, p, 2, cap=0, tag=False)
+                assert rc == 0
+                if low == 100:
+                    assert cuts[1] == F and cuts[3] == 0
+                else:
+                    assert cuts[1] == K and cuts[3] == F
