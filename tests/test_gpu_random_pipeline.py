@@ -54,7 +54,7 @@ def _case(rng):
                 placement=random_placement(rng, T * E, U, W, p=rng.dirichlet([1, 1, 1])))
 
 
-@pytest.mark.parametrize("seed", range(24))
+@pytest.mark.parametrize("seed", range(60))
 def test_random_pipeline(G, seed):
     import paper_2301_02959_amd as fs
     rng = np.random.default_rng(1000 + seed)

@@ -52,20 +52,26 @@ def both(G, counts, p, tiers, cap=None, tag=True):
     return rc, cuts
 
 
-@pytest.mark.parametrize("seed", range(10))
-def test_random_small(G, seed):
-    rng = np.random.default_rng(seed)
-    R = int(rng.integers(1, 9000))
-    S = int(rng.integers(50, 4000))
-    counts = np.minimum(rng.pareto(0.8, R) * rng.integers(1, 30), 4 * S).astype(np.uint32)
-    counts[rng.random(R) < 0.2] = 0
-    U = int(rng.choice([1, 2, 4, 8, 32]))
-    W = int(rng.choice([w for w in (1, 2, 4, 8) if U % w == 0]))
-    p = params(num_samples=S, B=int(rng.integers(1, 300)), U=U, W=W, dp_multiplier=int(rng.integers(1, 8)),
-               granule=int(rng.choice([1, 2, 3, 32])), a2a_global=int(rng.integers(1, 30)),
-               a2a_intra=int(rng.integers(1, 90)), ar_global=int(rng.integers(1, 90)), ar_cross=int(rng.integers(1, 60)))
-    for tiers in (2, 3):
-        both(G, counts, p, tiers)
+@pytest.mark.parametrize("block", range(10))
+def test_random_small(G, block):
+    """Thirty random parameter sets per block: list lengths around the multiples of 64 and 4096, all-equal and
+    mostly-zero counts, every tier count, capacities and with or without tags."""
+    for seed in range(30 * block, 30 * block + 30):
+        rng = np.random.default_rng(10_000 + seed)
+        R = int(rng.choice([1, 2, 63, 64, 65, 4095, 4096, 4097, int(rng.integers(1, 60000))]))
+        S = int(rng.integers(1, 6000))
+        scale = int(rng.integers(1, 60))
+        counts = np.minimum(rng.pareto(rng.choice([0.5, 0.8, 1.2, 2.0]), R) * scale, 4 * S).astype(np.uint32)
+        counts[rng.random(R) < rng.choice([0.0, 0.2, 0.9])] = 0
+        if rng.random() < 0.2:
+            counts[:] = int(rng.integers(0, 5))
+        U = int(rng.choice([1, 2, 4, 8, 32, 64]))
+        W = int(rng.choice([w for w in (1, 2, 4, 8, 64) if U % w == 0]))
+        p = params(num_samples=S, B=int(rng.integers(1, 600)), U=U, W=W, dp_multiplier=int(rng.integers(1, 9)),
+                   granule=int(rng.choice([1, 2, 3, 32, 100])), a2a_global=int(rng.integers(1, 40)),
+                   a2a_intra=int(rng.integers(1, 120)), ar_global=int(rng.integers(1, 120)), ar_cross=int(rng.integers(1, 80)))
+        for tiers in (2, 3):
+            both(G, counts, p, tiers, cap=int(rng.choice([R, 0, max(1, R // 3)])), tag=bool(rng.random() < 0.7))
 
 
 def test_hand_case_and_edges(G):
