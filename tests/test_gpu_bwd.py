@@ -70,6 +70,22 @@ def test_bwd_random_duplicates(G, dt, D):
     _check(G, gnp, gt, rows, pos, 1500, 7777, R, dt, atomic_too=False)      # a sub-range (one owner's share)
 
 
+@pytest.mark.parametrize("R", [2 ** 32 - 2, 2 ** 31 + 5, 2 ** 24 + 1, 257])
+def test_bwd_row_ids_up_to_the_largest_table(G, R):
+    """Rows spread over the whole admitted id range (keys that use all 32 bits: four 8-bit sort passes for the
+    largest table), the last row included; only the ids matter here, no table of that size exists."""
+    rng = np.random.default_rng(R % 1000)
+    n, D = 12_345, 8
+    distinct = np.unique(np.concatenate([rng.integers(0, R, 3000), [0, R - 1, R // 2, min(R - 1, 2 ** 31 - 1), min(R - 1, 2 ** 31)]]))
+    rows_i = distinct[np.minimum(rng.pareto(0.7, n).astype(np.int64), len(distinct) - 1)]
+    order = np.argsort(rows_i % 3, kind="stable")
+    rows, pos = rows_i[order].astype(np.int64), order.astype(np.int32)
+    x = rng.standard_normal((n, D)).astype(np.float32)
+    gnp, gt = _np_grad(x, "f32")
+    ou, og = _check(G, gnp, gt, rows, pos, 0, n, R, "f32")
+    assert ou[-1] == R - 1 and ou[0] == 0
+
+
 def test_bwd_c1_end_to_end(G):
     cfg = fs_inputs.CONFIGS["c1"]
     b, pl = G.batch_on(cfg, "cpu")

@@ -144,3 +144,84 @@ def test_two_billion_lookups():
     assert int(want.abs().max()) < (1 << 24)                                       # every sum is an exact fp32 integer
     assert torch.equal(rg[:k].long(), want[present]) and torch.equal(rg[:k], rg[:k].round())
     _progress("[max] done")
+
+
+def test_largest_table_row_ids():
+    """R = 2^32 - 2 rows, the largest table the interface admits: placement and counts are 17 GB each, the lookups
+    aim at both ends of each table and at the rows either side of 2^31.  The oracle runs on the same ids with a
+    placement given as the few entries that differ from the constant background (it never reads the others)."""
+    import oracle
+    import paper_2301_02959_amd as fs
+    dev = "cuda:0"
+    free_b, _ = torch.cuda.mem_get_info()
+    if free_b < 120e9:
+        pytest.skip(f"needs ~120 GB of free HBM, {free_b / 1e9:.0f} GB free")
+    R = (1 << 32) - 2
+    T, B, U, W, self_ = 2, 64, 8, 4, 6
+    E = R // T                                                     # 2^31 - 1 rows per table
+    rng = np.random.default_rng(11)
+    S = T * B
+    lengths = rng.integers(0, 200, S)
+    offsets = np.zeros(S + 1, np.int64)
+    np.cumsum(lengths, out=offsets[1:])
+    n = int(offsets[-1])
+    special = np.array([0, 1, E - 1, E - 2, E // 2, (1 << 30), (1 << 30) - 1, 12345, E - 12345], np.int64)
+    ids = np.where(rng.random(n) < 0.6, special[rng.integers(0, len(special), n)], rng.integers(0, E, n)).astype(np.int64)
+    row_base = np.array([0, E, 2 * E], np.int64)
+    table = np.searchsorted(offsets[::B][1:], np.arange(n), side="right")
+    g = row_base[table] + ids                                      # global rows: up to 2^32 - 3
+    assert g.max() == R - 1 and g.min() == 0 and (g >= (1 << 31)).any() and (g < (1 << 31)).any()
+    # placement: tier 2 / owner 3 everywhere, except the rows this batch touches (random tiers and owners)
+    _progress("[max R] placement and counts, 17 GB each")
+    pl_d = torch.full((R,), entry(2, 3) - (1 << 32), dtype=torch.int32, device=dev)
+    touched = np.unique(g)
+    tiers = rng.integers(0, 3, len(touched))
+    owners = np.where(tiers == 2, rng.integers(0, U, len(touched)), rng.integers(0, W, len(touched)))
+    vals = ((tiers.astype(np.int64) << 30) | owners).astype(np.uint32)
+    pl_d[torch.from_numpy(touched).to(dev)] = torch.from_numpy(vals.view(np.int32)).to(dev)
+    # the oracle's placement: a compact table over the touched rows, the batch re-indexed into it
+    local = np.searchsorted(touched, g)
+    o_rc, o_st, o_bo, o_rows, o_pos, o_tc = oracle.route_bucketize(local, np.array([0, n], np.int64), 1, 1,
+                                                                   np.array([0, len(touched)], np.int64), vals, U, W, self_, n=n)
+    assert (o_rc, o_st) == (0, 0)
+    bo = torch.zeros(U + 1, dtype=torch.int64, device=dev)
+    rows = torch.empty(n, dtype=torch.int64, device=dev)
+    pos = torch.empty(n, dtype=torch.int32, device=dev)
+    tc = torch.zeros(3, dtype=torch.int64, device=dev)
+    st = torch.zeros(1, dtype=torch.int32, device=dev)
+    ids_d, off_d, rb_d = (torch.from_numpy(a).to(dev) for a in (ids, offsets, row_base))
+    _progress("[max R] route")
+    assert fs.fs_route_bucketize(ids_d, off_d, T, B, rb_d, pl_d, n, U, W, self_, bo, rows, pos, tc, st) == 0
+    torch.cuda.synchronize()
+    assert int(st.item()) == 0
+    assert np.array_equal(bo.cpu().numpy(), o_bo) and np.array_equal(tc.cpu().numpy(), o_tc)
+    assert np.array_equal(pos.cpu().numpy(), o_pos)
+    assert np.array_equal(rows.cpu().numpy(), touched[o_rows])                     # the oracle's rows are indices into touched
+    del pl_d
+    torch.cuda.empty_cache()
+    # histogram over the same ids: counts[g] += 1, everything else stays 0
+    _progress("[max R] histogram")
+    counts = torch.zeros(R, dtype=torch.int32, device=dev)
+    assert fs.fs_plan_replication(ids_d, off_d, T, B, rb_d, n, R, counts, fs.FS_PLAN_ACCUMULATE, dev_status=st) == 0
+    torch.cuda.synchronize()
+    assert int(st.item()) == 0
+    want = np.bincount(local, minlength=len(touched))
+    assert np.array_equal(counts[torch.from_numpy(touched).to(dev)].cpu().numpy(), want)
+    assert int(counts.sum(dtype=torch.int64).item()) == n
+    del counts
+    torch.cuda.empty_cache()
+    # backward on the routed lists: row ids that need all 32 key bits
+    _progress("[max R] backward")
+    D = 4
+    grad = torch.from_numpy(rng.integers(-3, 4, (n, D)).astype(np.float32)).to(dev)
+    uniq = torch.empty(len(touched), dtype=torch.int64, device=dev)
+    rg = torch.empty(len(touched), D, dtype=torch.float32, device=dev)
+    nu = torch.zeros(1, dtype=torch.int64, device=dev)
+    assert fs.fs_seq_grad_bwd(grad, rows, pos, 0, n, R, 0, uniq, rg, len(touched), nu, st) == 0
+    torch.cuda.synchronize()
+    assert int(st.item()) == 0 and int(nu.item()) == len(touched)
+    assert np.array_equal(uniq.cpu().numpy(), touched)
+    sums = np.zeros((len(touched), D))
+    np.add.at(sums, local, grad.cpu().numpy().astype(np.float64))
+    assert np.array_equal(rg.cpu().numpy().astype(np.float64), sums)              # small integers: exact in fp32
+    _progress("[max R] done")
