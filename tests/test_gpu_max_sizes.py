@@ -208,6 +208,32 @@ def test_largest_table_row_ids():
     want = np.bincount(local, minlength=len(touched))
     assert np.array_equal(counts[torch.from_numpy(touched).to(dev)].cpu().numpy(), want)
     assert int(counts.sum(dtype=torch.int64).item()) == n
+    # top-k under a budget and the tier cuts on those counts (workspaces of ~90 GB: four 17 GB sort buffers and
+    # the per-tile tables); the oracle sees the touched rows only, whose order is the global one
+    free_b, _ = torch.cuda.mem_get_info()
+    if free_b > 130e9:
+        _progress("[max R] select and tiers")
+        k_budget = len(touched) // 2
+        sel = torch.full((k_budget,), -1, dtype=torch.int64, device=dev)
+        nsel = torch.zeros(1, dtype=torch.int64, device=dev)
+        assert fs.fs_plan_replication(None, None, 1, 1, None, 0, R, counts, fs.FS_PLAN_SELECT, k_budget * 16, 16, sel, nsel,
+                                      dev_status=st) == 0
+        torch.cuda.synchronize()
+        o_rc, o_st, o_sel = oracle.plan_replication(None, None, 1, 1, None, len(touched), want.astype(np.uint32),
+                                                    oracle.PLAN_SELECT, k_budget * 16, 16)
+        assert o_rc == 0 and int(nsel.item()) == len(o_sel) == k_budget
+        assert np.array_equal(sel.cpu().numpy(), touched[o_sel])
+        del sel
+        torch.cuda.empty_cache()
+        tp = dict(num_samples=B, B=4, U=U, W=W, dp_multiplier=6, granule=1, a2a_global=1, a2a_intra=6, ar_global=3, ar_cross=2)
+        cuts = torch.zeros(fs.FS_TIER_CUTS, dtype=torch.int64, device=dev)
+        srt = torch.full((len(touched),), -1, dtype=torch.int64, device=dev)
+        assert fs.fs_plan_tiers(counts, R, tp, 3, srt, len(touched), cuts) == 0
+        torch.cuda.synchronize()
+        o_rc, o_cuts, o_rows = oracle.plan_tiers(want.astype(np.uint32), tp, 3, cap=len(touched))
+        assert o_rc == 0 and cuts.cpu().numpy().tolist() == o_cuts.tolist()
+        assert np.array_equal(srt.cpu().numpy()[:len(o_rows)], touched[o_rows])
+        del srt
     del counts
     torch.cuda.empty_cache()
     # backward on the routed lists: row ids that need all 32 key bits
