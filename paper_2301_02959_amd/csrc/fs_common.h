@@ -102,28 +102,39 @@ __device__ __forceinline__ uint64_t ballot(bool p) { return __ballot(p); }
 // restricted to lanes with `valid`.  nbits ballots, no LDS.
 __device__ __forceinline__ uint64_t match_bits(uint32_t key, int nbits, bool valid)
 {
-    uint64_t m = ballot(valid);
+    const uint64_t all = ballot(valid);
+    uint32_t m_lo = (uint32_t)all, m_hi = (uint32_t)(all >> 32);
 #pragma unroll 1
     for (int b = 0; b < nbits; ++b) {
-        const bool bit = (key >> b) & 1u;
-        const uint64_t v = ballot(bit);
-        m &= bit ? v : ~v;
+        uint32_t x = (uint32_t)((int32_t)(key << (31 - b)) >> 31);   // 0 or ~0: the lane's bit b
+        asm volatile("" : "+v"(x));
+        const uint64_t v = ballot(x != 0u);
+        m_lo &= ~((uint32_t)v ^ x);                                  // lanes whose bit b agrees with this lane's
+        m_hi &= ~((uint32_t)(v >> 32) ^ x);
     }
-    return m;
+    return ((uint64_t)m_hi << 32) | m_lo;
 }
 
-// The same with the bit count known at compile time: the loop unrolls, the shifts fold.
+// The same with the bit count known at compile time: the loop unrolls, the shifts fold.  Written on
+// 32-bit halves with the lane's bit spread to a whole word: per bit one bit-field extract, one compare
+// (the ballot), one exclusive-or per half, and the halves' mismatches are or-ed three at a time: a
+// third fewer vector instructions than selecting between the ballot and its complement, and the sort's
+// count and scatter kernels are bound by exactly these instructions.
 template <int NBITS>
 __device__ __forceinline__ uint64_t match_bits_n(uint32_t key, bool valid)
 {
-    uint64_t m = ballot(valid);
+    const uint64_t all = ballot(valid);
+    uint32_t m_lo = (uint32_t)all, m_hi = (uint32_t)(all >> 32);
 #pragma unroll
     for (int b = 0; b < NBITS; ++b) {
-        const bool bit = (key >> b) & 1u;
-        const uint64_t v = ballot(bit);
-        m &= bit ? v : ~v;
+        // x = 0 or ~0 as the lane's bit is clear or set; the lanes that agree with it are ~(v ^ x)
+        uint32_t x = (uint32_t)((int32_t)(key << (31 - b)) >> 31);
+        asm volatile("" : "+v"(x));          // one bit-field extract, and the ballot compares x itself (no second shift)
+        const uint64_t v = ballot(x != 0u);
+        m_lo &= ~((uint32_t)v ^ x);
+        m_hi &= ~((uint32_t)(v >> 32) ^ x);
     }
-    return m;
+    return ((uint64_t)m_hi << 32) | m_lo;
 }
 
 #define FS_DISPATCH_BITS(nbits, CALL)                                                   \
