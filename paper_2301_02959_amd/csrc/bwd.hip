@@ -33,16 +33,18 @@ constexpr uint32_t kNoKey = 0xFFFFFFFFu;     // never a row: R < 2^32 - 1
 
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 
-// Block b covers chunks [64 b, 64 b + 64): wave w walks 16 of them.  chunk_local[c] = runs that
-// start in the block's chunks before c; block_sum[b] = runs that start in the block.
-__global__ __launch_bounds__(kBlock) void bwd_count_heads_kernel(
+// Block b covers chunks [64 b, 64 b + 64): 16 waves, each walks 4 of them (with 4 waves of 16 chunks
+// each the kernel's time was the chain of 16 dependent rounds of loads per wave).  chunk_local[c] = runs
+// that start in the block's chunks before c; block_sum[b] = runs that start in the block.
+constexpr int kHeadsBlock = 1024;
+__global__ __launch_bounds__(kHeadsBlock) void bwd_count_heads_kernel(
     const uint32_t* __restrict__ keys, const uint32_t* __restrict__ vals, int64_t m, int64_t chunks,
     uint32_t* __restrict__ chunk_local, uint32_t* __restrict__ block_sum, int32_t* status)
 {
     __shared__ uint32_t heads[kChunksPerBlock];
     const int w = wave_id();
     const int lane = lane_id();
-    constexpr int kPerWave = kChunksPerBlock / kWavesPerBlock;
+    constexpr int kPerWave = kChunksPerBlock / (kHeadsBlock / kWave);
     bool disorder = false;
     for (int q = 0; q < kPerWave; ++q) {
         const int slot = w * kPerWave + q;
@@ -54,15 +56,12 @@ __global__ __launch_bounds__(kBlock) void bwd_count_heads_kernel(
             for (int s = 0; s < kChunk / kWave; ++s) {
                 const int64_t k = k0 + s * kWave + lane;
                 bool head = false;
-                if (k < m) {
-                    const uint32_t key = keys[k];
-                    if (k == 0) {
-                        head = true;
-                    } else {
-                        const uint32_t prev = keys[k - 1];
-                        head = key != prev;
-                        if (!head && vals[k] < vals[k - 1]) disorder = true;
-                    }
+                if (k < m) {                                         // the four loads in one round, none behind a compare
+                    const int64_t kp = k > 0 ? k - 1 : 0;
+                    const uint32_t key = keys[k], prev = keys[kp];
+                    const uint32_t val = vals[k], pval = vals[kp];
+                    head = k == 0 || key != prev;
+                    if (!head && val < pval) disorder = true;
                 }
                 count += (uint32_t)__popcll(ballot(head));
             }
@@ -617,7 +616,7 @@ extern "C" fs_status fs_seq_grad_bwd(
     fs_status rc = radix_sort_pairs(keys_a, vals_a, keys_b, vals_b, m, nullptr, bits_for((uint64_t)(R - 1)),
                                     sort_scratch, s, &keys, &vals, source);
     if (rc != FS_OK) return rc;
-    FS_LAUNCH("bwd_count_heads", bwd_count_heads_kernel, dim3((unsigned)blocks), dim3(kBlock), s,
+    FS_LAUNCH("bwd_count_heads", bwd_count_heads_kernel, dim3((unsigned)blocks), dim3(kHeadsBlock), s,
               keys, vals, m, chunks, chunk_local, block_base, dev_status);
     FS_LAUNCH("bwd_scan_blocks", bwd_scan_blocks_kernel, dim3(1), dim3(kScanBlock), s,
               block_base, blocks, cap_unique, num_unique, dev_status);
