@@ -67,31 +67,54 @@ __global__ __launch_bounds__(kBlock) void route_remap_kernel(
         tile_tables[1] = table_of(offsets, T, B, last);
     }
     __syncthreads();
-    const int t_lo = tile_tables[0];
-    const int t_hi = tile_tables[1];
+    const int t_lo = __builtin_amdgcn_readfirstlane(tile_tables[0]);
+    const int t_hi = __builtin_amdgcn_readfirstlane(tile_tables[1]);
     const int group_base = (self / W) * W;
     const int64_t R_all = row_base[T];                // rows of all tables; g must stay below it (and below 2^32 - 1)
     const bool rows_ok = R_all >= 1 && R_all < 4294967295LL;
     int32_t faults = rows_ok ? 0 : FS_DEV_BAD_ID;
     unsigned int tiers[3] = {0, 0, 0};
 
-#pragma unroll 2
+    // Three rounds of loads for the thread's 8 lookups, each round's loads all in flight together: the
+    // ids, then (only in a tile that spans tables) the offsets and row_base of each lookup's table,
+    // then the placement entries.  Item by item the kernel's time was a chain of 8 x 3 dependent loads.
+    int64_t id[kRouteItems];
+#pragma unroll
+    for (int it = 0; it < kRouteItems; ++it) {
+        const int64_t i = base + (int64_t)it * kBlock + threadIdx.x;
+        id[it] = load_stream(ids + (i < n ? i : n - 1));             // past the end: the last id again, unused
+    }
+    const int64_t first_lo = row_base[t_lo];
+    const int64_t rows_lo = row_base[t_lo + 1] - first_lo;
+    int64_t g[kRouteItems];
+#pragma unroll
+    for (int it = 0; it < kRouteItems; ++it) {
+        const int64_t i = base + (int64_t)it * kBlock + threadIdx.x;
+        int64_t first = first_lo, rows_t = rows_lo;
+        if (t_lo != t_hi) {                                          // block-uniform
+            int t = t_lo;
+            while (t < t_hi && offsets[(int64_t)(t + 1) * B] <= i) ++t;
+            first = row_base[t];
+            rows_t = row_base[t + 1] - first;
+        }
+        int64_t x = id[it];
+        const bool valid = i < n;
+        if (x < 0 || x >= rows_t) { if (valid) faults |= FS_DEV_BAD_ID; x = 0; }
+        int64_t row = first + x;
+        if ((uint64_t)row >= (uint64_t)R_all) { if (valid) faults |= FS_DEV_BAD_ID; row = 0; }   // row_base not ascending
+        g[it] = row;
+    }
+    uint32_t e[kRouteItems];
+#pragma unroll
+    for (int it = 0; it < kRouteItems; ++it) e[it] = rows_ok ? placement[g[it]] : 0u;
+#pragma unroll
     for (int it = 0; it < kRouteItems; ++it) {
         const int64_t i = base + (int64_t)it * kBlock + threadIdx.x;
         const bool valid = i < n;
         uint32_t dest = 0;
         if (valid) {
-            int t = t_lo;
-            while (t < t_hi && offsets[(int64_t)(t + 1) * B] <= i) ++t;
-            const int64_t first = row_base[t];
-            const int64_t rows_t = row_base[t + 1] - first;
-            int64_t id = load_stream(ids + i);
-            if (id < 0 || id >= rows_t) { faults |= FS_DEV_BAD_ID; id = 0; }
-            int64_t g = first + id;
-            if ((uint64_t)g >= (uint64_t)R_all) { faults |= FS_DEV_BAD_ID; g = 0; }   // row_base not ascending
-            const uint32_t e = rows_ok ? placement[g] : 0u;
-            const uint32_t tier = e >> FS_TIER_SHIFT;
-            const uint32_t owner = e & FS_OWNER_MASK;
+            const uint32_t tier = e[it] >> FS_TIER_SHIFT;
+            const uint32_t owner = e[it] & FS_OWNER_MASK;
             if (tier == FS_TIER_GLOBAL) {
                 dest = self; tiers[0]++;
             } else if (tier == FS_TIER_GROUP) {
@@ -106,7 +129,7 @@ __global__ __launch_bounds__(kBlock) void route_remap_kernel(
                 dest = self; tiers[0]++; faults |= FS_DEV_BAD_PLACEMENT;
             }
             dest_out[i] = (uint16_t)dest;
-            g_out[i] = (uint32_t)g;
+            g_out[i] = (uint32_t)g[it];
         }
         // one LDS add per distinct bucket per wave
         const uint64_t same = match_bits(dest, dest_bits, valid);
