@@ -43,19 +43,20 @@ struct RowPosReader {                         // pairs are (rows[i], pos[i]), va
     const int32_t* pos;
     int64_t R;
     int64_t n;
+    // one unsigned compare each also catches the negative values (R < 2^32, n < 2^31)
     __device__ __forceinline__ uint32_t key(int64_t i) const
     {
-        const int64_t r = load_stream(rows + i);
-        return (r < 0 || r >= R) ? 0u : (uint32_t)r;
+        const uint64_t r = (uint64_t)load_stream(rows + i);
+        return r >= (uint64_t)R ? 0u : (uint32_t)r;
     }
     __device__ __forceinline__ void pair(int64_t i, uint32_t* k, uint32_t* v, int32_t* faults) const
     {
-        int64_t r = load_stream(rows + i);
-        int64_t p = load_stream(pos + i);
-        if (r < 0 || r >= R) { r = 0; *faults |= FS_DEV_BAD_ID; }
-        if (p < 0 || p >= n) { p = 0; *faults |= FS_DEV_BAD_ID; }
+        uint64_t r = (uint64_t)load_stream(rows + i);
+        uint32_t p = (uint32_t)load_stream(pos + i);
+        if (r >= (uint64_t)R) { r = 0; *faults |= FS_DEV_BAD_ID; }
+        if (p >= (uint32_t)n) { p = 0; *faults |= FS_DEV_BAD_ID; }
         *k = (uint32_t)r;
-        *v = (uint32_t)p;
+        *v = p;
     }
 };
 
