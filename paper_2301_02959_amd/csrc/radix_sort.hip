@@ -108,7 +108,7 @@ __global__ __launch_bounds__(kBlock) void sort_count_kernel(
 // chunk_sums[chunk][b].
 constexpr int kSortChunkTiles = 64;
 
-__global__ __launch_bounds__(kBlock) void sort_scan_tiles_kernel(
+__global__ __launch_bounds__(1024) void sort_scan_tiles_kernel(
     uint32_t* __restrict__ tile_hist, int bins, int64_t m_max, const int64_t* __restrict__ m_dev,
     uint32_t* __restrict__ chunk_sums)
 {
@@ -117,7 +117,7 @@ __global__ __launch_bounds__(kBlock) void sort_scan_tiles_kernel(
     const int64_t t0 = (int64_t)blockIdx.x * kSortChunkTiles;
     if (t0 >= used) return;
     const int64_t t1 = t0 + kSortChunkTiles < used ? t0 + kSortChunkTiles : used;
-    for (int b = threadIdx.x; b < bins; b += kBlock) {
+    for (int b = threadIdx.x; b < bins; b += blockDim.x) {       // launched with one thread per digit (up to 1024)
         uint32_t run = 0;
         int64_t t = t0;
         for (; t + 8 <= t1; t += 8) {                            // 8 loads in flight
@@ -333,6 +333,7 @@ fs_status radix_sort_pairs(uint32_t* keys_a, uint32_t* vals_a, uint32_t* keys_b,
         // spread the bits evenly over the passes: 27 bits -> 9, 9, 9; 32 bits -> 8, 8, 8, 8
         const int left = key_bits - shift;
         const int nbits = (left + (passes - p) - 1) / (passes - p);
+        const unsigned scan_threads = (1u << nbits) < (unsigned)kWave ? (unsigned)kWave : (1u << nbits);   // <= 1024
         if (p == 0 && from_rows) {
             const RowPosReader in{src.rows, src.pos, src.R, src.n};
 #define FS_COUNT_ROWS(NB)                                                                                     \
@@ -340,7 +341,7 @@ fs_status radix_sort_pairs(uint32_t* keys_a, uint32_t* vals_a, uint32_t* keys_b,
               m_dev, shift, tile_hist)
             FS_DISPATCH_BITS(nbits, FS_COUNT_ROWS)
 #undef FS_COUNT_ROWS
-            FS_LAUNCH("sort_scan_tiles", sort_scan_tiles_kernel, dim3((unsigned)chunks), dim3(kBlock), stream,
+            FS_LAUNCH("sort_scan_tiles", sort_scan_tiles_kernel, dim3((unsigned)chunks), dim3(scan_threads), stream,
                       tile_hist, 1 << nbits, m_max, m_dev, chunk_sums);
             FS_LAUNCH("sort_scan_chunks", sort_scan_chunks_kernel, dim3(((1u << nbits) + kBlock - 1) / kBlock),
                       dim3(kBlock), stream, chunk_sums, 1 << nbits, m_max, m_dev, totals);
@@ -356,7 +357,7 @@ fs_status radix_sort_pairs(uint32_t* keys_a, uint32_t* vals_a, uint32_t* keys_b,
               m_dev, shift, tile_hist)
             FS_DISPATCH_BITS(nbits, FS_COUNT_PAIRS)
 #undef FS_COUNT_PAIRS
-            FS_LAUNCH("sort_scan_tiles", sort_scan_tiles_kernel, dim3((unsigned)chunks), dim3(kBlock), stream,
+            FS_LAUNCH("sort_scan_tiles", sort_scan_tiles_kernel, dim3((unsigned)chunks), dim3(scan_threads), stream,
                       tile_hist, 1 << nbits, m_max, m_dev, chunk_sums);
             FS_LAUNCH("sort_scan_chunks", sort_scan_chunks_kernel, dim3(((1u << nbits) + kBlock - 1) / kBlock),
                       dim3(kBlock), stream, chunk_sums, 1 << nbits, m_max, m_dev, totals);
