@@ -163,6 +163,21 @@ __global__ __launch_bounds__(kScanBlock) void plan_scan_kernel(uint32_t* __restr
                                                                int64_t* __restrict__ num_candidates)
 {
     __shared__ uint32_t wave_sums[16];
+    const int64_t per = (tiles + kScanBlock - 1) / kScanBlock;
+    if (per <= 16) {
+        // up to 16 k tiles: a thread sums a short run of consecutive tiles, ONE scan over the block's 1024
+        // sums, the thread then writes its run's prefixes (0.019 -> 0.012 ms for 10 k tiles; for longer
+        // runs the strided accesses cost more than the scans they save)
+        const int64_t lo = (int64_t)threadIdx.x * per < tiles ? (int64_t)threadIdx.x * per : tiles;
+        const int64_t hi = lo + per < tiles ? lo + per : tiles;
+        uint32_t sum = 0;
+        for (int64_t k = lo; k < hi; ++k) sum += tile_count[k];
+        uint32_t total;
+        uint32_t run = block_exclusive_scan(sum, wave_sums, &total);
+        for (int64_t k = lo; k < hi; ++k) { const uint32_t v = tile_count[k]; tile_count[k] = run; run += v; }
+        if (threadIdx.x == 0) *num_candidates = (int64_t)total;
+        return;
+    }
     uint32_t carry = 0;                                          // coalesced rounds of 1024 tiles, 8 rounds of loads in flight
     for (int64_t base = 0; base < tiles; base += 8 * kScanBlock) {
         uint32_t v[8];

@@ -158,22 +158,16 @@ __global__ __launch_bounds__(kBlock) void route_remap_kernel(
 __global__ __launch_bounds__(kBlock) void route_scan_kernel(uint32_t* __restrict__ tile_hist, int64_t tiles,
                                                             uint32_t* __restrict__ totals)
 {
-    __shared__ uint32_t part[kBlock];
+    __shared__ uint32_t wave_sums[16];
     uint32_t* h = tile_hist + (int64_t)blockIdx.x * tiles;
     const int64_t per = (tiles + kBlock - 1) / kBlock;
-    const int64_t lo = (int64_t)threadIdx.x * per;
+    const int64_t lo = (int64_t)threadIdx.x * per < tiles ? (int64_t)threadIdx.x * per : tiles;
     const int64_t hi = lo + per < tiles ? lo + per : tiles;
     uint32_t sum = 0;
     for (int64_t k = lo; k < hi; ++k) sum += h[k];
-    part[threadIdx.x] = sum;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        uint32_t run = 0;
-        for (int k = 0; k < kBlock; ++k) { const uint32_t v = part[k]; part[k] = run; run += v; }
-        totals[blockIdx.x] = run;
-    }
-    __syncthreads();
-    uint32_t run = part[threadIdx.x];
+    uint32_t total;
+    uint32_t run = block_exclusive_scan(sum, wave_sums, &total);
+    if (threadIdx.x == 0) totals[blockIdx.x] = total;
     for (int64_t k = lo; k < hi; ++k) { const uint32_t v = h[k]; h[k] = run; run += v; }
 }
 
