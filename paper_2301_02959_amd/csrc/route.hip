@@ -155,12 +155,14 @@ __global__ __launch_bounds__(kBlock) void route_remap_kernel(
 }
 
 // One block per bucket b: tile_hist[b][0..tiles) -> exclusive prefix in place, total[b].
-__global__ __launch_bounds__(kBlock) void route_scan_kernel(uint32_t* __restrict__ tile_hist, int64_t tiles,
-                                                            uint32_t* __restrict__ totals)
+constexpr int kRouteScanBlock = 1024;                 // U + 3 blocks only: as many threads each as a block can have
+
+__global__ __launch_bounds__(kRouteScanBlock) void route_scan_kernel(uint32_t* __restrict__ tile_hist, int64_t tiles,
+                                                                     uint32_t* __restrict__ totals)
 {
     __shared__ uint32_t wave_sums[16];
     uint32_t* h = tile_hist + (int64_t)blockIdx.x * tiles;
-    const int64_t per = (tiles + kBlock - 1) / kBlock;
+    const int64_t per = (tiles + kRouteScanBlock - 1) / kRouteScanBlock;
     const int64_t lo = (int64_t)threadIdx.x * per < tiles ? (int64_t)threadIdx.x * per : tiles;
     const int64_t hi = lo + per < tiles ? lo + per : tiles;
     uint32_t sum = 0;
@@ -308,7 +310,7 @@ extern "C" fs_status fs_route_bucketize(
                        (size_t)U * sizeof(uint32_t), s,
                        ids, offsets, (int)T, (int64_t)B, row_base, placement, n, (int)U, (int)W, (int)self,
                        dest_bits, dest_tmp, g_tmp, tile_hist, tiles, dev_status);
-        FS_LAUNCH("route_scan", route_scan_kernel, dim3((unsigned)U + 3), dim3(kBlock), s, tile_hist, tiles, totals);
+        FS_LAUNCH("route_scan", route_scan_kernel, dim3((unsigned)U + 3), dim3(kRouteScanBlock), s, tile_hist, tiles, totals);
         const unsigned scatter_grid = (unsigned)xcd_striped_grid(tiles, kRouteStripe);
         FS_LAUNCH_SMEM("route_scatter", route_scatter_kernel, dim3(scatter_grid), dim3(kBlock),
                        (size_t)U * sizeof(uint32_t) + (size_t)kWavesPerBlock * U * sizeof(uint16_t), s,
