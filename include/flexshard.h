@@ -154,9 +154,9 @@ fs_status fs_seq_gather_fwd(
 
 /*
  * The two halves of fs_seq_gather_fwd that sit either side of the row exchange
- * (Section 3.2 metric 2, "dynamic communication": the looked-up rows travel
+ * (Section 3.2 metric 5, "dynamic communication": the looked-up rows travel
  * from the GPU that owns them back to the GPU that asked, in the order the ids
- * arrived there; Table 3, column "Dynamic Comms").
+ * arrived there; the communication-cost table, column "Dynamic Comms").
  *
  * fs_seq_gather_send -- owner side: send[j - j0, :] = weights[rows[j], :] for
  *   j in [j0, j1); send is [j1 - j0, D], contiguous, in bucket order.
@@ -239,7 +239,10 @@ fs_status fs_seq_gather_fwd_replica(
  *
  * Precondition (true of every fs_route_bucketize output and any [j0, j1) of
  * it): lookups of one row appear with ascending pos in j order.  A violation
- * sets FS_DEV_POS_ORDER and the sums of that row follow j order instead.
+ * sets FS_DEV_POS_ORDER; uniq_rows and *num_unique are then still exact, and
+ * every row's gradient is still the sum of its terms, but in an order that is
+ * not the stated one (the terms of a row are taken in j order), so only the
+ * bound of variant 1 holds for the values.
  *
  * Data faults: rows[j] outside [0, R) or pos[j] outside [0, n) is replaced by
  * row 0 / pos 0 (FS_DEV_BAD_ID), result unspecified but in bounds.

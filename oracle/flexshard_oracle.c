@@ -348,8 +348,11 @@ int oracle_seq_grad_bwd(
         if (p < 0 || p >= n) { flag(status, DEV_BAD_ID); p = 0; }
         lk[q].row = r; lk[q].pos = p; lk[q].j = q;
     }
-    /* the precondition the product states: equal rows come with ascending pos */
-    /* (checked after sorting: a stable-by-j order would differ from this one)  */
+    /* The order is by (row, pos) whatever the order in j.  Where equal rows do  */
+    /* not come with ascending pos in j, DEV_POS_ORDER says so: a caller that    */
+    /* relies on that precondition (a stable sort by row alone) would sum the    */
+    /* same terms in another order, so only sums-within-tolerance, the distinct  */
+    /* rows and their number can be compared on such an input.                   */
     qsort(lk, (size_t)m, sizeof(lookup_t), by_row_then_pos);
     for (int64_t k = 1; k < m; ++k)
         if (lk[k].row == lk[k - 1].row && lk[k].j < lk[k - 1].j) { flag(status, DEV_POS_ORDER); break; }

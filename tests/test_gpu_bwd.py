@@ -177,7 +177,12 @@ def test_bwd_capacity_faults_and_edges(G):
     assert rc == 0 and nu == 0 and st == 0
     # descending pos inside a row: flagged
     rc, st, u, g, nu = G.hip_bwd(gd, G.to_dev([4, 4, 4, 1], torch.int64), G.to_dev([2, 1, 0, 3], torch.int32), 0, 4, 10, 0)
-    assert st == oracle.POS_ORDER and u.tolist() == [1, 4]
+    assert st == oracle.POS_ORDER and u.tolist() == [1, 4] and nu == 2
+    #   same flag, rows and count as the oracle; the values are the same terms summed (here small integers: exact)
+    orc, ost, ou, og, og64, onu = oracle.seq_grad_bwd(grad.numpy(), np.array([4, 4, 4, 1]), np.array([2, 1, 0, 3], np.int32),
+                                                      0, 4, 10)
+    assert ost == oracle.POS_ORDER and ou.tolist() == [1, 4] and onu == 2
+    assert np.array_equal(g.cpu().numpy().astype(np.float64), og64)
     # bad row / pos: flagged, in bounds
     rc, st, u, g, nu = G.hip_bwd(gd, G.to_dev([12, 1], torch.int64), G.to_dev([0, 50], torch.int32), 0, 2, 10, 0)
     assert st & oracle.BAD_ID and u.tolist() == [0, 1] and torch.equal(g.cpu()[1], grad[0])

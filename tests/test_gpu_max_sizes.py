@@ -23,15 +23,14 @@ pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
 
 N_MAX = (1 << 31) - 1
 
-SCRATCH = "gpurun_out"
-
-
 def _progress(msg):
+    """Progress line for long tests: stdout (visible with -s) and, if FS_TEST_PROGRESS_FILE names a file,
+    a line appended there, so that a quiet minute of a long test is not mistaken for a hang."""
     print(msg, flush=True)
-    d = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), SCRATCH)
-    if os.path.isdir(d):
+    path = os.environ.get("FS_TEST_PROGRESS_FILE")
+    if path:
         try:
-            with open(os.path.join(d, "full_size_progress.log"), "a") as f:
+            with open(path, "a") as f:
                 f.write(f"{time.strftime('%H:%M:%S')} {msg}\n")
         except OSError:
             pass
