@@ -17,7 +17,8 @@
  * Conventions for every entry point
  *   - Every pointer is DEVICE memory owned by the caller unless the comment
  *     says "host".  The library allocates nothing, frees nothing and keeps no
- *     state between calls (the opt-in profiling hooks at the end excepted).
+ *     state between calls (the opt-in profiling hooks at the end and the
+ *     static scratch array of fs_route_bucketize_noalloc excepted).
  *   - All work is enqueued on `stream` (a hipStream_t passed as void*; NULL is
  *     the default stream).  No entry point synchronises with the host.
  *   - `workspace == NULL`: the required scratch size is written to
@@ -130,6 +131,30 @@ fs_status fs_route_bucketize(
     int64_t* tier_counts,
     void* workspace, size_t* workspace_bytes /* host */,
     void* stream, int32_t* dev_status);
+
+/*
+ * fs_route_bucketize_noalloc -- fs_route_bucketize for callers that cannot
+ * allocate device memory or bring a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same inputs, outputs,
+ * faults and kernels; the workspace is a static device array inside the
+ * library, FS_ROUTE_NOALLOC_SCRATCH_BYTES per GPU (held until the process ends).
+ * A batch whose workspace would be larger (about 6 bytes per lookup plus
+ * 4 * (U + 3) bytes per 2048 lookups: roughly 5 million lookups at U = 64)
+ * returns FS_ERR_WORKSPACE and launches nothing.  The call allocates and
+ * frees nothing.  The first call on a GPU looks up that GPU's address of the
+ * array (a host-side query, no allocation); make that call outside a capture.
+ * All calls on one GPU share the array: two calls that overlap in time on one
+ * GPU (different streams) race; calls on one stream, or ordered by events, are
+ * fine.  Nothing in the array has to survive from call to call or start at zero.
+ */
+#define FS_ROUTE_NOALLOC_SCRATCH_BYTES (32u << 20)
+
+fs_status fs_route_bucketize_noalloc(
+    const int64_t* ids, const int64_t* offsets, int32_t T, int32_t B,
+    const int64_t* row_base, const uint32_t* placement,
+    int64_t n, int32_t U, int32_t W, int32_t self,
+    int64_t* bucket_offsets, int64_t* out_rows, int32_t* out_pos,
+    int64_t* tier_counts, void* stream, int32_t* dev_status);
 
 /*
  * fs_seq_gather_fwd -- unpooled sequence lookup (Section 2, "Embedding

@@ -26,11 +26,12 @@ FS_OPT_SGD, FS_OPT_ADAGRAD_ROWWISE, FS_OPT_ADAGRAD = 0, 1, 2
  FS_CUT_SUM_DP, FS_CUT_SUM_FLEX) = range(10)
 FS_TIER_CUTS = 10
 FS_MAX_BUCKETS = 4096
+FS_ROUTE_NOALLOC_SCRATCH_BYTES = 32 << 20
 
 STATUS_NAMES = {0: "FS_OK", 1: "FS_ERR_NULL", 2: "FS_ERR_SIZE", 3: "FS_ERR_DTYPE", 4: "FS_ERR_ALIGN",
                 5: "FS_ERR_WORKSPACE", 6: "FS_ERR_CONFIG", 7: "FS_ERR_DEVICE"}
 
-EXPORTS = ["fs_route_bucketize", "fs_seq_gather_fwd", "fs_seq_grad_bwd", "fs_plan_replication",
+EXPORTS = ["fs_route_bucketize", "fs_route_bucketize_noalloc", "fs_seq_gather_fwd", "fs_seq_grad_bwd", "fs_plan_replication",
            "fs_seq_gather_send", "fs_seq_unbucketize", "fs_replica_build", "fs_seq_gather_fwd_replica", "fs_plan_tiers",
            "fs_cost_model", "fs_tier_traffic", "fs_sparse_update", "fs_util_copy", "fs_version", "fs_bwd_tile", "fs_prof_begin", "fs_prof_only", "fs_prof_end"]
 
@@ -54,7 +55,7 @@ def lib() -> ctypes.CDLL:
                 f"{LIB_PATH} is missing: build it with `python -m paper_2301_02959_amd.build` "
                 "(hipcc, gfx950); this package has no other code path")
         _lib = ctypes.CDLL(LIB_PATH)
-        for name in ("fs_route_bucketize", "fs_seq_gather_fwd", "fs_seq_grad_bwd", "fs_plan_replication",
+        for name in ("fs_route_bucketize", "fs_route_bucketize_noalloc", "fs_seq_gather_fwd", "fs_seq_grad_bwd", "fs_plan_replication",
                      "fs_seq_gather_send", "fs_seq_unbucketize", "fs_replica_build",
                      "fs_seq_gather_fwd_replica", "fs_plan_tiers", "fs_cost_model", "fs_tier_traffic", "fs_sparse_update", "fs_prof_begin", "fs_prof_only",
                      "fs_util_copy"):
@@ -124,6 +125,17 @@ def fs_route_bucketize(ids, offsets, T: int, B: int, row_base, placement, n: int
     else:
         size = ctypes.c_size_t(workspace.numel())
     return _check("fs_route_bucketize", call(_ptr(workspace), ctypes.byref(size)), raise_on_error)
+
+
+def fs_route_bucketize_noalloc(ids, offsets, T: int, B: int, row_base, placement, n: int, U: int, W: int, self_: int,
+                               bucket_offsets, out_rows, out_pos, tier_counts=None, dev_status=None,
+                               raise_on_error: bool = True) -> int:
+    code = lib().fs_route_bucketize_noalloc(
+        _ptr(ids, _I64), _ptr(offsets, _I64), ctypes.c_int32(T), ctypes.c_int32(B), _ptr(row_base, _I64), _ptr(placement, _U32),
+        ctypes.c_int64(n), ctypes.c_int32(U), ctypes.c_int32(W), ctypes.c_int32(self_),
+        _ptr(bucket_offsets, _I64), _ptr(out_rows, _I64), _ptr(out_pos, _I32), _ptr(tier_counts, _I64),
+        _stream(), _ptr(dev_status, _I32))
+    return _check("fs_route_bucketize_noalloc", code, raise_on_error)
 
 
 def route_workspace_bytes(T: int, B: int, n: int, U: int, W: int, self_: int) -> int:

@@ -15,6 +15,8 @@
 //                   out_rows / out_pos
 //   route_finalize  bucket_offsets and tier_counts
 // No spin-waits anywhere: the only cross-block communication is between launches.
+#include <atomic>
+
 #include "fs_common.h"
 
 namespace fs {
@@ -273,9 +275,8 @@ __global__ __launch_bounds__(kBlock) void route_finalize_kernel(
     }
 }
 
-}  // namespace fs
-
-extern "C" fs_status fs_route_bucketize(
+// Both entry points: host checks, workspace carving, the five launches.
+static fs_status route_run(
     const int64_t* ids, const int64_t* offsets, int32_t T, int32_t B,
     const int64_t* row_base, const uint32_t* placement,
     int64_t n, int32_t U, int32_t W, int32_t self,
@@ -283,7 +284,6 @@ extern "C" fs_status fs_route_bucketize(
     int64_t* tier_counts,
     void* workspace, size_t* workspace_bytes, void* stream, int32_t* dev_status)
 {
-    using namespace fs;
     if (!workspace_bytes) return FS_ERR_NULL;
     if (n < 0 || n >= (1LL << 31) || T < 1 || B < 1 || (int64_t)T * B >= (1LL << 31)) return FS_ERR_SIZE;
     if (U < 1 || U > FS_MAX_BUCKETS || W < 1 || U % W != 0 || self < 0 || self >= U) return FS_ERR_CONFIG;
@@ -319,4 +319,61 @@ extern "C" fs_status fs_route_bucketize(
     FS_LAUNCH("route_finalize", route_finalize_kernel, dim3(1), dim3(kBlock), s,
               totals, (int)U, n, bucket_offsets, tier_counts);
     return FS_OK;
+}
+
+// ---- the variant that allocates nothing ----------------------------------------
+// Its workspace is this array: one copy per GPU, held until the process ends.  The name below is a
+// host-side stand-in; the device address of each GPU's copy comes from hipGetSymbolAddress and is
+// what every launch receives.
+static __device__ __align__(256) unsigned char scratch[FS_ROUTE_NOALLOC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+static std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+static fs_status scratch_of_current_device(void** ptr)
+{
+    int device = -1;
+    if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= kMaxDevices) return FS_ERR_DEVICE;
+    void* p = g_scratch_ptr[device].load(std::memory_order_acquire);
+    if (p == nullptr) {                                   // first call on this GPU (two racing threads find the same address)
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return FS_ERR_DEVICE;
+        g_scratch_ptr[device].store(p, std::memory_order_release);
+    }
+    *ptr = p;
+    return FS_OK;
+}
+
+}  // namespace fs
+
+extern "C" fs_status fs_route_bucketize(
+    const int64_t* ids, const int64_t* offsets, int32_t T, int32_t B,
+    const int64_t* row_base, const uint32_t* placement,
+    int64_t n, int32_t U, int32_t W, int32_t self,
+    int64_t* bucket_offsets, int64_t* out_rows, int32_t* out_pos,
+    int64_t* tier_counts,
+    void* workspace, size_t* workspace_bytes, void* stream, int32_t* dev_status)
+{
+    return fs::route_run(ids, offsets, T, B, row_base, placement, n, U, W, self, bucket_offsets, out_rows, out_pos,
+                         tier_counts, workspace, workspace_bytes, stream, dev_status);
+}
+
+extern "C" fs_status fs_route_bucketize_noalloc(
+    const int64_t* ids, const int64_t* offsets, int32_t T, int32_t B,
+    const int64_t* row_base, const uint32_t* placement,
+    int64_t n, int32_t U, int32_t W, int32_t self,
+    int64_t* bucket_offsets, int64_t* out_rows, int32_t* out_pos,
+    int64_t* tier_counts, void* stream, int32_t* dev_status)
+{
+    using namespace fs;
+    size_t need = 0;                                      // size query: host checks only, nothing launched
+    fs_status rc = route_run(ids, offsets, T, B, row_base, placement, n, U, W, self, bucket_offsets, out_rows, out_pos,
+                             tier_counts, nullptr, &need, stream, dev_status);
+    if (rc != FS_OK) return rc;
+    if (need > (size_t)FS_ROUTE_NOALLOC_SCRATCH_BYTES) return FS_ERR_WORKSPACE;
+    void* ws = nullptr;
+    rc = scratch_of_current_device(&ws);
+    if (rc != FS_OK) return rc;
+    size_t have = (size_t)FS_ROUTE_NOALLOC_SCRATCH_BYTES;
+    return route_run(ids, offsets, T, B, row_base, placement, n, U, W, self, bucket_offsets, out_rows, out_pos,
+                     tier_counts, ws, &have, stream, dev_status);
 }
