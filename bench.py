@@ -4,14 +4,19 @@
 One step = one pass of the whole hot path over one synthetic batch resident in HBM:
   fs_plan_replication (histogram of the batch + top-k under a budget)
   -> fs_route_bucketize -> fs_seq_gather_fwd (all buckets) -> fs_seq_grad_bwd (all buckets).
-Prints ONE JSON line: lookups/s over the whole step, the roofline of the dominant kernel
-(timed live with HIP events around each launch) and the CPU oracle timed on a bounded sample.
+Prints ONE JSON line: lookups/s over the whole step on c3 (the configuration the bandwidth target is
+stated on), the roofline of the dominant kernel (timed live with HIP events around each launch), the
+roofline of every entry point as a whole call (`roofline.calls`), the CPU oracle timed on a bounded
+sample, and -- when no --config is given -- the same step on c4 (the largest single-GPU shard) and the
+c5 planning pass (10^9 sampled ids through the histogram, then the top-k) under `also_configs`.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--config c3] [--variant 0|1]
 """
 from __future__ import annotations
 
 import argparse
+import ctypes
+import gc
 import json
 import os
 import sys
@@ -29,7 +34,9 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", default="c3", help="c1..c5 (c3 = the configuration the target is stated on)")
+    ap.add_argument("--config", default=None,
+                    help="c1..c5; default: c3 (the configuration the target is stated on), followed by c4 and the "
+                         "c5 planning pass under also_configs")
     ap.add_argument("--variant", type=int, default=0, help="backward: 0 sort/bit-exact, 1 atomic partials")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", action="store_true",
@@ -39,32 +46,42 @@ def parse():
                     help="run the plan on a second stream beside the lookup path (1-2 %% faster per step, but the "
                          "gather then shares the chip and its own duration grows)")
     ap.add_argument("--no-exchange", action="store_true", help="skip the untimed send / unbucketize / replica-store report")
+    ap.add_argument("--no-also", action="store_true", help="skip c4 and the c5 planning pass of the default run")
     ap.add_argument("--cpu-tables", type=int, default=0, help="tables in the oracle's sample (0 = automatic)")
     ap.add_argument("--scale-rows", type=int, default=1, help="divide E by this (debugging only; reported)")
     return ap.parse_args()
 
 
-def main():
-    args = parse()
-    if args.gpus != 1:
-        print(f"bench.py: this build runs on ONE GPU only (owner buckets are output partitions, no "
-              f"collectives); --gpus {args.gpus} is not supported", file=sys.stderr)
-        sys.exit(2)
+def frac_of_peak(nbytes: float, ms: float) -> dict:
+    gbs = nbytes / (ms * 1e-3) / 1e9 if ms > 0 else 0.0
+    return {"ms": round(ms, 4), "algorithmic_bytes": int(nbytes), "achieved": round(gbs, 1),
+            "frac": round(gbs / HBM_PEAK_GBS, 4)}
 
-    import numpy as np
+
+def traffic_from_profiles(key: str):
+    """HBM bytes per launch of one kernel as the committed rocprofv3 counter runs measured them
+    (profiles/hbm_traffic.json: FETCH_SIZE and WRITE_SIZE, each scaled by a plain copy of known size).
+    Returns (bytes or None, provenance or None): a figure of those profile runs, not of this run."""
+    tfile = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    try:
+        table = json.load(open(tfile))
+    except Exception:
+        return None, None
+    entry = table.get(key)
+    if entry is None:
+        return None, None
+    if isinstance(entry, dict):
+        return entry.get("bytes"), {k: v for k, v in entry.items() if k != "bytes"}
+    return entry, {"file": "profiles/hbm_traffic.json"}
+
+
+def run_step_config(cfg, args, steps: int, warmup: int, full_report: bool):
+    """The step on one configuration.  Returns (result fields, tensors the cpu baseline needs)."""
     import torch
     import fs_inputs
     import paper_2301_02959_amd as fs
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(1)
     dev = "cuda:0"
-    torch.cuda.set_device(0)
-    cfg = fs_inputs.CONFIGS[args.config]
-    if args.scale_rows > 1:
-        cfg = cfg.scaled(E=cfg.E // args.scale_rows)
-
     # ---------------------------------------------------------------- inputs, resident in HBM
     t_gen = time.time()
     batch = fs_inputs.make_batch(cfg, dev, keep_perms=False)
@@ -93,8 +110,6 @@ def main():
     sel_rows = torch.zeros(budget_rows, dtype=torch.int64, device=dev)
     num_selected = torch.zeros(1, dtype=torch.int64, device=dev)
     plan_flags = fs.FS_PLAN_ACCUMULATE | fs.FS_PLAN_SELECT
-
-    import ctypes
 
     def ws_for(query):
         size = ctypes.c_size_t(0)
@@ -136,12 +151,22 @@ def main():
     # end of the step.  Default: everything on one stream, so that each kernel's duration is its own.
     main_stream = torch.cuda.current_stream()
     plan_stream = torch.cuda.Stream() if args.overlap_plan else main_stream
-
     plan_calls = [0]
 
     def plan():
         fs.fs_plan_replication(ids, offsets, T, B, row_base, n, R, counts, plan_flags, budget_rows * row_bytes,
                                row_bytes, sel_rows, num_selected, None, status, workspace=ws_plan)
+
+    def route():
+        fs.fs_route_bucketize(ids, offsets, T, B, row_base, placement, n, U, W, self_b, bucket_offsets, out_rows,
+                              out_pos, tier_counts, status, workspace=ws_route)
+
+    def gather():
+        fs.fs_seq_gather_fwd(weights, out_rows, out_pos, 0, n, out, status)
+
+    def backward():
+        fs.fs_seq_grad_bwd(grad_out, out_rows, out_pos, 0, n, R, args.variant, uniq_rows, row_grads, cap_unique,
+                           num_unique, status, workspace=ws_bwd)
 
     def step():
         plan_calls[0] += 1
@@ -151,21 +176,19 @@ def main():
                 plan()
         else:
             plan()                                       # on whatever stream is current (a graph capture's, too)
-        fs.fs_route_bucketize(ids, offsets, T, B, row_base, placement, n, U, W, self_b, bucket_offsets, out_rows,
-                              out_pos, tier_counts, status, workspace=ws_route)
-        fs.fs_seq_gather_fwd(weights, out_rows, out_pos, 0, n, out, status)
-        fs.fs_seq_grad_bwd(grad_out, out_rows, out_pos, 0, n, R, args.variant, uniq_rows, row_grads, cap_unique,
-                           num_unique, status, workspace=ws_bwd)
+        route()
+        gather()
+        backward()
         if plan_stream is not main_stream:
             main_stream.wait_stream(plan_stream)
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step()
     torch.cuda.synchronize()
 
     # ---------------------------------------------------------------- timed region
     # HIP events bracket only the three bandwidth kernels the roofline is about (two event records per
-    # timed launch are not free: with all ~46 launches of a step timed, the step is 4 % slower).
+    # timed launch are not free: with all launches of a step timed, the step is 4 % slower).
     roof_kernels = "gather_rows,bwd_segreduce,bwd_singletons"
     records_per_step = 64
     if args.graph:
@@ -177,39 +200,55 @@ def main():
         graph.replay()                                   # untimed: the first launch of a graph uploads it
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for _ in range(args.steps):
+        for _ in range(steps):
             graph.replay()
         torch.cuda.synchronize()
         t1 = time.perf_counter()
-        fs.fs_prof_begin(records_per_step * args.steps, only=roof_kernels)
-        for _ in range(args.steps):
+        fs.fs_prof_begin(records_per_step * steps, only=roof_kernels)
+        for _ in range(steps):
             step()
         torch.cuda.synchronize()
     else:
-        fs.fs_prof_begin(records_per_step * args.steps, only=roof_kernels)
+        fs.fs_prof_begin(records_per_step * steps, only=roof_kernels)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for _ in range(args.steps):
+        for _ in range(steps):
             step()
         torch.cuda.synchronize()
         t1 = time.perf_counter()
-    roof_records = fs.fs_prof_end(records_per_step * args.steps)
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    roof_records = fs.fs_prof_end(records_per_step * steps)
+    ms_per_step = (t1 - t0) * 1e3 / steps
     assert int(status.item()) == 0, f"device status {int(status.item())}"
     n_u = int(num_unique.item())
 
-    # the same steps once more with every launch timed, for the per-stage breakdown (not part of `value`)
-    fs.fs_prof_begin(records_per_step * args.steps)
-    for _ in range(args.steps):
+    # the same steps once more with an event between the entry points: each call as a whole, its launches
+    # and the gaps between them included (not part of `value`)
+    call_names = ("fs_plan_replication", "fs_route_bucketize", "fs_seq_gather_fwd", "fs_seq_grad_bwd")
+    call_fns = (plan, route, gather, backward)
+    marks = [[torch.cuda.Event(enable_timing=True) for _ in range(len(call_fns) + 1)] for _ in range(steps)]
+    for s in range(steps):
+        marks[s][0].record()
+        for k, fn in enumerate(call_fns):
+            fn()
+            marks[s][k + 1].record()
+        plan_calls[0] += 1
+    torch.cuda.synchronize()
+    call_ms = {name: sum(marks[s][k].elapsed_time(marks[s][k + 1]) for s in range(steps)) / steps
+               for k, name in enumerate(call_names)}
+
+    # and once more with every launch timed, for the per-kernel breakdown
+    fs.fs_prof_begin(records_per_step * steps)
+    for _ in range(steps):
         step()
     torch.cuda.synchronize()
-    records = fs.fs_prof_end(records_per_step * args.steps)
+    records = fs.fs_prof_end(records_per_step * steps)
 
     per_kernel = {}
     for name, ms in records:
         tot, cnt = per_kernel.get(name, (0.0, 0))
         per_kernel[name] = (tot + ms, cnt + 1)
-    kernel_ms = {k: v[0] / args.steps for k, v in per_kernel.items()}           # per step (summed launches)
+    kernel_ms = {k: v[0] / steps for k, v in per_kernel.items()}                # per step (summed launches)
+    launches_per_step = len(records) / steps
     roof = {}
     for name, ms in roof_records:
         tot, cnt = roof.get(name, (0.0, 0))
@@ -229,35 +268,38 @@ def main():
     _, run_len = torch.unique(out_rows, return_counts=True)
     n_1 = int((run_len == 1).sum().item())
     del run_len
+    k_sel = int(num_selected.item())
     alg = {
         "gather_rows": n * row_bytes + n_u * row_bytes + n * 12,                # write out, read each distinct row once, indices
         "bwd_segreduce": (n - n_1) * row_bytes + (n_u - n_1) * D * 4 + n * 8,   # read grad_out once, write row_grads, sorted pairs
         "bwd_singletons": n_1 * row_bytes + n_1 * D * 4 + n * 4,                # one row in, one fp32 row out, the sorted keys
     }
+    # algorithmic bytes of each entry point as a whole: what the operation must move, whatever the
+    # kernels do on the way (the backward's sort traffic, the router's intermediate arrays and the plan's
+    # candidate sort are overhead and count for nothing here)
+    alg_calls = {
+        "fs_seq_gather_fwd": n * row_bytes + n_u * row_bytes + n * 12,
+        "fs_seq_grad_bwd": n * row_bytes + n_u * D * 4 + n * 12 + n_u * 8,      # grad_out once, row_grads once, (row, pos) in, uniq_rows out
+        "fs_route_bucketize": n * (8 + 4 + 8 + 4) + (T * B + 1) * 8,           # id and placement entry in, out_rows and out_pos out, offsets
+        "fs_plan_replication": n * 8 + n_u * 8 + R * 4 + k_sel * 8,            # ids, one counter update per distinct row, counts once, selection out
+    }
     dominant = max(alg, key=lambda k: kernel_avg.get(k, 0.0))
     achieved = alg[dominant] / (kernel_avg[dominant] * 1e-3) / 1e9
-    traffic = None
-    tfile = os.path.join(ROOT, "profiles", "hbm_traffic.json")
-    if os.path.exists(tfile):
-        try:
-            traffic = json.load(open(tfile)).get(f"{cfg.name}:{dominant}")
-        except Exception:
-            traffic = None
+    traffic, traffic_source = traffic_from_profiles(f"{cfg.name}:{dominant}")
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                "traffic_source": traffic_source,
                 "algorithmic_bytes": alg[dominant], "avg_ms": round(kernel_avg[dominant], 4)}
     roofline["also"] = [{"kernel": k, "achieved": round(alg[k] / (kernel_avg[k] * 1e-3) / 1e9, 1),
                          "frac": round(alg[k] / (kernel_avg[k] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-                         "algorithmic_bytes": alg[k], "avg_ms": round(kernel_avg[k], 4)}
+                         "algorithmic_bytes": alg[k], "avg_ms": round(kernel_avg[k], 4),
+                         "traffic": traffic_from_profiles(f"{cfg.name}:{k}")[0]}
                         for k in alg if k != dominant and k in kernel_avg]
+    roofline["calls"] = {name: frac_of_peak(alg_calls[name], call_ms[name]) for name in call_names}
 
     result = {
-        "metric": "embedding lookups/sec and achieved HBM GB/s (% of peak), fwd+bwd, 1 GPU",
-        "value": round(n / (ms_per_step * 1e-3), 1), "unit": "lookups/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": {"f32": "f32", "f16": "f16", "bf16": "bf16"}[cfg.dtype] + " rows, f32 accumulation, int64/int32 indices",
-        "data": "synthetic",
+        "ms_per_step": round(ms_per_step, 4),
+        "value": round(n / (ms_per_step * 1e-3), 1),
         "config": {"workload": f"{cfg.name}: {T} tables x {cfg.E} rows x D={D} {cfg.dtype}, batch {B}, "
                                f"{cfg.length_law} lengths, Zipf({cfg.alpha}), {U} buckets (W={W})",
                    "lookups": n, "distinct_rows": n_u, "single_lookup_rows": n_1, "bwd_variant": args.variant,
@@ -266,9 +308,12 @@ def main():
                    "tier_counts": [int(x) for x in tier_counts.tolist()], "scale_rows": args.scale_rows},
         "roofline": roofline,
         "stage_ms": {k: round(v, 4) for k, v in stage_ms.items()},
+        "launches_per_step": round(launches_per_step, 1),
         "kernel_ms_per_step": {k: round(v, 4) for k, v in sorted(kernel_ms.items())},
         "input_gen_s": round(t_gen, 1),
     }
+    if not full_report:
+        return result, None
 
     # what the tiers of this batch mean for the row exchange (the paper's headline quantity, its Section 6.2)
     _, traffic_report = fs.fs_tier_traffic(tier_counts.tolist(), D, cfg.row_bytes // D)
@@ -300,7 +345,6 @@ def main():
         send = torch.empty(n, D, dtype=cfg.torch_dtype, device=dev)
         store = torch.empty(budget_rows, D, dtype=cfg.torch_dtype, device=dev)
         slots = torch.empty(R, dtype=torch.int32, device=dev)
-        k_sel = int(num_selected.item())
 
         def xstep():
             fs.fs_replica_build(weights, sel_rows, budget_rows, num_selected, store, slots, status)
@@ -364,9 +408,149 @@ def main():
                                        "n_dp": c[5], "dp_share": round(c[8] / max(c[7], 1), 4)}}
         del tier_rows
 
+    keep = (ids, offsets, placement, weights, grad_out)
+    return result, keep
+
+
+def run_c5_planning(args):
+    """The planning configuration: 10^9 sampled ids (4 tables x 250 M, one segment per table) through
+    fs_plan_replication's histogram in calls of 2^26 ids, then the top-k under a 4 GB budget at 256 bytes
+    per row.  Ids are drawn on the GPU chunk by chunk (never resident as a whole); each call is timed with
+    HIP events on its stream while its chunk is resident."""
+    import torch
+    import fs_inputs
+    import paper_2301_02959_amd as fs
+
+    dev = "cuda:0"
+    cfg = fs_inputs.CONFIGS["c5"]
+    R, T = cfg.R, cfg.T
+    per_table = 250_000_000
+    counts = torch.zeros(R, dtype=torch.int32, device=dev)
+    row_base = torch.arange(T + 1, dtype=torch.int64, device=dev) * cfg.E
+    status = torch.zeros(1, dtype=torch.int32, device=dev)
+    budget, bpr = 4_000_000_000, 256
+    cap = min(R, budget // bpr)
+    sel = torch.zeros(cap, dtype=torch.int64, device=dev)
+    nsel = torch.zeros(1, dtype=torch.int64, device=dev)
+    chunk = 1 << 26
+
+    def ws_of(flags, n):
+        size = ctypes.c_size_t(0)
+        z = ctypes.c_void_p(0)
+        rc = fs.lib().fs_plan_replication(z, z, ctypes.c_int32(T), ctypes.c_int32(1), z, ctypes.c_int64(n),
+                                          ctypes.c_int64(R), z, ctypes.c_int32(flags), ctypes.c_int64(budget),
+                                          ctypes.c_int64(bpr), z, z, z, z, ctypes.byref(size), z, z)
+        assert rc == 0, rc
+        return torch.empty(max(int(size.value), 256), dtype=torch.uint8, device=dev)
+
+    ws_acc = ws_of(fs.FS_PLAN_ACCUMULATE, chunk)
+    ws_sel = ws_of(fs.FS_PLAN_SELECT, 0)
+    hist_ms, seen, calls, first = 0.0, 0, 0, True
+    t_wall = time.time()
+    for t, ids in fs_inputs.make_profile_sample(cfg, per_table, dev, chunk=chunk):
+        m = ids.numel()
+        offsets = torch.zeros(T + 1, dtype=torch.int64, device=dev)
+        offsets[t + 1:] = m
+        if first:                                        # untimed: loads the kernels, on counters of its own
+            warm = torch.zeros(R, dtype=torch.int32, device=dev)
+            fs.fs_plan_replication(ids, offsets, T, 1, row_base, m, R, warm, fs.FS_PLAN_ACCUMULATE, dev_status=status,
+                                   workspace=ws_acc)
+            del warm
+            first = False
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        fs.fs_plan_replication(ids, offsets, T, 1, row_base, m, R, counts, fs.FS_PLAN_ACCUMULATE, dev_status=status,
+                               workspace=ws_acc)
+        e1.record()
+        torch.cuda.synchronize()
+        hist_ms += e0.elapsed_time(e1)
+        seen += m
+        calls += 1
+        del ids
+    sel_ms = []
+    for _ in range(3):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        fs.fs_plan_replication(None, None, 1, 1, None, 0, R, counts, fs.FS_PLAN_SELECT, budget, bpr, sel, nsel, None, status,
+                               workspace=ws_sel)
+        e1.record()
+        torch.cuda.synchronize()
+        sel_ms.append(e0.elapsed_time(e1))
+    assert int(status.item()) == 0, f"device status {int(status.item())}"
+    assert int(counts.to(torch.int64).sum().item()) == seen == T * per_table
+    k = int(nsel.item())
+    distinct = int((counts != 0).sum().item())
+    assert k == min(cap, distinct)
+    hist_bytes = seen * 8 + distinct * 8                 # every id once, one counter update per distinct row
+    sel_bytes = R * 4 + k * 8                            # counts once, the selection out
+    total_ms = hist_ms + min(sel_ms)
+    return {
+        "config": {"workload": f"c5 planning: {seen} sampled ids over {T} tables x {cfg.E} rows, Zipf({cfg.alpha}), "
+                               f"histogram in {calls} calls of up to 2^26 ids, then top-k under {budget} bytes at {bpr} "
+                               f"bytes per row",
+                   "ids": seen, "distinct_rows": distinct, "selected": k, "budget_rows": cap},
+        "metric": "sampled ids/sec through fs_plan_replication (histogram, then top-k)", "unit": "ids/s",
+        "value": round(seen / (total_ms * 1e-3), 1), "ms": round(total_ms, 3),
+        "roofline": {"bound": "hbm", "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "calls": {"fs_plan_replication[ACCUMULATE]": {**frac_of_peak(hist_bytes, hist_ms), "launch_calls": calls},
+                               "fs_plan_replication[SELECT]": frac_of_peak(sel_bytes, min(sel_ms))}},
+        "wall_s_with_id_generation": round(time.time() - t_wall, 1),
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print(f"bench.py: this build runs on ONE GPU only (owner buckets are output partitions, no "
+              f"collectives); --gpus {args.gpus} is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import fs_inputs
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    main_name = args.config or "c3"
+    cfg = fs_inputs.CONFIGS[main_name]
+    if args.scale_rows > 1:
+        cfg = cfg.scaled(E=cfg.E // args.scale_rows)
+
+    fields, keep = run_step_config(cfg, args, args.steps, args.warmup, full_report=True)
+    result = {
+        "metric": "embedding lookups/sec and achieved HBM GB/s (% of peak), fwd+bwd, 1 GPU",
+        "value": fields.pop("value"), "unit": "lookups/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": fields.pop("ms_per_step"),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": {"f32": "f32", "f16": "f16", "bf16": "bf16"}[cfg.dtype] + " rows, f32 accumulation, int64/int32 indices",
+        "data": "synthetic",
+    }
+    result.update(fields)
+
     # ---------------------------------------------------------------- CPU oracle on a bounded sample
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(args, cfg, ids, offsets, placement, weights, grad_out)
+        result["cpu_baseline"] = cpu_baseline(args, cfg, *keep)
+    del keep, fields
+    gc.collect()
+    torch.cuda.empty_cache()
+
+    # ---------------------------------------------------------------- the other single-GPU workloads
+    # Only in the default run: c4 (the largest shard, 164 GB of tables: the same step, fewer repetitions)
+    # and the c5 planning pass.  Reported beside the headline, never part of `value`.
+    if args.config is None and not args.no_also:
+        also = []
+        free_b = torch.cuda.mem_get_info()[0]
+        if free_b > 262e9:
+            c4_fields, _ = run_step_config(fs_inputs.CONFIGS["c4"], args, max(3, args.steps // 4), 2, full_report=False)
+            c4_fields["unit"] = "lookups/s"
+            also.append(c4_fields)
+            gc.collect()
+            torch.cuda.empty_cache()
+        else:
+            also.append({"config": {"workload": "c4"}, "skipped": f"needs ~262 GB of free HBM, {free_b / 1e9:.0f} GB free"})
+        also.append(run_c5_planning(args))
+        result["also_configs"] = also
 
     print(json.dumps(result), flush=True)
 
@@ -375,7 +559,6 @@ def cpu_baseline(args, cfg, ids, offsets, placement, weights, grad_out):
     """The oracle as it stands (one thread) on the first tables of the same batch: plan + route +
     gather + backward on the host copy of exactly those inputs."""
     import numpy as np
-    import torch
     import fs_inputs
     import oracle
 
