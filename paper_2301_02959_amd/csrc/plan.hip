@@ -17,9 +17,6 @@
 
 namespace fs {
 
-constexpr int kHistSpan = 32768;          // ids per block
-constexpr int kHistSlots = 4096;          // LDS cache entries
-constexpr int kHistSlotBits = 12;
 constexpr int kSelTile = kBlock * 32;     // rows per block in the compaction (fewer, larger tiles: the one-block
                                           // scan of the tile counts is what they cost)
 
@@ -55,18 +52,30 @@ __global__ __launch_bounds__(kBlock) void plan_check_offsets_kernel(
 
 constexpr int kHistBlock = 1024;          // 16 waves per span: a span per 256 threads leaves the chip idle
 
+// One block counts the ids of [blockIdx.x * span, + span) into an LDS table of 2^SLOT_BITS (row, count)
+// entries: a row takes the first of its two slots (two hashes of the row) that is free or already its
+// own; a row that finds both taken by other rows is added to the global counter at once.  At the end
+// the table is flushed with one saturating add per used slot.  The first row to claim a slot keeps it,
+// so a row lives in at most one slot and the counts stay exact.
+//   SLOT_BITS = 12: 32 KB of LDS, several blocks per CU, spans of 32 k ids (small batches)
+//   SLOT_BITS = 14: 128 KB of LDS, one block per CU, spans of up to 128 k ids: a popular row is flushed
+//                   once per span, so fewer, longer spans mean fewer global updates for the head of the
+//                   distribution, and the larger table keeps the second tier of rows out of the misses
+template <int SLOT_BITS>
 __global__ __launch_bounds__(kHistBlock) void plan_histogram_kernel(
     const int64_t* __restrict__ ids, const int64_t* __restrict__ offsets, int T, int64_t B,
-    const int64_t* __restrict__ row_base, int64_t n, int64_t R, uint32_t* __restrict__ counts,
+    const int64_t* __restrict__ row_base, int64_t n, int64_t R, int64_t span, uint32_t* __restrict__ counts,
     const int32_t* __restrict__ ok_flag, int32_t* status)
 {
-    __shared__ uint32_t tags[kHistSlots];      // row + 1, 0 = free
-    __shared__ uint32_t hits[kHistSlots];
+    constexpr int kSlots = 1 << SLOT_BITS;
+    __shared__ uint32_t tags[kSlots];          // row + 1, 0 = free
+    __shared__ uint32_t hits[kSlots];
     __shared__ int span_tables[2];
     if (*ok_flag == 0) return;                 // bad offsets: count nothing
-    const int64_t base = (int64_t)blockIdx.x * kHistSpan;
-    const int64_t end = base + kHistSpan < n ? base + kHistSpan : n;
-    for (int s = threadIdx.x; s < kHistSlots; s += kHistBlock) { tags[s] = 0; hits[s] = 0; }
+    const int64_t base = (int64_t)blockIdx.x * span;
+    const int64_t end = base + span < n ? base + span : n;
+    if (base >= end) return;
+    for (int s = threadIdx.x; s < kSlots; s += kHistBlock) { tags[s] = 0; hits[s] = 0; }
     if (threadIdx.x == 0) {
         span_tables[0] = plan_table_of(offsets, T, B, base);
         span_tables[1] = plan_table_of(offsets, T, B, end - 1);
@@ -83,13 +92,22 @@ __global__ __launch_bounds__(kHistBlock) void plan_histogram_kernel(
         if (id < 0 || id >= rows_t) { faults |= FS_DEV_BAD_ID; id = 0; }
         if ((uint64_t)(first + id) >= (uint64_t)R) { faults |= FS_DEV_BAD_ID; return; }   // row_base does not fit R
         const uint32_t g = (uint32_t)(first + id);
-        const uint32_t slot = (g * 2654435761u) >> (32 - kHistSlotBits);
-        uint32_t tag = tags[slot];
-        if (tag == 0) tag = atomicCAS(&tags[slot], 0u, g + 1u);
-        if (tag == 0 || tag == g + 1u) atomicAdd(&hits[slot], 1u);
-        else add_saturating(counts + g, 1u, &faults);
+        const uint32_t want = g + 1u;
+        const uint32_t s1 = (g * 2654435761u) >> (32 - SLOT_BITS);
+        uint32_t tag = tags[s1];
+        if (tag == 0) tag = atomicCAS(&tags[s1], 0u, want);
+        if (tag == 0 || tag == want) { atomicAdd(&hits[s1], 1u); return; }
+        const uint32_t s2 = ((g ^ (g >> 15)) * 2246822519u) >> (32 - SLOT_BITS);
+        tag = tags[s2];
+        if (tag == 0) tag = atomicCAS(&tags[s2], 0u, want);
+        if (tag == 0 || tag == want) { atomicAdd(&hits[s2], 1u); return; }
+        add_saturating(counts + g, 1u, &faults);
     };
+#ifdef FS_EXP_HIST_AHEAD
+    constexpr int kAhead = FS_EXP_HIST_AHEAD;
+#else
     constexpr int kAhead = 8;                                    // ids in flight per thread
+#endif
     int64_t i = base + threadIdx.x;
     for (; i + (int64_t)(kAhead - 1) * kHistBlock < end; i += (int64_t)kAhead * kHistBlock) {
         int64_t id[kAhead];
@@ -100,12 +118,60 @@ __global__ __launch_bounds__(kHistBlock) void plan_histogram_kernel(
     }
     for (; i < end; i += kHistBlock) count_one(i, load_stream(ids + i));
     __syncthreads();
-    for (int s = threadIdx.x; s < kHistSlots; s += kHistBlock)
-        if (tags[s] != 0 && hits[s] != 0) add_saturating(counts + (tags[s] - 1u), hits[s], &faults);
+    // The flush: one saturating add per used slot.  A thread's adds are all issued before the first old
+    // value is looked at: one after the other, each waiting for its answer, they are the longest stretch
+    // of a span (nothing else runs on the CU beside the block that holds its LDS).
+    constexpr int kPerThread = kSlots / kHistBlock;
+    constexpr int kBatch = kPerThread < 8 ? kPerThread : 8;
+#pragma unroll 1
+    for (int s0 = 0; s0 < kPerThread; s0 += kBatch) {
+        uint32_t tag[kBatch], add[kBatch], old[kBatch];
+#pragma unroll
+        for (int q = 0; q < kBatch; ++q) {
+            const int s = (s0 + q) * kHistBlock + threadIdx.x;
+            tag[q] = tags[s];
+            add[q] = hits[s];
+        }
+#pragma unroll
+        for (int q = 0; q < kBatch; ++q)
+            old[q] = (tag[q] != 0 && add[q] != 0) ? atomicAdd(counts + (tag[q] - 1u), add[q]) : 0u;
+#pragma unroll
+        for (int q = 0; q < kBatch; ++q) {
+            if (tag[q] != 0 && add[q] != 0 && old[q] > 0xFFFFFFFFu - add[q]) {     // wrapped: pin the counter at the maximum
+                atomicExch(counts + (tag[q] - 1u), 0xFFFFFFFFu);
+                faults |= FS_DEV_COUNT_OVERFLOW;
+            }
+        }
+    }
     if (ballot(faults != 0) != 0) {
         for (int off = 32; off > 0; off >>= 1) faults |= __shfl_down(faults, off);
         if (lane_id() == 0) report(status, faults);
     }
+}
+
+// Span length and table size for n ids: small batches keep the 32 k spans and the small table (many blocks
+// per CU); from two long spans per CU on, spans are as long as the large table serves well (128 k ids),
+// shortened so that their number is a multiple of the CU count where that is possible.
+constexpr int64_t kHistSpanSmall = 32768;
+#ifdef FS_EXP_HIST_SPAN
+constexpr int64_t kHistSpanLarge = FS_EXP_HIST_SPAN;
+#else
+constexpr int64_t kHistSpanLarge = 131072;
+#endif
+constexpr int64_t kHistCus = 256;
+
+static void hist_shape(int64_t n, int64_t* span, bool* large)
+{
+#ifdef FS_EXP_HIST_MIN_LARGE
+    *large = n >= (int64_t)FS_EXP_HIST_MIN_LARGE;
+#else
+    *large = n >= 2 * kHistCus * (kHistSpanLarge / 2);          // at least one 64 k span for every CU, twice over
+#endif
+    if (!*large) { *span = kHistSpanSmall; return; }
+    const int64_t rounds = (n + kHistCus * kHistSpanLarge - 1) / (kHistCus * kHistSpanLarge);   // spans per CU
+    int64_t s = (n + kHistCus * rounds - 1) / (kHistCus * rounds);
+    s = (s + 8191) / 8192 * 8192;                                // whole rounds of 8 ids per thread
+    *span = s < kHistSpanLarge ? s : kHistSpanLarge;
 }
 
 // ---- selection --------------------------------------------------------------
@@ -487,9 +553,19 @@ extern "C" fs_status fs_plan_replication(
         FS_LAUNCH("plan_check_offsets", plan_check_offsets_kernel, dim3(grid), dim3(kBlock), s,
                   offsets, S, n, ok_flag, dev_status);
         if (n > 0) {
-            const int64_t blocks = (n + kHistSpan - 1) / kHistSpan;
-            FS_LAUNCH("plan_histogram", plan_histogram_kernel, dim3((unsigned)blocks), dim3(kHistBlock), s,
-                      ids, offsets, (int)T, (int64_t)B, row_base, n, R, counts, ok_flag, dev_status);
+            int64_t span;
+            bool large;
+            hist_shape(n, &span, &large);
+            const int64_t blocks = (n + span - 1) / span;
+            if (large)
+#ifndef FS_EXP_HIST_BITS
+#define FS_EXP_HIST_BITS 14
+#endif
+                FS_LAUNCH("plan_histogram", plan_histogram_kernel<FS_EXP_HIST_BITS>, dim3((unsigned)blocks), dim3(kHistBlock), s,
+                          ids, offsets, (int)T, (int64_t)B, row_base, n, R, span, counts, ok_flag, dev_status);
+            else
+                FS_LAUNCH("plan_histogram", plan_histogram_kernel<12>, dim3((unsigned)blocks), dim3(kHistBlock), s,
+                          ids, offsets, (int)T, (int64_t)B, row_base, n, R, span, counts, ok_flag, dev_status);
         }
     }
     if (sel) {
