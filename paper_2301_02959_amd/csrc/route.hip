@@ -2,18 +2,20 @@
 //
 // A stable counting sort of the n lookups by destination bucket, in four steps
 // that touch each lookup twice:
-//   route_prepare   validate offsets
 //   route_remap     one 2048-lookup tile per block: table of each lookup, global
 //                   row g, placement entry, destination; per-tile bucket
 //                   histogram (wave-aggregated LDS adds) plus the tile's three tier
-//                   counts; dest (u16) and g (u32) go to the workspace
+//                   counts; dest (u16) and g (u32) go to the workspace; each block also
+//                   validates its share of the offsets
 //   route_scan      one block per bucket (and per tier): exclusive scan of its per-tile
 //                   counts over the tiles, and its total
 //   route_scatter   same tiles: each wave ranks its 512 consecutive lookups by
 //                   ballot matching against a wave-private running histogram in
 //                   LDS, adds the tile's and the bucket's base, writes
 //                   out_rows / out_pos
-//   route_finalize  bucket_offsets and tier_counts
+//                   (its first block also writes bucket_offsets and tier_counts)
+//   route_prepare / route_finalize   only for an empty batch: the offsets check and the
+//                   zero outputs
 // No spin-waits anywhere: the only cross-block communication is between launches.
 #include <atomic>
 
@@ -57,6 +59,17 @@ __global__ __launch_bounds__(kBlock) void route_remap_kernel(
     uint32_t* __restrict__ tile_hist /* [U + 3][tiles]: buckets, then the three tiers */, int64_t tiles,
     int32_t* status)
 {
+    // this block's share of the offsets check (S = T * B segments over `tiles` blocks)
+    {
+        const int64_t S = (int64_t)T * B;
+        const int64_t per = (S + tiles - 1) / tiles;
+        const int64_t lo = (int64_t)blockIdx.x * per;
+        const int64_t hi = lo + per < S ? lo + per : S;
+        bool bad = false;
+        for (int64_t sg = lo + threadIdx.x; sg < hi; sg += kBlock) bad |= offsets[sg] > offsets[sg + 1];
+        if (blockIdx.x == 0 && threadIdx.x == 0) bad |= offsets[0] != 0 || offsets[S] != n;
+        if (ballot(bad) != 0 && lane_id() == 0) report(status, FS_DEV_BAD_OFFSETS);
+    }
     extern __shared__ uint32_t lds_hist[];            // [U]
     __shared__ int tile_tables[2];
     __shared__ unsigned int wave_tiers[kWavesPerBlock][3];
@@ -178,7 +191,8 @@ __global__ __launch_bounds__(kRouteScanBlock) void route_scan_kernel(uint32_t* _
 __global__ __launch_bounds__(kBlock) void route_scatter_kernel(
     const uint16_t* __restrict__ dest_in, const uint32_t* __restrict__ g_in, int64_t n, int U, int dest_bits,
     const uint32_t* __restrict__ tile_hist /* scanned */, int64_t tiles, const uint32_t* __restrict__ totals,
-    int64_t* __restrict__ out_rows, int32_t* __restrict__ out_pos)
+    int64_t* __restrict__ out_rows, int32_t* __restrict__ out_pos,
+    int64_t* __restrict__ bucket_offsets, int64_t* __restrict__ tier_counts)
 {
     extern __shared__ uint32_t lds[];
     uint32_t* bucket_base = lds;                                        // [U] first output index of the tile in bucket b
@@ -207,9 +221,16 @@ __global__ __launch_bounds__(kBlock) void route_scatter_kernel(
         }
         __syncthreads();
         uint32_t run = scan_part[threadIdx.x];
+        const bool writes_offsets = blockIdx.x == 0;                    // tile 0 exists whenever this kernel runs
         for (int b = lo; b < hi; ++b) {
             bucket_base[b] = run + tile_hist[(int64_t)b * tiles + tile];
+            if (writes_offsets) bucket_offsets[b] = (int64_t)run;
             run += totals[b];
+        }
+        if (writes_offsets && threadIdx.x == 0) {
+            bucket_offsets[U] = n;                                      // every lookup has a bucket
+            if (tier_counts != nullptr)
+                for (int k = 0; k < 3; ++k) tier_counts[k] = (int64_t)totals[U + k];
         }
     }
     for (int b = threadIdx.x; b < kWavesPerBlock * U; b += kBlock) wave_hist[b] = 0;
@@ -302,10 +323,15 @@ static fs_status route_run(
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int64_t S = (int64_t)T * B;
     const int dest_bits = bits_for((uint64_t)(U - 1));
-    const unsigned prep_grid = (unsigned)((S + kBlock - 1) / kBlock < 1024 ? (S + kBlock - 1) / kBlock : 1024);
-    FS_LAUNCH("route_prepare", route_prepare_kernel, dim3(prep_grid), dim3(kBlock), s,
-              offsets, S, n, dev_status);
-    if (n > 0) {
+    if (n == 0) {
+        const unsigned prep_grid = (unsigned)((S + kBlock - 1) / kBlock < 1024 ? (S + kBlock - 1) / kBlock : 1024);
+        FS_LAUNCH("route_prepare", route_prepare_kernel, dim3(prep_grid), dim3(kBlock), s,
+                  offsets, S, n, dev_status);
+        FS_LAUNCH("route_finalize", route_finalize_kernel, dim3(1), dim3(kBlock), s,
+                  totals, (int)U, n, bucket_offsets, tier_counts);
+        return FS_OK;
+    }
+    {
         FS_LAUNCH_SMEM("route_remap", route_remap_kernel, dim3((unsigned)tiles), dim3(kBlock),
                        (size_t)U * sizeof(uint32_t), s,
                        ids, offsets, (int)T, (int64_t)B, row_base, placement, n, (int)U, (int)W, (int)self,
@@ -314,10 +340,9 @@ static fs_status route_run(
         const unsigned scatter_grid = (unsigned)xcd_striped_grid(tiles, kRouteStripe);
         FS_LAUNCH_SMEM("route_scatter", route_scatter_kernel, dim3(scatter_grid), dim3(kBlock),
                        (size_t)U * sizeof(uint32_t) + (size_t)kWavesPerBlock * U * sizeof(uint16_t), s,
-                       dest_tmp, g_tmp, n, (int)U, dest_bits, tile_hist, tiles, totals, out_rows, out_pos);
+                       dest_tmp, g_tmp, n, (int)U, dest_bits, tile_hist, tiles, totals, out_rows, out_pos,
+                       bucket_offsets, tier_counts);
     }
-    FS_LAUNCH("route_finalize", route_finalize_kernel, dim3(1), dim3(kBlock), s,
-              totals, (int)U, n, bucket_offsets, tier_counts);
     return FS_OK;
 }
 
