@@ -24,6 +24,14 @@ struct SortSource {
     int32_t* status = nullptr;
 };
 
+// Number of passes radix_sort_pairs makes over keys of key_bits bits.
+inline int radix_sort_passes(int key_bits)
+{
+    if (key_bits < 1) key_bits = 1;
+    if (key_bits > 32) key_bits = 32;
+    return (key_bits + kSortMaxDigitBits - 1) / kSortMaxDigitBits;
+}
+
 // Scratch the sort needs for up to m_max pairs (beyond the two key/value buffers).
 size_t radix_sort_scratch_bytes(int64_t m_max);
 

@@ -3,13 +3,14 @@
 // Per pass, four launches over 4096-pair tiles (blocks walk the tiles with a grid stride):
 //   sort_count    per-tile digit histogram (one LDS add per distinct digit per wave, found by
 //                 ballot matching), stored tile-major
-//   sort_scan_*   exclusive scan of every digit's per-tile counts over the tiles (two levels,
-//                 coalesced across digits), and the digits' totals
+//   sort_scan     exclusive scan of every digit's per-tile counts over the tiles (two levels,
+//                 coalesced across digits), and the digits' totals; the block that finishes its
+//                 chunk of tiles last (a counter, no waiting) runs the second level
 //   sort_scatter  each wave ranks its 1024 consecutive pairs against a wave-private running
 //                 histogram in LDS (ballot matching keeps equal digits in order); the tile is put
 //                 in digit order in LDS, then written out so that consecutive lanes write
 //                 consecutive addresses of one digit's run
-// Stability comes from wave -> tile -> digit prefix order; there are no spin-waits.
+// Stability comes from wave -> tile -> digit prefix order; no block ever waits for another.
 // The first pass can read (int64 row, int32 position) directly, validating them on the way.
 #include "radix_sort.h"
 
@@ -72,10 +73,11 @@ __device__ __forceinline__ void count_digit(uint32_t* hist, uint32_t digit, bool
 template <typename Reader, int NBITS>
 __global__ __launch_bounds__(kBlock) void sort_count_kernel(
     Reader in, int64_t m_max, const int64_t* __restrict__ m_dev,
-    int shift, uint32_t* __restrict__ tile_hist /* [tiles][bins] */)
+    int shift, uint32_t* __restrict__ tile_hist /* [tiles][bins] */, uint32_t* __restrict__ scan_done)
 {
     constexpr int bins = 1 << NBITS;
     __shared__ uint32_t hist[bins];
+    if (blockIdx.x == 0 && threadIdx.x == 0) *scan_done = 0;    // the scan kernel that follows counts its finished blocks here
     const int64_t m = sort_count_of(m_dev, m_max);
     const int64_t used = (m + kSortTile - 1) / kSortTile;      // tiles that hold pairs (m may live on the device)
     constexpr uint32_t mask = (uint32_t)bins - 1u;
@@ -105,54 +107,60 @@ __global__ __launch_bounds__(kBlock) void sort_count_kernel(
 // Column-wise exclusive scan of tile_hist[tile][digit] over the tiles, in two levels so that every
 // access is coalesced across digits.  Level 1: a block takes a chunk of 64 tiles; thread b walks
 // the chunk's tiles for digit b, leaves the running prefix in place and the chunk's sum in
-// chunk_sums[chunk][b].
+// chunk_sums[chunk][b].  Level 2 (one block): thread b walks the chunks for digit b: chunk_sums ->
+// exclusive prefix, totals[b].
 constexpr int kSortChunkTiles = 64;
+#ifdef FS_EXP_SCAN_AHEAD
+constexpr int kScanAhead = FS_EXP_SCAN_AHEAD;
+#else
+constexpr int kScanAhead = 8;
+#endif
 
-__global__ __launch_bounds__(1024) void sort_scan_tiles_kernel(
+__global__ __launch_bounds__(1024) void sort_scan_kernel(
     uint32_t* __restrict__ tile_hist, int bins, int64_t m_max, const int64_t* __restrict__ m_dev,
-    uint32_t* __restrict__ chunk_sums)
+    uint32_t* __restrict__ chunk_sums, uint32_t* __restrict__ totals, uint32_t* __restrict__ scan_done)
 {
+    __shared__ bool is_last;
     const int64_t m = sort_count_of(m_dev, m_max);
     const int64_t used = (m + kSortTile - 1) / kSortTile;
+    const int64_t chunks = (used + kSortChunkTiles - 1) / kSortChunkTiles;
     const int64_t t0 = (int64_t)blockIdx.x * kSortChunkTiles;
-    if (t0 >= used) return;
+    if (t0 >= used) return;                                      // block-uniform: this block has no tiles
     const int64_t t1 = t0 + kSortChunkTiles < used ? t0 + kSortChunkTiles : used;
     for (int b = threadIdx.x; b < bins; b += blockDim.x) {       // launched with one thread per digit (up to 1024)
         uint32_t run = 0;
         int64_t t = t0;
-        for (; t + 8 <= t1; t += 8) {                            // 8 loads in flight
-            uint32_t v[8];
+        for (; t + kScanAhead <= t1; t += kScanAhead) {          // kScanAhead loads in flight: a thread's time is its rounds of loads
+            uint32_t v[kScanAhead];
 #pragma unroll
-            for (int q = 0; q < 8; ++q) v[q] = tile_hist[(t + q) * bins + b];
+            for (int q = 0; q < kScanAhead; ++q) v[q] = tile_hist[(t + q) * bins + b];
 #pragma unroll
-            for (int q = 0; q < 8; ++q) { tile_hist[(t + q) * bins + b] = run; run += v[q]; }
+            for (int q = 0; q < kScanAhead; ++q) { tile_hist[(t + q) * bins + b] = run; run += v[q]; }
         }
         for (; t < t1; ++t) { const uint32_t v = tile_hist[t * bins + b]; tile_hist[t * bins + b] = run; run += v; }
         chunk_sums[(int64_t)blockIdx.x * bins + b] = run;
     }
-}
-
-// Level 2: thread b walks the chunks for digit b: chunk_sums -> exclusive prefix, totals[b].
-__global__ __launch_bounds__(kBlock) void sort_scan_chunks_kernel(
-    uint32_t* __restrict__ chunk_sums, int bins, int64_t m_max, const int64_t* __restrict__ m_dev,
-    uint32_t* __restrict__ totals)
-{
-    const int64_t m = sort_count_of(m_dev, m_max);
-    const int64_t used = (m + kSortTile - 1) / kSortTile;
-    const int64_t chunks = (used + kSortChunkTiles - 1) / kSortChunkTiles;
-    const int b = blockIdx.x * kBlock + threadIdx.x;
-    if (b >= bins) return;
-    uint32_t run = 0;
-    int64_t c = 0;
-    for (; c + 8 <= chunks; c += 8) {
-        uint32_t v[8];
+    // Level 2 needs every block's chunk sums.  Each block publishes its own (fence), then takes a ticket;
+    // the block that draws the last ticket sees all of them (fence) and runs the second level.  Nobody waits.
+    __threadfence();
+    __syncthreads();
+    if (threadIdx.x == 0) is_last = atomicAdd(scan_done, 1u) == (uint32_t)(chunks - 1);
+    __syncthreads();
+    if (!is_last) return;
+    __threadfence();
+    for (int b = threadIdx.x; b < bins; b += blockDim.x) {       // thread b walks the chunks for digit b
+        uint32_t run = 0;
+        int64_t c = 0;
+        for (; c + kScanAhead <= chunks; c += kScanAhead) {
+            uint32_t v[kScanAhead];
 #pragma unroll
-        for (int q = 0; q < 8; ++q) v[q] = chunk_sums[(c + q) * bins + b];
+            for (int q = 0; q < kScanAhead; ++q) v[q] = chunk_sums[(c + q) * bins + b];
 #pragma unroll
-        for (int q = 0; q < 8; ++q) { chunk_sums[(c + q) * bins + b] = run; run += v[q]; }
+            for (int q = 0; q < kScanAhead; ++q) { chunk_sums[(c + q) * bins + b] = run; run += v[q]; }
+        }
+        for (; c < chunks; ++c) { const uint32_t v = chunk_sums[c * bins + b]; chunk_sums[c * bins + b] = run; run += v; }
+        totals[b] = run;
     }
-    for (; c < chunks; ++c) { const uint32_t v = chunk_sums[c * bins + b]; chunk_sums[c * bins + b] = run; run += v; }
-    totals[b] = run;
 }
 
 template <typename Reader, int NBITS>
@@ -296,6 +304,7 @@ size_t radix_sort_scratch_bytes(int64_t m_max)
 {
     Carver c(nullptr);
     c.take<uint32_t>((size_t)kSortMaxBins);
+    c.take<uint32_t>(1);
     c.take<uint32_t>((size_t)kSortMaxBins * (size_t)sort_tiles(m_max));
     c.take<uint32_t>((size_t)kSortMaxBins * (size_t)((sort_tiles(m_max) + kSortChunkTiles - 1) / kSortChunkTiles));
     return c.used;
@@ -314,6 +323,7 @@ fs_status radix_sort_pairs(uint32_t* keys_a, uint32_t* vals_a, uint32_t* keys_b,
     if (tiles > 0x7FFFFFFF) return FS_ERR_SIZE;
     Carver c(scratch);
     uint32_t* totals = c.take<uint32_t>((size_t)kSortMaxBins);
+    uint32_t* scan_done = c.take<uint32_t>(1);
     uint32_t* tile_hist = c.take<uint32_t>((size_t)kSortMaxBins * (size_t)tiles);
     const int64_t chunks = (tiles + kSortChunkTiles - 1) / kSortChunkTiles;
     uint32_t* chunk_sums = c.take<uint32_t>((size_t)kSortMaxBins * (size_t)chunks);
@@ -322,7 +332,7 @@ fs_status radix_sort_pairs(uint32_t* keys_a, uint32_t* vals_a, uint32_t* keys_b,
     // is sized for m_max, and idle blocks would otherwise dominate a small sort
     const int64_t padded_tiles = xcd_striped_grid(tiles, kSortStripe);       // a multiple of 8
     const unsigned grid = (unsigned)(padded_tiles < kSortMaxGrid ? padded_tiles : kSortMaxGrid);
-    const int passes = (key_bits + kSortMaxDigitBits - 1) / kSortMaxDigitBits;
+    const int passes = radix_sort_passes(key_bits);
     int shift = 0;
     const bool from_rows = src.rows != nullptr;
     // from_rows: source -> A -> B -> A ...; else A -> B -> A ...
@@ -338,13 +348,11 @@ fs_status radix_sort_pairs(uint32_t* keys_a, uint32_t* vals_a, uint32_t* keys_b,
             const RowPosReader in{src.rows, src.pos, src.R, src.n};
 #define FS_COUNT_ROWS(NB)                                                                                     \
     FS_LAUNCH("sort_count", (sort_count_kernel<RowPosReader, NB>), dim3(grid), dim3(kBlock), stream, in, m_max,     \
-              m_dev, shift, tile_hist)
+              m_dev, shift, tile_hist, scan_done)
             FS_DISPATCH_BITS(nbits, FS_COUNT_ROWS)
 #undef FS_COUNT_ROWS
-            FS_LAUNCH("sort_scan_tiles", sort_scan_tiles_kernel, dim3((unsigned)chunks), dim3(scan_threads), stream,
-                      tile_hist, 1 << nbits, m_max, m_dev, chunk_sums);
-            FS_LAUNCH("sort_scan_chunks", sort_scan_chunks_kernel, dim3(((1u << nbits) + kBlock - 1) / kBlock),
-                      dim3(kBlock), stream, chunk_sums, 1 << nbits, m_max, m_dev, totals);
+            FS_LAUNCH("sort_scan", sort_scan_kernel, dim3((unsigned)chunks), dim3(scan_threads), stream,
+                      tile_hist, 1 << nbits, m_max, m_dev, chunk_sums, totals, scan_done);
 #define FS_SCATTER_ROWS(NB)                                                                                   \
     FS_LAUNCH("sort_scatter", (sort_scatter_kernel<RowPosReader, NB>), dim3(grid), dim3(kBlock), stream, in, m_max, \
               m_dev, shift, tile_hist, chunk_sums, totals, dst_k, dst_v, src.status)
@@ -354,13 +362,11 @@ fs_status radix_sort_pairs(uint32_t* keys_a, uint32_t* vals_a, uint32_t* keys_b,
             const PairReader in{src_k, src_v};
 #define FS_COUNT_PAIRS(NB)                                                                                    \
     FS_LAUNCH("sort_count", (sort_count_kernel<PairReader, NB>), dim3(grid), dim3(kBlock), stream, in, m_max,       \
-              m_dev, shift, tile_hist)
+              m_dev, shift, tile_hist, scan_done)
             FS_DISPATCH_BITS(nbits, FS_COUNT_PAIRS)
 #undef FS_COUNT_PAIRS
-            FS_LAUNCH("sort_scan_tiles", sort_scan_tiles_kernel, dim3((unsigned)chunks), dim3(scan_threads), stream,
-                      tile_hist, 1 << nbits, m_max, m_dev, chunk_sums);
-            FS_LAUNCH("sort_scan_chunks", sort_scan_chunks_kernel, dim3(((1u << nbits) + kBlock - 1) / kBlock),
-                      dim3(kBlock), stream, chunk_sums, 1 << nbits, m_max, m_dev, totals);
+            FS_LAUNCH("sort_scan", sort_scan_kernel, dim3((unsigned)chunks), dim3(scan_threads), stream,
+                      tile_hist, 1 << nbits, m_max, m_dev, chunk_sums, totals, scan_done);
 #define FS_SCATTER_PAIRS(NB)                                                                                  \
     FS_LAUNCH("sort_scatter", (sort_scatter_kernel<PairReader, NB>), dim3(grid), dim3(kBlock), stream, in, m_max,   \
               m_dev, shift, tile_hist, chunk_sums, totals, dst_k, dst_v, (int32_t*)nullptr)
