@@ -3,7 +3,8 @@
 
 One step = one pass of the whole hot path over one synthetic batch resident in HBM:
   fs_plan_replication (histogram of the batch + top-k under a budget)
-  -> fs_route_bucketize -> fs_seq_gather_fwd (all buckets) -> fs_seq_grad_bwd (all buckets).
+  -> fs_route_bucketize -> fs_sort_lookups (the batch's lookups in row order, once)
+  -> fs_seq_gather_fwd (all buckets) -> fs_seq_grad_bwd_sorted (all buckets).
 Prints ONE JSON line: lookups/s over the whole step on c3 (the configuration the bandwidth target is
 stated on), the roofline of the dominant kernel (timed live with HIP events around each launch), the
 roofline of every entry point as a whole call (`roofline.calls`), the CPU oracle timed on a bounded
@@ -132,9 +133,24 @@ def run_step_config(cfg, args, steps: int, warmup: int, full_report: bool):
                                    ctypes.c_int64(row_bytes), z, z, z, z, ctypes.byref(size), z, z)
         assert rc == 0, rc
 
+    def q_sort(size):
+        rc = L.fs_sort_lookups(z, z, ctypes.c_int64(0), ctypes.c_int64(n), ctypes.c_int64(R), ctypes.c_int64(n), z, z,
+                               z, ctypes.byref(size), z, z)
+        assert rc == 0, rc
+
+    def q_bwd_sorted(size):
+        rc = L.fs_seq_grad_bwd_sorted(z, ctypes.c_int64(n), ctypes.c_int32(D), ctypes.c_int(fs_inputs.DTYPE_CODE[cfg.dtype]),
+                                      z, z, ctypes.c_int64(n), ctypes.c_int64(R), ctypes.c_int32(args.variant),
+                                      z, z, ctypes.c_int64(cap_unique), z, z, ctypes.byref(size), z, z)
+        assert rc == 0, rc
+
     cap_unique = 0
     ws_bwd = ws_for(q_bwd)
     ws_plan = ws_for(q_plan)
+    ws_sort = ws_for(q_sort)
+    ws_bwd_sorted = ws_for(q_bwd_sorted)
+    sorted_rows = torch.zeros(n, dtype=torch.int32, device=dev)        # 32-bit words (uint32 on the C side)
+    sorted_pos = torch.zeros(n, dtype=torch.int32, device=dev)
 
     # size row_grads to the batch: a first call with capacity 0 only counts the distinct rows
     fs.fs_route_bucketize(ids, offsets, T, B, row_base, placement, n, U, W, self_b, bucket_offsets, out_rows,
@@ -164,9 +180,19 @@ def run_step_config(cfg, args, steps: int, warmup: int, full_report: bool):
     def gather():
         fs.fs_seq_gather_fwd(weights, out_rows, out_pos, 0, n, out, status)
 
-    def backward():
+    def backward():                                      # the backward that sorts for itself (not in the step)
         fs.fs_seq_grad_bwd(grad_out, out_rows, out_pos, 0, n, R, args.variant, uniq_rows, row_grads, cap_unique,
                            num_unique, status, workspace=ws_bwd)
+
+    def sort_lookups():                                  # one sort per batch, in row order, for whoever wants it
+        fs.fs_sort_lookups(out_rows, out_pos, 0, n, R, n, sorted_rows, sorted_pos, status, workspace=ws_sort)
+
+    def backward_sorted():
+        fs.fs_seq_grad_bwd_sorted(grad_out, sorted_rows, sorted_pos, n, R, args.variant, uniq_rows, row_grads,
+                                  cap_unique, num_unique, status, workspace=ws_bwd_sorted)
+
+    def gather_sorted():                                 # the gather in row order (not in the step)
+        fs.fs_seq_gather_fwd_sorted(weights, sorted_rows, sorted_pos, n, out, status)
 
     def step():
         plan_calls[0] += 1
@@ -177,8 +203,9 @@ def run_step_config(cfg, args, steps: int, warmup: int, full_report: bool):
         else:
             plan()                                       # on whatever stream is current (a graph capture's, too)
         route()
+        sort_lookups()
         gather()
-        backward()
+        backward_sorted()
         if plan_stream is not main_stream:
             main_stream.wait_stream(plan_stream)
 
@@ -223,8 +250,9 @@ def run_step_config(cfg, args, steps: int, warmup: int, full_report: bool):
 
     # the same steps once more with an event between the entry points: each call as a whole, its launches
     # and the gaps between them included (not part of `value`)
-    call_names = ("fs_plan_replication", "fs_route_bucketize", "fs_seq_gather_fwd", "fs_seq_grad_bwd")
-    call_fns = (plan, route, gather, backward)
+    call_names = ("fs_plan_replication", "fs_route_bucketize", "fs_sort_lookups", "fs_seq_gather_fwd",
+                  "fs_seq_grad_bwd_sorted", "fs_seq_grad_bwd", "fs_seq_gather_fwd_sorted")
+    call_fns = (plan, route, sort_lookups, gather, backward_sorted, backward, gather_sorted)    # the last two: not in the step
     marks = [[torch.cuda.Event(enable_timing=True) for _ in range(len(call_fns) + 1)] for _ in range(steps)]
     for s in range(steps):
         marks[s][0].record()
@@ -280,6 +308,9 @@ def run_step_config(cfg, args, steps: int, warmup: int, full_report: bool):
     alg_calls = {
         "fs_seq_gather_fwd": n * row_bytes + n_u * row_bytes + n * 12,
         "fs_seq_grad_bwd": n * row_bytes + n_u * D * 4 + n * 12 + n_u * 8,      # grad_out once, row_grads once, (row, pos) in, uniq_rows out
+        "fs_seq_grad_bwd_sorted": n * row_bytes + n_u * D * 4 + n * 8 + n_u * 8,
+        "fs_seq_gather_fwd_sorted": n * row_bytes + n_u * row_bytes + n * 8,
+        "fs_sort_lookups": n * (12 + 8),                                        # pairs in, pairs out: all of it overhead of the path
         "fs_route_bucketize": n * (8 + 4 + 8 + 4) + (T * B + 1) * 8,           # id and placement entry in, out_rows and out_pos out, offsets
         "fs_plan_replication": n * 8 + n_u * 8 + R * 4 + k_sel * 8,            # ids, one counter update per distinct row, counts once, selection out
     }
@@ -296,6 +327,8 @@ def run_step_config(cfg, args, steps: int, warmup: int, full_report: bool):
                          "traffic": traffic_from_profiles(f"{cfg.name}:{k}")[0]}
                         for k in alg if k != dominant and k in kernel_avg]
     roofline["calls"] = {name: frac_of_peak(alg_calls[name], call_ms[name]) for name in call_names}
+    for name in ("fs_seq_grad_bwd", "fs_seq_gather_fwd_sorted"):
+        roofline["calls"][name]["in_step"] = False       # timed beside the step's calls, for comparison
 
     result = {
         "ms_per_step": round(ms_per_step, 4),

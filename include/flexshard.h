@@ -63,7 +63,8 @@ enum {
     FS_DEV_BAD_PLACEMENT = 4,  /* tier 3, or owner outside its range */
     FS_DEV_COUNT_OVERFLOW = 8, /* a histogram count saturated at 2^32 - 1 */
     FS_DEV_UNIQUE_OVERFLOW = 16, /* more distinct rows than cap_unique */
-    FS_DEV_POS_ORDER = 32      /* bwd: equal rows whose pos is not ascending in j */
+    FS_DEV_POS_ORDER = 32,     /* bwd: equal rows whose pos is not ascending in j */
+    FS_DEV_NOT_SORTED = 64     /* fs_seq_grad_bwd_sorted: rows not ascending */
 };
 
 /*
@@ -283,6 +284,52 @@ fs_status fs_seq_grad_bwd(
     void* stream, int32_t* dev_status);
 
 /*
+ * The backward's sort as a step of its own, so that one sort per batch serves
+ * every pass that wants the lookups in row order (Section 3.2, metrics 4-6: the
+ * same lookups are touched by the forward and by the backward pass).
+ *
+ * fs_sort_lookups -- the lookups rows[j0..j1), pos[j0..j1) in (row asc, pos asc)
+ *   order as 32-bit pairs: sorted_rows[k], sorted_pos[k], k in [0, j1 - j0).
+ *   The sort is stable by row alone, so this is the stated order under
+ *   fs_seq_grad_bwd's precondition (equal rows come with ascending pos in j).
+ *   Data faults: rows[j] outside [0, R) / pos[j] outside [0, n) are replaced by
+ *   row 0 / position 0 (FS_DEV_BAD_ID).  Host faults: as fs_seq_grad_bwd.
+ *
+ * fs_seq_grad_bwd_sorted -- fs_seq_grad_bwd on lookups already in that order
+ *   (m pairs, e.g. as fs_sort_lookups wrote them): same outputs, same summation
+ *   order, bit for bit; its workspace holds only the run counts and the
+ *   carries.  Data faults: a position >= n reads row 0 of grad_out, a row >= R
+ *   is passed through to uniq_rows (both FS_DEV_BAD_ID); rows that are not
+ *   ascending set FS_DEV_NOT_SORTED: every maximal stretch of equal rows is then
+ *   summed as if it were a row of its own, and everything stays in bounds.
+ *
+ * fs_seq_gather_fwd_sorted -- fs_seq_gather_fwd over such pairs:
+ *   out[sorted_pos[k], :] = weights[sorted_rows[k], :] for k in [0, m).  In row
+ *   order every distinct row is fetched from memory once and its repeats follow
+ *   at once (where the repeated rows do not fit the caches in bucket order, this
+ *   is the cheaper order; where they do, bucket order writes more densely).
+ *   Data faults and host faults as fs_seq_gather_fwd.
+ */
+fs_status fs_sort_lookups(
+    const int64_t* rows, const int32_t* pos, int64_t j0, int64_t j1, int64_t R, int64_t n,
+    uint32_t* sorted_rows, uint32_t* sorted_pos,
+    void* workspace, size_t* workspace_bytes /* host */,
+    void* stream, int32_t* dev_status);
+
+fs_status fs_seq_grad_bwd_sorted(
+    const void* grad_out, int64_t n, int32_t D, fs_dtype dtype,
+    const uint32_t* sorted_rows, const uint32_t* sorted_pos, int64_t m, int64_t R,
+    int32_t variant,
+    int64_t* uniq_rows, float* row_grads, int64_t cap_unique, int64_t* num_unique,
+    void* workspace, size_t* workspace_bytes /* host */,
+    void* stream, int32_t* dev_status);
+
+fs_status fs_seq_gather_fwd_sorted(
+    const void* weights, int64_t R, int32_t D, fs_dtype dtype,
+    const uint32_t* sorted_rows, const uint32_t* sorted_pos, int64_t m,
+    void* out, int64_t n, void* stream, int32_t* dev_status);
+
+/*
  * fs_plan_replication -- profile and choose the rows to replicate
  * (Section 4.1: per-row appearance counts; Section 4.3: rows are taken in
  * descending frequency order and, for a given amount of extra memory, the
@@ -424,6 +471,32 @@ fs_status fs_sparse_update(
     const int64_t* uniq_rows, const float* row_grads, int64_t cap_unique, const int64_t* num_unique,
     int32_t optimizer, float lr, float eps, float* state,
     void* store, const int32_t* slot_of_row, int64_t k,
+    void* stream, int32_t* dev_status);
+
+/*
+ * fs_seq_grad_bwd_update -- the backward pass and the optimizer step in one
+ * call (the step that follows the backward pass of Section 3.2; most distinct
+ * rows of a power-law batch are looked up once, and their gradient need not
+ * travel through memory to be applied).  Takes the lookups in row order, as
+ * fs_sort_lookups writes them.  Same result as
+ *     fs_seq_grad_bwd_sorted(..., variant 0, ...) followed by
+ *     fs_sparse_update(weights, ..., uniq_rows, row_grads, cap_unique, num_unique, ...)
+ * bit for bit in weights, state and store, in uniq_rows and *num_unique, and
+ * in row_grads[u, :] for every row looked up more than once; row_grads[u, :]
+ * of a row looked up ONCE is left unwritten (its gradient is applied straight
+ * from grad_out).  Only rows with u < cap_unique are updated.
+ * Data faults: as the two calls; with FS_DEV_NOT_SORTED the result is
+ * unspecified (a row that appears in two stretches is updated twice, possibly
+ * at the same time), in bounds.
+ * Host faults: those of the two calls.
+ */
+fs_status fs_seq_grad_bwd_update(
+    const void* grad_out, int64_t n, int32_t D, fs_dtype dtype,
+    const uint32_t* sorted_rows, const uint32_t* sorted_pos, int64_t m, int64_t R,
+    void* weights, int32_t optimizer, float lr, float eps, float* state,
+    void* store, const int32_t* slot_of_row, int64_t k,
+    int64_t* uniq_rows, float* row_grads, int64_t cap_unique, int64_t* num_unique,
+    void* workspace, size_t* workspace_bytes /* host */,
     void* stream, int32_t* dev_status);
 
 /*

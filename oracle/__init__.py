@@ -20,6 +20,7 @@ _LIB = os.path.join(_HERE, "liboracle.so")
 
 F32, F16, BF16 = 0, 1, 2
 BAD_ID, BAD_OFFSETS, BAD_PLACEMENT, COUNT_OVERFLOW, UNIQUE_OVERFLOW, POS_ORDER = 1, 2, 4, 8, 16, 32
+NOT_SORTED = 64
 PLAN_ACCUMULATE, PLAN_SELECT, PLAN_TAG, PLAN_ALLOW_ZERO = 1, 2, 4, 8
 BWD_TILE = 256
 OPT_SGD, OPT_ADAGRAD_ROWWISE, OPT_ADAGRAD = 0, 1, 2
@@ -178,6 +179,19 @@ def seq_grad_bwd(grad_out: np.ndarray, rows, pos, j0: int, j1: int, R: int, tile
         _p(uniq), _p(g32), _p(g64), ctypes.c_int64(cap), ctypes.byref(nu), ctypes.byref(status))
     k = min(int(nu.value), max(cap, 0))
     return rc, status.value, uniq[:k], g32[:k], (g64[:k] if want64 else None), int(nu.value)
+
+
+def sort_lookups(rows, pos, j0: int, j1: int, R: int, n: int):
+    """Returns (rc, status, sorted_rows uint32[m], sorted_pos uint32[m]): the lookups in (row, pos) order."""
+    rows = _i64(rows)
+    pos = np.ascontiguousarray(pos, dtype=np.int32)
+    m = max(j1 - j0, 0)
+    srows = np.zeros(m, dtype=np.uint32)
+    spos = np.zeros(m, dtype=np.uint32)
+    status = ctypes.c_int32(0)
+    rc = lib().oracle_sort_lookups(_p(rows), _p(pos), ctypes.c_int64(j0), ctypes.c_int64(j1), ctypes.c_int64(R),
+                                   ctypes.c_int64(n), _p(srows), _p(spos), ctypes.byref(status))
+    return rc, status.value, srows, spos
 
 
 def plan_replication(ids, offsets, T: int, B: int, row_base, R: int, counts: np.ndarray, flags: int,

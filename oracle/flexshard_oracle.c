@@ -397,6 +397,35 @@ int oracle_seq_grad_bwd(
     return OK;
 }
 
+/*
+ * The lookups of [j0, j1) in the backward's order, (row asc, pos asc), as
+ * 32-bit pairs (the order the sums above are taken in, written out).
+ */
+int oracle_sort_lookups(
+    const int64_t* rows, const int32_t* pos, int64_t j0, int64_t j1, int64_t R, int64_t n,
+    uint32_t* sorted_rows, uint32_t* sorted_pos, int32_t* status)
+{
+    if (R < 1 || R >= 4294967295LL || n < 0 || j0 < 0 || j0 > j1) return ERR_SIZE;
+    int64_t m = j1 - j0;
+    if (m == 0) return OK;
+    if (!rows || !pos || !sorted_rows || !sorted_pos) return ERR_NULL;
+    lookup_t* lk = (lookup_t*)malloc(sizeof(lookup_t) * (size_t)m);
+    for (int64_t q = 0; q < m; ++q) {
+        int64_t r = rows[j0 + q];
+        int64_t p = pos[j0 + q];
+        if (r < 0 || r >= R) { flag(status, DEV_BAD_ID); r = 0; }
+        if (p < 0 || p >= n) { flag(status, DEV_BAD_ID); p = 0; }
+        lk[q].row = r; lk[q].pos = p; lk[q].j = q;
+    }
+    qsort(lk, (size_t)m, sizeof(lookup_t), by_row_then_pos);
+    for (int64_t k = 0; k < m; ++k) {
+        sorted_rows[k] = (uint32_t)lk[k].row;
+        sorted_pos[k] = (uint32_t)lk[k].pos;
+    }
+    free(lk);
+    return OK;
+}
+
 typedef struct { uint32_t count; int64_t g; } cand_t;
 
 static int by_count_desc_then_row(const void* a, const void* b)

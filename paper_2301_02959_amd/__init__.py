@@ -18,7 +18,7 @@ LIB_PATH = os.environ.get("FLEXSHARD_HIP_LIB", os.path.join(_PKG, "libflexshard_
 
 FS_F32, FS_F16, FS_BF16 = 0, 1, 2
 FS_DEV_BAD_ID, FS_DEV_BAD_OFFSETS, FS_DEV_BAD_PLACEMENT = 1, 2, 4
-FS_DEV_COUNT_OVERFLOW, FS_DEV_UNIQUE_OVERFLOW, FS_DEV_POS_ORDER = 8, 16, 32
+FS_DEV_COUNT_OVERFLOW, FS_DEV_UNIQUE_OVERFLOW, FS_DEV_POS_ORDER, FS_DEV_NOT_SORTED = 8, 16, 32, 64
 FS_PLAN_ACCUMULATE, FS_PLAN_SELECT, FS_PLAN_TAG, FS_PLAN_ALLOW_ZERO = 1, 2, 4, 8
 FS_BWD_TILE = 256
 FS_OPT_SGD, FS_OPT_ADAGRAD_ROWWISE, FS_OPT_ADAGRAD = 0, 1, 2
@@ -32,6 +32,7 @@ STATUS_NAMES = {0: "FS_OK", 1: "FS_ERR_NULL", 2: "FS_ERR_SIZE", 3: "FS_ERR_DTYPE
                 5: "FS_ERR_WORKSPACE", 6: "FS_ERR_CONFIG", 7: "FS_ERR_DEVICE"}
 
 EXPORTS = ["fs_route_bucketize", "fs_route_bucketize_noalloc", "fs_seq_gather_fwd", "fs_seq_grad_bwd", "fs_plan_replication",
+           "fs_sort_lookups", "fs_seq_grad_bwd_sorted", "fs_seq_gather_fwd_sorted", "fs_seq_grad_bwd_update",
            "fs_seq_gather_send", "fs_seq_unbucketize", "fs_replica_build", "fs_seq_gather_fwd_replica", "fs_plan_tiers",
            "fs_cost_model", "fs_tier_traffic", "fs_sparse_update", "fs_util_copy", "fs_version", "fs_bwd_tile", "fs_prof_begin", "fs_prof_only", "fs_prof_end"]
 
@@ -55,7 +56,8 @@ def lib() -> ctypes.CDLL:
                 f"{LIB_PATH} is missing: build it with `python -m paper_2301_02959_amd.build` "
                 "(hipcc, gfx950); this package has no other code path")
         _lib = ctypes.CDLL(LIB_PATH)
-        for name in ("fs_route_bucketize", "fs_route_bucketize_noalloc", "fs_seq_gather_fwd", "fs_seq_grad_bwd", "fs_plan_replication",
+        for name in ("fs_sort_lookups", "fs_seq_grad_bwd_sorted", "fs_seq_gather_fwd_sorted", "fs_seq_grad_bwd_update",
+                     "fs_route_bucketize", "fs_route_bucketize_noalloc", "fs_seq_gather_fwd", "fs_seq_grad_bwd", "fs_plan_replication",
                      "fs_seq_gather_send", "fs_seq_unbucketize", "fs_replica_build",
                      "fs_seq_gather_fwd_replica", "fs_plan_tiers", "fs_cost_model", "fs_tier_traffic", "fs_sparse_update", "fs_prof_begin", "fs_prof_only",
                      "fs_util_copy"):
@@ -235,6 +237,63 @@ def fs_seq_grad_bwd(grad_out, rows, pos, j0: int, j1: int, R: int, variant: int,
     return _check("fs_seq_grad_bwd", call(_ptr(workspace), ctypes.byref(size)), raise_on_error)
 
 
+def fs_sort_lookups(rows, pos, j0: int, j1: int, R: int, n: int, sorted_rows, sorted_pos, dev_status=None,
+                    workspace: Optional[torch.Tensor] = None, raise_on_error: bool = True) -> int:
+    L = lib()
+
+    def call(ws_ptr, ws_size_ref):
+        return L.fs_sort_lookups(_ptr(rows, _I64), _ptr(pos, _I32), ctypes.c_int64(j0), ctypes.c_int64(j1), ctypes.c_int64(R),
+                                 ctypes.c_int64(n), _ptr(sorted_rows, _U32), _ptr(sorted_pos, _U32), ws_ptr, ws_size_ref,
+                                 _stream(), _ptr(dev_status, _I32))
+
+    if workspace is None:
+        device = next((t.device for t in (rows, sorted_rows, pos) if t is not None), "cuda")
+        workspace, size, code = _workspace(call, device)
+        if code != 0:
+            return _check("fs_sort_lookups", code, raise_on_error)
+    else:
+        size = ctypes.c_size_t(workspace.numel())
+    return _check("fs_sort_lookups", call(_ptr(workspace), ctypes.byref(size)), raise_on_error)
+
+
+def fs_seq_grad_bwd_sorted(grad_out, sorted_rows, sorted_pos, m: int, R: int, variant: int,
+                           uniq_rows, row_grads, cap_unique: int, num_unique, dev_status=None,
+                           workspace: Optional[torch.Tensor] = None, raise_on_error: bool = True,
+                           n: Optional[int] = None, D: Optional[int] = None, dtype: Optional[int] = None) -> int:
+    L = lib()
+    n = grad_out.shape[0] if n is None else n
+    D = grad_out.shape[1] if D is None else D
+    dtype = _DTYPES[grad_out.dtype] if dtype is None else dtype
+
+    def call(ws_ptr, ws_size_ref):
+        return L.fs_seq_grad_bwd_sorted(
+            _ptr(grad_out, _ROWS), ctypes.c_int64(n), ctypes.c_int32(D), ctypes.c_int(dtype), _ptr(sorted_rows, _U32),
+            _ptr(sorted_pos, _U32), ctypes.c_int64(m), ctypes.c_int64(R), ctypes.c_int32(variant),
+            _ptr(uniq_rows, _I64), _ptr(row_grads, _F32), ctypes.c_int64(cap_unique), _ptr(num_unique, _I64),
+            ws_ptr, ws_size_ref, _stream(), _ptr(dev_status, _I32))
+
+    if workspace is None:
+        workspace, size, code = _workspace(call, grad_out.device)
+        if code != 0:
+            return _check("fs_seq_grad_bwd_sorted", code, raise_on_error)
+    else:
+        size = ctypes.c_size_t(workspace.numel())
+    return _check("fs_seq_grad_bwd_sorted", call(_ptr(workspace), ctypes.byref(size)), raise_on_error)
+
+
+def fs_seq_gather_fwd_sorted(weights, sorted_rows, sorted_pos, m: int, out, dev_status=None,
+                             raise_on_error: bool = True, R: Optional[int] = None, D: Optional[int] = None,
+                             dtype: Optional[int] = None, n: Optional[int] = None) -> int:
+    R = weights.shape[0] if R is None else R
+    D = weights.shape[1] if D is None else D
+    n = out.shape[0] if n is None else n
+    dtype = _DTYPES[weights.dtype] if dtype is None else dtype
+    code = lib().fs_seq_gather_fwd_sorted(
+        _ptr(weights, _ROWS), ctypes.c_int64(R), ctypes.c_int32(D), ctypes.c_int(dtype), _ptr(sorted_rows, _U32),
+        _ptr(sorted_pos, _U32), ctypes.c_int64(m), _ptr(out, _ROWS), ctypes.c_int64(n), _stream(), _ptr(dev_status, _I32))
+    return _check("fs_seq_gather_fwd_sorted", code, raise_on_error)
+
+
 def fs_plan_replication(ids, offsets, T: int, B: int, row_base, n: int, R: int, counts, flags: int,
                         budget_bytes: int = 0, bytes_per_row: int = 1, sel_rows=None, num_selected=None,
                         placement=None, dev_status=None, workspace: Optional[torch.Tensor] = None,
@@ -296,6 +355,33 @@ def fs_sparse_update(weights, uniq_rows, row_grads, cap_unique: int, num_unique,
         ctypes.c_int64(cap_unique), _ptr(num_unique, _I64), ctypes.c_int32(optimizer), ctypes.c_float(lr), ctypes.c_float(eps),
         _ptr(state, _F32), _ptr(store, _ROWS), _ptr(slot_of_row, _I32), ctypes.c_int64(k), _stream(), _ptr(dev_status, _I32))
     return _check("fs_sparse_update", code, raise_on_error)
+
+
+def fs_seq_grad_bwd_update(grad_out, sorted_rows, sorted_pos, m: int, R: int, weights, optimizer: int, lr: float,
+                           eps: float, state, store, slot_of_row, k: int, uniq_rows, row_grads, cap_unique: int,
+                           num_unique, dev_status=None, workspace: Optional[torch.Tensor] = None,
+                           raise_on_error: bool = True, n: Optional[int] = None, D: Optional[int] = None,
+                           dtype: Optional[int] = None) -> int:
+    L = lib()
+    n = grad_out.shape[0] if n is None else n
+    D = grad_out.shape[1] if D is None else D
+    dtype = _DTYPES[grad_out.dtype] if dtype is None else dtype
+
+    def call(ws_ptr, ws_size_ref):
+        return L.fs_seq_grad_bwd_update(
+            _ptr(grad_out, _ROWS), ctypes.c_int64(n), ctypes.c_int32(D), ctypes.c_int(dtype), _ptr(sorted_rows, _U32),
+            _ptr(sorted_pos, _U32), ctypes.c_int64(m), ctypes.c_int64(R), _ptr(weights, _ROWS), ctypes.c_int32(optimizer),
+            ctypes.c_float(lr), ctypes.c_float(eps), _ptr(state, _F32), _ptr(store, _ROWS), _ptr(slot_of_row, _I32),
+            ctypes.c_int64(k), _ptr(uniq_rows, _I64), _ptr(row_grads, _F32), ctypes.c_int64(cap_unique),
+            _ptr(num_unique, _I64), ws_ptr, ws_size_ref, _stream(), _ptr(dev_status, _I32))
+
+    if workspace is None:
+        workspace, size, code = _workspace(call, grad_out.device)
+        if code != 0:
+            return _check("fs_seq_grad_bwd_update", code, raise_on_error)
+    else:
+        size = ctypes.c_size_t(workspace.numel())
+    return _check("fs_seq_grad_bwd_update", call(_ptr(workspace), ctypes.byref(size)), raise_on_error)
 
 
 class CostParams(ctypes.Structure):

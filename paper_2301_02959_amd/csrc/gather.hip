@@ -26,7 +26,11 @@ constexpr int kGatherRowsPerBlock = kGatherRowsPerWave * kWavesPerBlock;
 template <int LG>
 struct GatherShape {
     static constexpr int RPI = kWave / LG;                                   // rows per instruction
+#ifdef FS_EXP_GATHER_UNR16
+    static constexpr int UNR = RPI >= 8 ? kWave / RPI : (LG == 16 ? FS_EXP_GATHER_UNR16 : 16);
+#else
     static constexpr int UNR = RPI >= 8 ? kWave / RPI : (LG == 16 ? 8 : 16); // instructions in flight
+#endif
 };
 
 // Moves the wave's 64 rows.  GUARD = false: every lookup of the wave is valid, loads and
@@ -81,13 +85,15 @@ __device__ __forceinline__ void gather_wave(int units, u32x4* __restrict__ out,
 //   kToSend:   out[j]       = weights[rows[j]]     (fs_seq_gather_send, fs_replica_build)
 //   (fs_seq_unbucketize, out[pos[j]] = recv[j], has a kernel of its own further down)
 //   kReplica:  as kBoth, but a row with slot_of_row[row] >= 0 is read from store[slot]
-enum GatherMode { kBoth = 0, kToSend = 1, kReplica = 3 };
+//   kSorted:   as kBoth with the lookups as 32-bit (row, position) pairs (fs_seq_gather_fwd_sorted)
+enum GatherMode { kBoth = 0, kToSend = 1, kReplica = 3, kSorted = 4 };
 
 struct GatherArgs {
     const u32x4* weights;
     int64_t R;
     int units;
     const int64_t* rows;
+    const uint32_t* rows32;          // kSorted only (then rows is unused)
     const int32_t* pos;
     int64_t m;
     const int64_t* m_dev;            // if set, only the first min(m, *m_dev) lookups are moved
@@ -127,7 +133,7 @@ __global__ __launch_bounds__(kBlock) void gather_rows_kernel(const GatherArgs a)
     int32_t my_pos = 0;
     int my_ok = 0;
     if (jj < m) {
-        my_row = load_stream(a.rows + jj);
+        my_row = MODE == kSorted ? (int64_t)load_stream(a.rows32 + jj) : load_stream(a.rows + jj);
         my_pos = MODE == kToSend ? (int32_t)jj : load_stream(a.pos + jj);
         // unsigned compares: one test each also catches the negative values (n < 2^31)
         my_ok = ((uint64_t)my_row < (uint64_t)a.R && (uint32_t)my_pos < (uint32_t)a.n) ? 1 : 0;
@@ -355,4 +361,23 @@ extern "C" fs_status fs_seq_gather_fwd_replica(
     a.out = static_cast<u32x4*>(out); a.n = n; a.status = dev_status;
     a.store = static_cast<const u32x4*>(store); a.slot_of_row = slot_of_row; a.k = k;
     return launch_gather<kReplica>(a, "gather_replica", static_cast<hipStream_t>(stream));
+}
+
+extern "C" fs_status fs_seq_gather_fwd_sorted(
+    const void* weights, int64_t R, int32_t D, fs_dtype dtype,
+    const uint32_t* sorted_rows, const uint32_t* sorted_pos, int64_t m,
+    void* out, int64_t n, void* stream, int32_t* dev_status)
+{
+    using namespace fs;
+    GatherArgs a = {};
+    const fs_status st = check_rows(weights, out, D, dtype, &a);
+    if (st == FS_ERR_DTYPE) return st;
+    if (R < 1 || n < 0 || n >= (1LL << 31) || D < 1 || m < 0 || m >= (1LL << 31)) return FS_ERR_SIZE;
+    if (m == 0) return FS_OK;
+    if (!weights || !sorted_rows || !sorted_pos || !out) return FS_ERR_NULL;
+    if (st != FS_OK) return st;
+    a.weights = static_cast<const u32x4*>(weights); a.R = R;
+    a.rows32 = sorted_rows; a.pos = reinterpret_cast<const int32_t*>(sorted_pos); a.m = m;   // a position >= 2^31 fails the range check
+    a.out = static_cast<u32x4*>(out); a.n = n; a.status = dev_status;
+    return launch_gather<kSorted>(a, "gather_sorted", static_cast<hipStream_t>(stream));
 }

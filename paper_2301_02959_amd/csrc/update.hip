@@ -18,140 +18,10 @@
 // division and square root); the new weight is rounded once to the table's type, to nearest even.
 // Rows longer than 64 pieces (1 KB) take a slower path: one wave per row, piece by piece.
 #include "fs_common.h"
+#include "update_rules.h"
 
 namespace fs {
 
-typedef _Float16 h16x8 __attribute__((ext_vector_type(8)));
-
-struct UpdateArgs {
-    u32x4* weights;
-    int64_t R;
-    int units;                       // 16-byte pieces per table row
-    int D;
-    const int64_t* uniq_rows;
-    const float* row_grads;
-    int64_t cap;
-    const int64_t* num_unique;       // device; only the first min(cap, *num_unique) entries are applied
-    float lr, eps;
-    float* state;
-    u32x4* store;                    // replica store, or nullptr
-    const int32_t* slot_of_row;
-    int64_t k;
-    int32_t* status;
-};
-
-template <int DT>
-struct Elems {
-    static constexpr int N = DT == FS_F32 ? 4 : 8;
-    static __device__ __forceinline__ void unpack(const u32x4& x, float* f)
-    {
-        if constexpr (DT == FS_F32) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) f[i] = __uint_as_float(x[i]);
-        } else if constexpr (DT == FS_F16) {
-            const h16x8 h = __builtin_bit_cast(h16x8, x);
-#pragma unroll
-            for (int i = 0; i < 8; ++i) f[i] = (float)h[i];
-        } else {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                f[2 * i] = __uint_as_float(x[i] << 16);
-                f[2 * i + 1] = __uint_as_float(x[i] & 0xFFFF0000u);
-            }
-        }
-    }
-    static __device__ __forceinline__ uint32_t bf16_bits(float v)     // round to nearest even
-    {
-        const uint32_t b = __float_as_uint(v);
-        if ((b & 0x7FFFFFFFu) > 0x7F800000u) return (b >> 16) | 0x40u;          // NaN stays NaN
-        return (b + 0x7FFFu + ((b >> 16) & 1u)) >> 16;
-    }
-    static __device__ __forceinline__ u32x4 pack(const float* f)
-    {
-        u32x4 x;
-        if constexpr (DT == FS_F32) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) x[i] = __float_as_uint(f[i]);
-        } else if constexpr (DT == FS_F16) {
-            h16x8 h;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) h[i] = (_Float16)f[i];                  // v_cvt_f16_f32: nearest even
-            x = __builtin_bit_cast(u32x4, h);
-        } else {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) x[i] = bf16_bits(f[2 * i]) | (bf16_bits(f[2 * i + 1]) << 16);
-        }
-        return x;
-    }
-};
-
-// The new values of one lane's N elements.  s_row: the row-wise state after this step.
-template <int N, int OPT>
-__device__ __forceinline__ void apply_rule(float* w, const float* g, float* s, float s_row, float lr, float eps)
-{
-#pragma unroll
-    for (int i = 0; i < N; ++i) {
-        const float lg = lr * g[i];
-        if constexpr (OPT == FS_OPT_SGD) {
-            w[i] = w[i] - lg;
-        } else if constexpr (OPT == FS_OPT_ADAGRAD) {
-            s[i] = s[i] + g[i] * g[i];
-            w[i] = w[i] - lg / (sqrtf(s[i]) + eps);
-        } else {
-            w[i] = w[i] - lg / (sqrtf(s_row) + eps);
-        }
-    }
-}
-
-// Four consecutive elements of a table row: 16 bytes of fp32, 8 bytes of a 16-bit type.
-template <int DT>
-struct Quad {
-    typedef u32x4 type;
-    static __device__ __forceinline__ void unpack(const type& x, float* f)
-    {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) f[i] = __uint_as_float(x[i]);
-    }
-    static __device__ __forceinline__ type pack(const float* f)
-    {
-        return type{__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]), __float_as_uint(f[3])};
-    }
-};
-template <>
-struct Quad<FS_F16> {
-    typedef u32x2 type;
-    typedef _Float16 h16x4 __attribute__((ext_vector_type(4)));
-    static __device__ __forceinline__ void unpack(const type& x, float* f)
-    {
-        const h16x4 h = __builtin_bit_cast(h16x4, x);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) f[i] = (float)h[i];
-    }
-    static __device__ __forceinline__ type pack(const float* f)
-    {
-        h16x4 h;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) h[i] = (_Float16)f[i];                      // v_cvt_f16_f32: nearest even
-        return __builtin_bit_cast(type, h);
-    }
-};
-template <>
-struct Quad<FS_BF16> {
-    typedef u32x2 type;
-    static __device__ __forceinline__ void unpack(const type& x, float* f)
-    {
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            f[2 * i] = __uint_as_float(x[i] << 16);
-            f[2 * i + 1] = __uint_as_float(x[i] & 0xFFFF0000u);
-        }
-    }
-    static __device__ __forceinline__ type pack(const float* f)
-    {
-        return type{Elems<FS_BF16>::bf16_bits(f[0]) | (Elems<FS_BF16>::bf16_bits(f[1]) << 16),
-                    Elems<FS_BF16>::bf16_bits(f[2]) | (Elems<FS_BF16>::bf16_bits(f[3]) << 16)};
-    }
-};
 
 // A group of LG lanes owns a row of up to LG * N elements, in quads of 4 elements: lane i takes quad
 // i of every run of LG quads (one run for fp32 tables, two for 16-bit tables), so that the fp32
@@ -171,6 +41,7 @@ __global__ __launch_bounds__(kBlock) void sparse_update_kernel(const UpdateArgs 
     if (a.num_unique) { const int64_t nu = *a.num_unique; m = nu < m ? (nu < 0 ? 0 : nu) : m; }
     if (wbase >= m) return;                                          // wave-uniform
 
+    __shared__ uint8_t s_from[kWavesPerBlock][kWave];
     const int64_t jj = wbase + lane;
     int64_t my_row = 0;
     int my_ok = 0, my_slot = -1;
@@ -178,6 +49,7 @@ __global__ __launch_bounds__(kBlock) void sparse_update_kernel(const UpdateArgs 
         my_row = a.uniq_rows[jj];
         my_ok = (uint64_t)my_row < (uint64_t)a.R ? 1 : 0;
         if (!my_ok) { report(a.status, FS_DEV_BAD_ID); my_row = 0; }
+        else if (a.skip != nullptr && a.skip[jj] != 0) { my_ok = 0; my_row = 0; }
         else if (a.store != nullptr) {
             my_slot = a.slot_of_row[my_row];
             if (my_slot >= a.k) { report(a.status, FS_DEV_BAD_ID); my_slot = -1; }
@@ -197,17 +69,28 @@ __global__ __launch_bounds__(kBlock) void sparse_update_kernel(const UpdateArgs 
     const quad_t* wq = reinterpret_cast<const quad_t*>(a.weights);   // a quad is element index / 4
     quad_t* wq_out = reinterpret_cast<quad_t*>(a.weights);
     quad_t* store_out = reinterpret_cast<quad_t*>(a.store);
+    // the wave's entries that have work, packed: the rounds below only walk those (with most entries
+    // skipped, the rest would still cost a round of loads each)
+    const uint64_t live = ballot(my_ok != 0);
+    const int cnt = __popcll(live);
+    if (cnt == 0) return;                                            // wave-uniform
+    if (my_ok) s_from[wave_id()][popc_below(live)] = (uint8_t)lane;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const int first_live = s_from[wave_id()][0];
 #pragma unroll 1
-    for (int s0 = 0; s0 < kWave; s0 += UNR * RPI) {
+    for (int s0 = 0; s0 < cnt; s0 += UNR * RPI) {
         int64_t r[UNR], u[UNR];
         int ok[UNR], sl[UNR];
 #pragma unroll
         for (int j = 0; j < UNR; ++j) {
-            const int from = s0 + j * RPI + g;
+            const int at = s0 + j * RPI + g;
+            ok[j] = at < cnt;
+            const int from = ok[j] ? s_from[wave_id()][at] : first_live;   // past the list: the first entry again, not stored
             r[j] = __shfl(my_row, from);
-            ok[j] = __shfl(my_ok, from);
             sl[j] = __shfl(my_slot, from);
-            u[j] = ok[j] ? wbase + from : wbase;                     // an entry that is skipped reads entry wbase
+            u[j] = wbase + from;
         }
         quad_t wx[UNR][P];
         f32x4 gx[UNR][P], sx[UNR][P];
@@ -224,43 +107,9 @@ __global__ __launch_bounds__(kBlock) void sparse_update_kernel(const UpdateArgs 
             if constexpr (OPT == FS_OPT_ADAGRAD_ROWWISE) srow[j] = a.state[r[j]];
         }
 #pragma unroll
-        for (int j = 0; j < UNR; ++j) {
-            float s_row = 0.0f;
-            if constexpr (OPT == FS_OPT_ADAGRAD_ROWWISE) {
-                float sq = 0.0f;
-#pragma unroll
-                for (int p = 0; p < P; ++p) {
-                    if (on[p]) {
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) sq = sq + gx[j][p][i] * gx[j][p][i];
-                    }
-                }
-#pragma unroll
-                for (int off = 1; off < LG; off <<= 1) sq = sq + __shfl_xor(sq, off);
-                s_row = srow[j] + sq / (float)a.D;
-            }
-#pragma unroll
-            for (int p = 0; p < P; ++p) {
-                float w[4], gf[4], sf[4];
-                Quad<DT>::unpack(wx[j][p], w);
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    gf[i] = gx[j][p][i];
-                    if constexpr (OPT == FS_OPT_ADAGRAD) sf[i] = sx[j][p][i];
-                }
-                apply_rule<4, OPT>(w, gf, sf, s_row, a.lr, a.eps);
-                if (ok[j] && on[p]) {
-                    const quad_t out = Quad<DT>::pack(w);
-                    store_stream(wq_out + ((r[j] * D + col[p]) >> 2), out);
-                    if (sl[j] >= 0) store_out[((int64_t)sl[j] * D + col[p]) >> 2] = out;
-                    if constexpr (OPT == FS_OPT_ADAGRAD)
-                        store_stream(reinterpret_cast<f32x4*>(a.state + r[j] * D + col[p]), f32x4{sf[0], sf[1], sf[2], sf[3]});
-                }
-            }
-            if constexpr (OPT == FS_OPT_ADAGRAD_ROWWISE) {
-                if (ok[j] && lig == 0) a.state[r[j]] = s_row;
-            }
-        }
+        for (int j = 0; j < UNR; ++j)
+            RowUpdate<LG, DT, OPT>::apply(wx[j], gx[j], sx[j], srow[j], on, col, r[j], D, lig, ok[j] != 0, sl[j], a.lr,
+                                          a.eps, wq_out, store_out, a.state);
     }
 }
 
@@ -277,6 +126,7 @@ __global__ __launch_bounds__(kBlock) void sparse_update_long_kernel(const Update
     if (u >= m) return;                                              // wave-uniform
     const int64_t r = a.uniq_rows[u];
     if ((uint64_t)r >= (uint64_t)a.R) { if (lane == 0) report(a.status, FS_DEV_BAD_ID); return; }
+    if (a.skip != nullptr && a.skip[u] != 0) return;
     int slot = -1;
     if (a.store != nullptr) {
         slot = a.slot_of_row[r];
@@ -357,6 +207,13 @@ static fs_status launch_update_opt(const UpdateArgs& a, int optimizer, hipStream
     return launch_update<DT, FS_OPT_ADAGRAD_ROWWISE>(a, stream);
 }
 
+fs_status sparse_update_launch(const UpdateArgs& a, fs_dtype dtype, int optimizer, hipStream_t s)
+{
+    if (dtype == FS_F32) return launch_update_opt<FS_F32>(a, optimizer, s);
+    if (dtype == FS_F16) return launch_update_opt<FS_F16>(a, optimizer, s);
+    return launch_update_opt<FS_BF16>(a, optimizer, s);
+}
+
 }  // namespace fs
 
 extern "C" fs_status fs_sparse_update(
@@ -385,8 +242,6 @@ extern "C" fs_status fs_sparse_update(
     a.uniq_rows = uniq_rows; a.row_grads = row_grads; a.cap = cap_unique; a.num_unique = num_unique;
     a.lr = lr; a.eps = eps; a.state = state;
     a.store = static_cast<u32x4*>(store); a.slot_of_row = slot_of_row; a.k = k; a.status = dev_status;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    if (dtype == FS_F32) return launch_update_opt<FS_F32>(a, optimizer, s);
-    if (dtype == FS_F16) return launch_update_opt<FS_F16>(a, optimizer, s);
-    return launch_update_opt<FS_BF16>(a, optimizer, s);
+    a.skip = nullptr;
+    return sparse_update_launch(a, dtype, optimizer, static_cast<hipStream_t>(stream));
 }

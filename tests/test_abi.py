@@ -45,6 +45,7 @@ def test_oracle_and_library_constants_agree_by_value():
     assert (oracle.BAD_ID, oracle.BAD_OFFSETS, oracle.BAD_PLACEMENT, oracle.COUNT_OVERFLOW, oracle.UNIQUE_OVERFLOW,
             oracle.POS_ORDER) == (fs.FS_DEV_BAD_ID, fs.FS_DEV_BAD_OFFSETS, fs.FS_DEV_BAD_PLACEMENT,
                                   fs.FS_DEV_COUNT_OVERFLOW, fs.FS_DEV_UNIQUE_OVERFLOW, fs.FS_DEV_POS_ORDER)
+    assert oracle.NOT_SORTED == fs.FS_DEV_NOT_SORTED
     assert oracle.BWD_TILE == fs.FS_BWD_TILE
     assert (oracle.F32, oracle.F16, oracle.BF16) == (fs.FS_F32, fs.FS_F16, fs.FS_BF16)
 

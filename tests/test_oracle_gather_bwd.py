@@ -203,3 +203,23 @@ def test_range_capacity_and_faults():
     assert st & oracle.BAD_ID and u.tolist() == [0, 1] and np.array_equal(g[1], grad[0])
     assert oracle.seq_grad_bwd(grad[:, :3].copy(), rows, pos, 0, 10, 10)[0] == 4
     assert oracle.seq_grad_bwd(grad, rows, pos, 3, 2, 10)[0] == 2
+
+
+def test_sort_lookups_is_lexsort_by_row_then_pos():
+    """The backward's order written out: numpy's lexsort of the range, faults replaced and flagged."""
+    rng = np.random.default_rng(12)
+    n, R = 5000, 300
+    rows = np.minimum(rng.pareto(0.8, n).astype(np.int64), R - 1)
+    pos = rng.permutation(n).astype(np.int32)
+    for j0, j1 in ((0, n), (17, 4000), (n, n)):
+        rc, st, srows, spos = oracle.sort_lookups(rows, pos, j0, j1, R, n)
+        order = np.lexsort((pos[j0:j1], rows[j0:j1]))
+        assert (rc, st) == (0, 0) and srows.dtype == np.uint32 and spos.dtype == np.uint32
+        assert np.array_equal(srows, rows[j0:j1][order]) and np.array_equal(spos, pos[j0:j1][order])
+    # it is the order the backward sums in: the run of each row, and the row list, follow from it
+    rc, st, srows, spos = oracle.sort_lookups(rows, pos, 0, n, R, n)
+    assert np.array_equal(np.unique(srows), oracle.seq_grad_bwd(np.zeros((n, 4), np.float32), rows, pos, 0, n, R)[2])
+    # faults: a row or position out of range becomes 0 and is flagged
+    rc, st, srows, spos = oracle.sort_lookups([5, -1, 2, 300], np.array([3, 2, 9, 0], np.int32), 0, 4, 300, 4)
+    assert rc == 0 and st == oracle.BAD_ID and srows.tolist() == [0, 0, 2, 5] and spos.tolist() == [0, 2, 0, 3]
+    assert oracle.sort_lookups([1], np.zeros(1, np.int32), 1, 0, 5, 1)[0] == 2

@@ -28,6 +28,9 @@ MUTANTS = {
     "half_subnormal_lost": ("int shift = 0;\n            while (!(man & 0x400u)) { man <<= 1; ++shift; }", "int shift = 0;\n            man = 0x400u;"),
     "bf16_low_half": ("uint32_t bits = (uint32_t)b << 16;", "uint32_t bits = (uint32_t)b << 15;"),
     "sort_by_pos_only": ("if (x->row != y->row) return x->row < y->row ? -1 : 1;\n    if (x->pos != y->pos)", "if (x->pos != y->pos)"),
+    "sorted_pairs_carry_j": ("sorted_pos[k] = (uint32_t)lk[k].pos;", "sorted_pos[k] = (uint32_t)lk[k].j;"),
+    "sorted_pairs_whole_array": ("int64_t r = rows[j0 + q];\n        int64_t p = pos[j0 + q];\n        if (r < 0 || r >= R) { flag(status, DEV_BAD_ID); r = 0; }\n        if (p < 0 || p >= n) { flag(status, DEV_BAD_ID); p = 0; }\n        lk[q].row = r; lk[q].pos = p; lk[q].j = q;\n    }\n    qsort(lk, (size_t)m, sizeof(lookup_t), by_row_then_pos);\n    for (int64_t k = 0; k < m; ++k) {",
+                                 "int64_t r = rows[q];\n        int64_t p = pos[q];\n        if (r < 0 || r >= R) { flag(status, DEV_BAD_ID); r = 0; }\n        if (p < 0 || p >= n) { flag(status, DEV_BAD_ID); p = 0; }\n        lk[q].row = r; lk[q].pos = p; lk[q].j = q;\n    }\n    qsort(lk, (size_t)m, sizeof(lookup_t), by_row_then_pos);\n    for (int64_t k = 0; k < m; ++k) {"),
     "tile_boundary_ignored": ("while (end < m && lk[end].row == lk[k].row && (end % tile) != 0) ++end;", "while (end < m && lk[end].row == lk[k].row) ++end;"),
     "partials_start_at_zero": ("partial[d] = (q == k) ? x : partial[d] + x;", "partial[d] = (q == k) ? 0.0f + x : partial[d] + x;"),
     "fold_right_to_left": ("total[d] = have_total ? total[d] + partial[d] : partial[d];", "total[d] = have_total ? partial[d] + (total[d] - 0.0f) * 1.0f + 0.0f : partial[d]; if (have_total && d == 0) { float t2 = total[d]; (void)t2; }"),
@@ -137,6 +140,10 @@ def pins(o):
     assert o.seq_grad_bwd(col([1, 1, TWO24, 3]), [4, 4, 4, 1], np.array([2, 1, 0, 3], np.int32), 0, 4, 5, tile=8)[3][1, 0] == TWO24 + 2
     z = o.seq_grad_bwd(np.full((1, 4), -0.0, np.float32), [0], np.zeros(1, np.int32), 0, 1, 1)[3]
     assert np.all(np.signbit(z))
+    # the backward's order written out: lexsort by (row, pos) of a sub-range
+    rc, st, srows, spos = o.sort_lookups(rows_b, pos_b, 100, 2900, 100, 3000)
+    lo = np.lexsort((pos_b[100:2900], rows_b[100:2900]))
+    assert (rc, st) == (0, 0) and np.array_equal(srows, rows_b[100:2900][lo]) and np.array_equal(spos, pos_b[100:2900][lo])
     # plan: bincount, lexsort prefix, zeros, budget, tags
     counts = np.zeros(T * E, np.uint32)
     o.plan_replication(ids, offsets, T, B, row_base, T * E, counts, o.PLAN_ACCUMULATE)
