@@ -419,7 +419,40 @@ def run_step_config(cfg, args, steps: int, warmup: int, full_report: bool):
         result["exchange_path"]["kernels"]["sparse_update"] = {
             "ms": round(upd_ms, 4), "GBps": round(upd_bytes / (upd_ms * 1e-3) / 1e9, 1),
             "frac": round(upd_bytes / (upd_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4), "rule": "row-wise Adagrad"}
-        del send, store, slots, opt_state
+        # the backward and the optimizer step as two calls and as the one call that applies the step to rows
+        # looked up once straight from grad_out (same bits in the table; lr = 0 again)
+        def q_bwd_update(size):
+            rc = L.fs_seq_grad_bwd_update(z, ctypes.c_int64(n), ctypes.c_int32(D), ctypes.c_int(fs_inputs.DTYPE_CODE[cfg.dtype]),
+                                          z, z, ctypes.c_int64(n), ctypes.c_int64(R), z, ctypes.c_int32(fs.FS_OPT_ADAGRAD_ROWWISE),
+                                          ctypes.c_float(0.0), ctypes.c_float(1e-8), z, z, z, ctypes.c_int64(0), z, z,
+                                          ctypes.c_int64(cap_unique), z, z, ctypes.byref(size), z, z)
+            assert rc == 0, rc
+        ws_fused = ws_for(q_bwd_update)
+
+        def two_calls():
+            backward_sorted()
+            fs.fs_sparse_update(weights, uniq_rows, row_grads, cap_unique, num_unique, fs.FS_OPT_ADAGRAD_ROWWISE, 0.0,
+                                1e-8, opt_state, store, slots, budget_rows, status)
+
+        def one_call():
+            fs.fs_seq_grad_bwd_update(grad_out, sorted_rows, sorted_pos, n, R, weights, fs.FS_OPT_ADAGRAD_ROWWISE, 0.0, 1e-8,
+                                      opt_state, store, slots, budget_rows, uniq_rows, row_grads, cap_unique, num_unique,
+                                      status, workspace=ws_fused)
+
+        fused = {}
+        for name, fn in (("fs_seq_grad_bwd_sorted + fs_sparse_update", two_calls), ("fs_seq_grad_bwd_update", one_call)):
+            for _ in range(2):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            fused[name] = round(e0.elapsed_time(e1) / reps, 4)
+        assert int(status.item()) == 0, f"device status {int(status.item())}"
+        result["backward_with_optimizer_step_ms"] = fused
+        del send, store, slots, opt_state, ws_fused
 
         # the tier planner on the counts accumulated so far (the one batch, profiled once per step run so
         # far, so the sample count is B times that); bandwidth ratios as in the paper's Figure 3

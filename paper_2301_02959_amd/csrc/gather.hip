@@ -26,11 +26,8 @@ constexpr int kGatherRowsPerBlock = kGatherRowsPerWave * kWavesPerBlock;
 template <int LG>
 struct GatherShape {
     static constexpr int RPI = kWave / LG;                                   // rows per instruction
-#ifdef FS_EXP_GATHER_UNR16
-    static constexpr int UNR = RPI >= 8 ? kWave / RPI : (LG == 16 ? FS_EXP_GATHER_UNR16 : 16);
-#else
-    static constexpr int UNR = RPI >= 8 ? kWave / RPI : (LG == 16 ? 8 : 16); // instructions in flight
-#endif
+    static constexpr int UNR = RPI >= 8 ? kWave / RPI : (LG == 16 ? 8 : 16); // instructions in flight (256-byte rows with 16:
+                                                                             // 9 % slower on 4 M lookups, 5 % faster on 8 M)
 };
 
 // Moves the wave's 64 rows.  GUARD = false: every lookup of the wave is valid, loads and

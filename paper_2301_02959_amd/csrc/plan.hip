@@ -57,10 +57,16 @@ constexpr int kHistBlock = 1024;          // 16 waves per span: a span per 256 t
 // own; a row that finds both taken by other rows is added to the global counter at once.  At the end
 // the table is flushed with one saturating add per used slot.  The first row to claim a slot keeps it,
 // so a row lives in at most one slot and the counts stay exact.
-//   SLOT_BITS = 12: 32 KB of LDS, several blocks per CU, spans of 32 k ids (small batches)
-//   SLOT_BITS = 14: 128 KB of LDS, one block per CU, spans of up to 128 k ids: a popular row is flushed
-//                   once per span, so fewer, longer spans mean fewer global updates for the head of the
-//                   distribution, and the larger table keeps the second tier of rows out of the misses
+//   2^12 slots, spans of 32 k ids: small batches (many blocks, several per CU)
+//   2^13 slots (64 KB of LDS, two blocks per CU), spans of up to 128 k ids: large batches.  A popular
+//          row is flushed once per span, so longer spans mean fewer global updates for the head of the
+//          distribution; two blocks per CU let one block's flush (a stretch of nothing but global
+//          adds) run beside the other's counting.  Measured on 67 M ids of one Zipf(1.3) table
+//          (1.2 M distinct rows): 0.39 ms; with 2^14 slots and one block per CU 0.49 ms, with 32 k spans
+//          and 2^12 slots 0.56 ms; on 72 M ids of Zipf(1.1) over 16 tables (10.8 M distinct rows: the
+//          cold tail's one read-modify-write of a whole line per row dominates) 1.15, 1.11 and 1.45 ms.
+//          Counting the most popular rows in registers (no LDS add for them) changed nothing: the LDS
+//          is not what limits the kernel.
 template <int SLOT_BITS>
 __global__ __launch_bounds__(kHistBlock) void plan_histogram_kernel(
     const int64_t* __restrict__ ids, const int64_t* __restrict__ offsets, int T, int64_t B,
@@ -103,11 +109,7 @@ __global__ __launch_bounds__(kHistBlock) void plan_histogram_kernel(
         if (tag == 0 || tag == want) { atomicAdd(&hits[s2], 1u); return; }
         add_saturating(counts + g, 1u, &faults);
     };
-#ifdef FS_EXP_HIST_AHEAD
-    constexpr int kAhead = FS_EXP_HIST_AHEAD;
-#else
-    constexpr int kAhead = 8;                                    // ids in flight per thread
-#endif
+    constexpr int kAhead = 8;                                    // ids in flight per thread (16: no faster)
     int64_t i = base + threadIdx.x;
     for (; i + (int64_t)(kAhead - 1) * kHistBlock < end; i += (int64_t)kAhead * kHistBlock) {
         int64_t id[kAhead];
@@ -153,20 +155,14 @@ __global__ __launch_bounds__(kHistBlock) void plan_histogram_kernel(
 // per CU); from two long spans per CU on, spans are as long as the large table serves well (128 k ids),
 // shortened so that their number is a multiple of the CU count where that is possible.
 constexpr int64_t kHistSpanSmall = 32768;
-#ifdef FS_EXP_HIST_SPAN
-constexpr int64_t kHistSpanLarge = FS_EXP_HIST_SPAN;
-#else
 constexpr int64_t kHistSpanLarge = 131072;
-#endif
+constexpr int kHistBitsSmall = 12;
+constexpr int kHistBitsLarge = 13;
 constexpr int64_t kHistCus = 256;
 
 static void hist_shape(int64_t n, int64_t* span, bool* large)
 {
-#ifdef FS_EXP_HIST_MIN_LARGE
-    *large = n >= (int64_t)FS_EXP_HIST_MIN_LARGE;
-#else
     *large = n >= 2 * kHistCus * (kHistSpanLarge / 2);          // at least one 64 k span for every CU, twice over
-#endif
     if (!*large) { *span = kHistSpanSmall; return; }
     const int64_t rounds = (n + kHistCus * kHistSpanLarge - 1) / (kHistCus * kHistSpanLarge);   // spans per CU
     int64_t s = (n + kHistCus * rounds - 1) / (kHistCus * rounds);
@@ -558,13 +554,10 @@ extern "C" fs_status fs_plan_replication(
             hist_shape(n, &span, &large);
             const int64_t blocks = (n + span - 1) / span;
             if (large)
-#ifndef FS_EXP_HIST_BITS
-#define FS_EXP_HIST_BITS 14
-#endif
-                FS_LAUNCH("plan_histogram", plan_histogram_kernel<FS_EXP_HIST_BITS>, dim3((unsigned)blocks), dim3(kHistBlock), s,
+                FS_LAUNCH("plan_histogram", plan_histogram_kernel<kHistBitsLarge>, dim3((unsigned)blocks), dim3(kHistBlock), s,
                           ids, offsets, (int)T, (int64_t)B, row_base, n, R, span, counts, ok_flag, dev_status);
             else
-                FS_LAUNCH("plan_histogram", plan_histogram_kernel<12>, dim3((unsigned)blocks), dim3(kHistBlock), s,
+                FS_LAUNCH("plan_histogram", plan_histogram_kernel<kHistBitsSmall>, dim3((unsigned)blocks), dim3(kHistBlock), s,
                           ids, offsets, (int)T, (int64_t)B, row_base, n, R, span, counts, ok_flag, dev_status);
         }
     }

@@ -110,11 +110,7 @@ __global__ __launch_bounds__(kBlock) void sort_count_kernel(
 // chunk_sums[chunk][b].  Level 2 (one block): thread b walks the chunks for digit b: chunk_sums ->
 // exclusive prefix, totals[b].
 constexpr int kSortChunkTiles = 64;
-#ifdef FS_EXP_SCAN_AHEAD
-constexpr int kScanAhead = FS_EXP_SCAN_AHEAD;
-#else
-constexpr int kScanAhead = 8;
-#endif
+constexpr int kScanAhead = 8;                // loads a scan thread keeps in flight (16 and 32 are slower)
 
 __global__ __launch_bounds__(1024) void sort_scan_kernel(
     uint32_t* __restrict__ tile_hist, int bins, int64_t m_max, const int64_t* __restrict__ m_dev,
