@@ -46,6 +46,9 @@ def parse():
     ap.add_argument("--overlap-plan", action="store_true",
                     help="run the plan on a second stream beside the lookup path (1-2 %% faster per step, but the "
                          "gather then shares the chip and its own duration grows)")
+    ap.add_argument("--gather-order", default="auto", choices=("auto", "bucket", "row"),
+                    help="order in which the forward gather takes the lookups: as routed, as sorted, or whichever is "
+                         "faster on this workload (timed once before the warm-up)")
     ap.add_argument("--no-exchange", action="store_true", help="skip the untimed send / unbucketize / replica-store report")
     ap.add_argument("--no-also", action="store_true", help="skip c4 and the c5 planning pass of the default run")
     ap.add_argument("--cpu-tables", type=int, default=0, help="tables in the oracle's sample (0 = automatic)")
@@ -194,6 +197,26 @@ def run_step_config(cfg, args, steps: int, warmup: int, full_report: bool):
     def gather_sorted():                                 # the gather in row order (not in the step)
         fs.fs_seq_gather_fwd_sorted(weights, sorted_rows, sorted_pos, n, out, status)
 
+    # The forward gather may take the lookups in bucket order (as routed) or in row order (as sorted for the
+    # backward).  Which is faster depends on the workload (whether the repeated rows fit the caches in bucket
+    # order), so both are timed once, before the warm-up, and the step uses the faster one.
+    gather_order = "bucket"
+    fwd = gather
+    if args.gather_order != "bucket":
+        route(); sort_lookups()
+        t_order = {}
+        for name, fn in (("bucket", gather), ("row", gather_sorted)):
+            fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(3):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            t_order[name] = e0.elapsed_time(e1) / 3
+        if args.gather_order == "row" or (args.gather_order == "auto" and t_order["row"] < 0.98 * t_order["bucket"]):
+            gather_order, fwd = "row", gather_sorted
+
     def step():
         plan_calls[0] += 1
         if plan_stream is not main_stream:
@@ -204,7 +227,7 @@ def run_step_config(cfg, args, steps: int, warmup: int, full_report: bool):
             plan()                                       # on whatever stream is current (a graph capture's, too)
         route()
         sort_lookups()
-        gather()
+        fwd()
         backward_sorted()
         if plan_stream is not main_stream:
             main_stream.wait_stream(plan_stream)
@@ -216,7 +239,8 @@ def run_step_config(cfg, args, steps: int, warmup: int, full_report: bool):
     # ---------------------------------------------------------------- timed region
     # HIP events bracket only the three bandwidth kernels the roofline is about (two event records per
     # timed launch are not free: with all launches of a step timed, the step is 4 % slower).
-    roof_kernels = "gather_rows,bwd_segreduce,bwd_singletons"
+    gather_kernel = "gather_rows" if gather_order == "bucket" else "gather_sorted"
+    roof_kernels = f"{gather_kernel},bwd_segreduce,bwd_singletons"
     records_per_step = 64
     if args.graph:
         # one step captured, replayed K times; HIP events recorded under capture do not yield times, so the
@@ -285,7 +309,7 @@ def run_step_config(cfg, args, steps: int, warmup: int, full_report: bool):
     stage_ms = {
         "plan": sum(v for k, v in kernel_ms.items() if k.startswith("plan_")),
         "route": sum(v for k, v in kernel_ms.items() if k.startswith("route_")),
-        "gather": kernel_ms.get("gather_rows", 0.0),
+        "gather": kernel_ms.get(gather_kernel, 0.0),
         "bwd": sum(v for k, v in kernel_ms.items() if k.startswith("bwd_")),
         "sort": sum(v for k, v in kernel_ms.items() if k.startswith("sort_")),
     }
@@ -298,7 +322,7 @@ def run_step_config(cfg, args, steps: int, warmup: int, full_report: bool):
     del run_len
     k_sel = int(num_selected.item())
     alg = {
-        "gather_rows": n * row_bytes + n_u * row_bytes + n * 12,                # write out, read each distinct row once, indices
+        gather_kernel: n * row_bytes + n_u * row_bytes + n * (12 if gather_order == "bucket" else 8),   # write out, read each distinct row once, indices
         "bwd_segreduce": (n - n_1) * row_bytes + (n_u - n_1) * D * 4 + n * 8,   # read grad_out once, write row_grads, sorted pairs
         "bwd_singletons": n_1 * row_bytes + n_1 * D * 4 + n * 4,                # one row in, one fp32 row out, the sorted keys
     }
@@ -327,7 +351,7 @@ def run_step_config(cfg, args, steps: int, warmup: int, full_report: bool):
                          "traffic": traffic_from_profiles(f"{cfg.name}:{k}")[0]}
                         for k in alg if k != dominant and k in kernel_avg]
     roofline["calls"] = {name: frac_of_peak(alg_calls[name], call_ms[name]) for name in call_names}
-    for name in ("fs_seq_grad_bwd", "fs_seq_gather_fwd_sorted"):
+    for name in ("fs_seq_grad_bwd", "fs_seq_gather_fwd_sorted" if gather_order == "bucket" else "fs_seq_gather_fwd"):
         roofline["calls"][name]["in_step"] = False       # timed beside the step's calls, for comparison
 
     result = {
@@ -336,6 +360,7 @@ def run_step_config(cfg, args, steps: int, warmup: int, full_report: bool):
         "config": {"workload": f"{cfg.name}: {T} tables x {cfg.E} rows x D={D} {cfg.dtype}, batch {B}, "
                                f"{cfg.length_law} lengths, Zipf({cfg.alpha}), {U} buckets (W={W})",
                    "lookups": n, "distinct_rows": n_u, "single_lookup_rows": n_1, "bwd_variant": args.variant,
+                   "gather_order": gather_order,
                    "schedule": ("plan on a second stream beside route, gather, backward" if args.overlap_plan else "one stream")
                                + (", replayed from a HIP graph" if args.graph else ""),
                    "tier_counts": [int(x) for x in tier_counts.tolist()], "scale_rows": args.scale_rows},
@@ -368,6 +393,27 @@ def run_step_config(cfg, args, steps: int, warmup: int, full_report: bool):
         copy_ms = e0.elapsed_time(e1) / 5
         result["plain_copy"] = {"bytes_each_way": copy_bytes, "ms": round(copy_ms, 4),
                                 "GBps_read_plus_write": round(2 * copy_bytes / (copy_ms * 1e-3) / 1e9, 1)}
+
+    # the same for the backward's traffic shape: a read stream of 512-byte pieces with one 1 KB write per
+    # run of the batch's average length (and with no writes at all), without any of the kernel's arithmetic
+    if copy_bytes > 0 and cap_unique > 0:
+        src_bytes = grad_out.numel() * grad_out.element_size() // 512 * 512
+        avg_run = max(1, min(256, int(round((n - n_1) / max(n_u - n_1, 1)))))
+        mix = {}
+        for label, w in (("read_only", 0), ("read_with_writes", avg_run)):
+            for _ in range(2):
+                fs.fs_util_read_write_mix(grad_out.view(-1)[:src_bytes // grad_out.element_size()], w, row_grads if w else None)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(5):
+                fs.fs_util_read_write_mix(grad_out.view(-1)[:src_bytes // grad_out.element_size()], w, row_grads if w else None)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / 5
+            moved = src_bytes + (src_bytes // 512 // w * 1024 if w else 0)
+            mix[label] = {"ms": round(ms, 4), "GBps": round(moved / (ms * 1e-3) / 1e9, 1),
+                          **({"pieces_per_write": w, "write_share": round(1 - src_bytes / moved, 4)} if w else {})}
+        result["reference_streams"] = mix
 
     # ---------------------------------------------------------------- the exchange halves and the replica store
     # Not part of the step or of `value`: the same lookups once more through fs_seq_gather_send +

@@ -563,6 +563,17 @@ int32_t fs_bwd_tile(void);
 fs_status fs_util_copy(void* dst, const void* src, int64_t bytes, void* stream);
 
 /*
+ * Reference stream for the backward's traffic shape (not part of the method; the benchmark prints
+ * its rate beside the kernels'): src is read once in 512-byte pieces by groups that each walk 256
+ * consecutive pieces; with pieces_per_write = w > 0 a group writes its running 32-bit-integer sum
+ * of the pieces so far as one 1 KB row of dst after every w pieces (16 columns of 32 bits repeated
+ * over the row; group g's rows start at row g * ceil(256 / w), wrapping around dst).  w = 0 only
+ * reads.  src_bytes a multiple of 512, dst_bytes of 1024, both 16-byte aligned (FS_ERR_ALIGN).
+ */
+fs_status fs_util_read_write_mix(const void* src, int64_t src_bytes, int32_t pieces_per_write,
+                                 void* dst, int64_t dst_bytes, void* stream);
+
+/*
  * Opt-in per-kernel timing.  fs_prof_begin(max_records) makes every later
  * kernel launch of this library (on any stream) bracketed by a pair of HIP
  * events; fs_prof_end() synchronises those events, writes up to `cap` records

@@ -34,7 +34,7 @@ STATUS_NAMES = {0: "FS_OK", 1: "FS_ERR_NULL", 2: "FS_ERR_SIZE", 3: "FS_ERR_DTYPE
 EXPORTS = ["fs_route_bucketize", "fs_route_bucketize_noalloc", "fs_seq_gather_fwd", "fs_seq_grad_bwd", "fs_plan_replication",
            "fs_sort_lookups", "fs_seq_grad_bwd_sorted", "fs_seq_gather_fwd_sorted", "fs_seq_grad_bwd_update",
            "fs_seq_gather_send", "fs_seq_unbucketize", "fs_replica_build", "fs_seq_gather_fwd_replica", "fs_plan_tiers",
-           "fs_cost_model", "fs_tier_traffic", "fs_sparse_update", "fs_util_copy", "fs_version", "fs_bwd_tile", "fs_prof_begin", "fs_prof_only", "fs_prof_end"]
+           "fs_cost_model", "fs_tier_traffic", "fs_sparse_update", "fs_util_copy", "fs_util_read_write_mix", "fs_version", "fs_bwd_tile", "fs_prof_begin", "fs_prof_only", "fs_prof_end"]
 
 _DTYPES = {torch.float32: FS_F32, torch.float16: FS_F16, torch.bfloat16: FS_BF16}
 
@@ -60,7 +60,7 @@ def lib() -> ctypes.CDLL:
                      "fs_route_bucketize", "fs_route_bucketize_noalloc", "fs_seq_gather_fwd", "fs_seq_grad_bwd", "fs_plan_replication",
                      "fs_seq_gather_send", "fs_seq_unbucketize", "fs_replica_build",
                      "fs_seq_gather_fwd_replica", "fs_plan_tiers", "fs_cost_model", "fs_tier_traffic", "fs_sparse_update", "fs_prof_begin", "fs_prof_only",
-                     "fs_util_copy"):
+                     "fs_util_copy", "fs_util_read_write_mix"):
             getattr(_lib, name).restype = ctypes.c_int
         _lib.fs_version.restype = ctypes.c_int32
         _lib.fs_bwd_tile.restype = ctypes.c_int32
@@ -413,6 +413,13 @@ def fs_util_copy(dst, src, nbytes: Optional[int] = None, raise_on_error: bool = 
     nbytes = src.numel() * src.element_size() if nbytes is None else nbytes
     code = lib().fs_util_copy(_ptr(dst), _ptr(src), ctypes.c_int64(nbytes), _stream())
     return _check("fs_util_copy", code, raise_on_error)
+
+
+def fs_util_read_write_mix(src, pieces_per_write: int, dst=None, raise_on_error: bool = True) -> int:
+    code = lib().fs_util_read_write_mix(_ptr(src), ctypes.c_int64(src.numel() * src.element_size()),
+                                        ctypes.c_int32(pieces_per_write), _ptr(dst),
+                                        ctypes.c_int64(0 if dst is None else dst.numel() * dst.element_size()), _stream())
+    return _check("fs_util_read_write_mix", code, raise_on_error)
 
 
 def fs_version() -> int:

@@ -50,3 +50,20 @@ def test_timing_hooks_select_kernels():
     assert fs.fs_prof_end(16) == []
     torch.cuda.synchronize()
     assert torch.equal(out, W[:50])
+
+
+def test_read_write_mix_reference_stream():
+    """The reference stream writes each group's running sum after every w pieces, in bounds and in order."""
+    import paper_2301_02959_amd as fs
+    dev = "cuda:0"
+    pieces, w = 700, 64                                  # groups of 256, 256 and 188 pieces
+    src = torch.ones(pieces * 128, dtype=torch.int32, device=dev)
+    dst = torch.full((12 * 256,), -1, dtype=torch.int32, device=dev)
+    fs.fs_util_read_write_mix(src, w, dst)
+    fs.fs_util_read_write_mix(src, 0, None)              # reads only
+    torch.cuda.synchronize()
+    rows = dst.view(12, 256).cpu()
+    want = [64, 128, 192, 256, 64, 128, 192, 256, 64, 128, -1, -1]
+    assert all(bool((rows[r] == want[r]).all()) for r in range(12))
+    assert fs.fs_util_read_write_mix(src[:100], w, dst, raise_on_error=False) == 4       # not whole pieces
+    assert fs.fs_util_read_write_mix(src, w, None, raise_on_error=False) == 1
