@@ -396,21 +396,24 @@ def run_step_config(cfg, args, steps: int, warmup: int, full_report: bool):
 
     # the same for the backward's traffic shape: a read stream of 512-byte pieces with one 1 KB write per
     # run of the batch's average length (and with no writes at all), without any of the kernel's arithmetic
-    if copy_bytes > 0 and cap_unique > 0:
-        src_bytes = grad_out.numel() * grad_out.element_size() // 512 * 512
+    src_bytes = grad_out.numel() * grad_out.element_size() // 512 * 512
+    dst_elems = row_grads.numel() // 256 * 256                       # whole 1 KB rows of the fp32 buffer
+    if src_bytes > 0 and dst_elems > 0:
         avg_run = max(1, min(256, int(round((n - n_1) / max(n_u - n_1, 1)))))
         mix = {}
+        mix_src = grad_out.view(-1)[:src_bytes // grad_out.element_size()]
+        mix_dst = row_grads.view(-1)[:dst_elems]
         for label, w in (("read_only", 0), ("read_with_writes", avg_run)):
             for _ in range(2):
-                fs.fs_util_read_write_mix(grad_out.view(-1)[:src_bytes // grad_out.element_size()], w, row_grads if w else None)
+                fs.fs_util_read_write_mix(mix_src, w, mix_dst if w else None)
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
             for _ in range(5):
-                fs.fs_util_read_write_mix(grad_out.view(-1)[:src_bytes // grad_out.element_size()], w, row_grads if w else None)
+                fs.fs_util_read_write_mix(mix_src, w, mix_dst if w else None)
             e1.record()
             torch.cuda.synchronize()
             ms = e0.elapsed_time(e1) / 5
-            moved = src_bytes + (src_bytes // 512 // w * 1024 if w else 0)
+            moved = src_bytes + (src_bytes // 512 // 256 * (256 // w) * 1024 if w else 0)   # a group of 256 pieces writes 256 // w rows
             mix[label] = {"ms": round(ms, 4), "GBps": round(moved / (ms * 1e-3) / 1e9, 1),
                           **({"pieces_per_write": w, "write_share": round(1 - src_bytes / moved, 4)} if w else {})}
         result["reference_streams"] = mix

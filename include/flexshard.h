@@ -89,6 +89,8 @@ enum {
  * summation order (see fs_seq_grad_bwd). */
 #define FS_BWD_TILE 256
 
+/* Most owner buckets a call admits.  The router's scatter keeps 12 bytes of LDS per bucket and
+ * workgroup (an output base, and a running count per wave): 48 KB at 4096 buckets; the CU has 160 KB. */
 #define FS_MAX_BUCKETS 4096
 
 /*

@@ -4,8 +4,9 @@
 //   sort_count    per-tile digit histogram (one LDS add per distinct digit per wave, found by
 //                 ballot matching), stored tile-major
 //   sort_scan     exclusive scan of every digit's per-tile counts over the tiles (two levels,
-//                 coalesced across digits), and the digits' totals; the block that finishes its
-//                 chunk of tiles last (a counter, no waiting) runs the second level
+//                 coalesced across digits), and the digits' totals; for small sorts the block that
+//                 finishes its chunk of tiles last (a counter, no waiting) runs the second level,
+//                 for large ones the second level is a launch of its own (sort_scan_chunks)
 //   sort_scatter  each wave ranks its 1024 consecutive pairs against a wave-private running
 //                 histogram in LDS (ballot matching keeps equal digits in order); the tile is put
 //                 in digit order in LDS, then written out so that consecutive lanes write
@@ -110,11 +111,13 @@ __global__ __launch_bounds__(kBlock) void sort_count_kernel(
 // chunk_sums[chunk][b].  Level 2 (one block): thread b walks the chunks for digit b: chunk_sums ->
 // exclusive prefix, totals[b].
 constexpr int kSortChunkTiles = 64;
+constexpr int kSortFusedScanChunks = 16;     // up to this many chunks (4 M pairs) the scan's second level runs inside its first launch
+constexpr int kSortFusedScanChunksDev = 1024;
 constexpr int kScanAhead = 8;                // loads a scan thread keeps in flight (16 and 32 are slower)
 
 __global__ __launch_bounds__(1024) void sort_scan_kernel(
     uint32_t* __restrict__ tile_hist, int bins, int64_t m_max, const int64_t* __restrict__ m_dev,
-    uint32_t* __restrict__ chunk_sums, uint32_t* __restrict__ totals, uint32_t* __restrict__ scan_done)
+    uint32_t* __restrict__ chunk_sums, uint32_t* __restrict__ totals, uint32_t* __restrict__ scan_done, int fused)
 {
     __shared__ bool is_last;
     const int64_t m = sort_count_of(m_dev, m_max);
@@ -136,6 +139,7 @@ __global__ __launch_bounds__(1024) void sort_scan_kernel(
         for (; t < t1; ++t) { const uint32_t v = tile_hist[t * bins + b]; tile_hist[t * bins + b] = run; run += v; }
         chunk_sums[(int64_t)blockIdx.x * bins + b] = run;
     }
+    if (!fused) return;                                          // block-uniform: level 2 is a launch of its own
     // Level 2 needs every block's chunk sums.  Each block publishes its own (fence), then takes a ticket;
     // the block that draws the last ticket sees all of them (fence) and runs the second level.  Nobody waits.
     __threadfence();
@@ -157,6 +161,31 @@ __global__ __launch_bounds__(1024) void sort_scan_kernel(
         for (; c < chunks; ++c) { const uint32_t v = chunk_sums[c * bins + b]; chunk_sums[c * bins + b] = run; run += v; }
         totals[b] = run;
     }
+}
+
+// Level 2 as a launch of its own, for sorts with many chunks: there the one workgroup that would run it
+// inside sort_scan_kernel reads every other workgroup's sums from memory, alone on the chip, and takes
+// longer than a launch costs (72 M pairs, 275 chunks: 230 µs against 11 µs).
+__global__ __launch_bounds__(kBlock) void sort_scan_chunks_kernel(
+    uint32_t* __restrict__ chunk_sums, int bins, int64_t m_max, const int64_t* __restrict__ m_dev,
+    uint32_t* __restrict__ totals)
+{
+    const int64_t m = sort_count_of(m_dev, m_max);
+    const int64_t used = (m + kSortTile - 1) / kSortTile;
+    const int64_t chunks = (used + kSortChunkTiles - 1) / kSortChunkTiles;
+    const int b = blockIdx.x * kBlock + threadIdx.x;
+    if (b >= bins) return;
+    uint32_t run = 0;
+    int64_t c = 0;
+    for (; c + kScanAhead <= chunks; c += kScanAhead) {
+        uint32_t v[kScanAhead];
+#pragma unroll
+        for (int q = 0; q < kScanAhead; ++q) v[q] = chunk_sums[(c + q) * bins + b];
+#pragma unroll
+        for (int q = 0; q < kScanAhead; ++q) { chunk_sums[(c + q) * bins + b] = run; run += v[q]; }
+    }
+    for (; c < chunks; ++c) { const uint32_t v = chunk_sums[c * bins + b]; chunk_sums[c * bins + b] = run; run += v; }
+    totals[b] = run;
 }
 
 template <typename Reader, int NBITS>
@@ -329,6 +358,10 @@ fs_status radix_sort_pairs(uint32_t* keys_a, uint32_t* vals_a, uint32_t* keys_b,
     const int64_t padded_tiles = xcd_striped_grid(tiles, kSortStripe);       // a multiple of 8
     const unsigned grid = (unsigned)(padded_tiles < kSortMaxGrid ? padded_tiles : kSortMaxGrid);
     const int passes = radix_sort_passes(key_bits);
+    // The second scan level runs inside the first level's launch for small sorts.  When the pair count lives on
+    // the device (the plan's candidates: a few per cent of the rows the buffers are sized for), "small" cannot be
+    // known here; the launch is then fused up to a size at which the lone workgroup costs at most a tenth of a pass.
+    const bool fused_scan = chunks <= kSortFusedScanChunks || (m_dev != nullptr && chunks <= kSortFusedScanChunksDev);
     int shift = 0;
     const bool from_rows = src.rows != nullptr;
     // from_rows: source -> A -> B -> A ...; else A -> B -> A ...
@@ -348,7 +381,10 @@ fs_status radix_sort_pairs(uint32_t* keys_a, uint32_t* vals_a, uint32_t* keys_b,
             FS_DISPATCH_BITS(nbits, FS_COUNT_ROWS)
 #undef FS_COUNT_ROWS
             FS_LAUNCH("sort_scan", sort_scan_kernel, dim3((unsigned)chunks), dim3(scan_threads), stream,
-                      tile_hist, 1 << nbits, m_max, m_dev, chunk_sums, totals, scan_done);
+                      tile_hist, 1 << nbits, m_max, m_dev, chunk_sums, totals, scan_done, fused_scan ? 1 : 0);
+            if (!fused_scan)
+                FS_LAUNCH("sort_scan_chunks", sort_scan_chunks_kernel, dim3(((1u << nbits) + kBlock - 1) / kBlock),
+                          dim3(kBlock), stream, chunk_sums, 1 << nbits, m_max, m_dev, totals);
 #define FS_SCATTER_ROWS(NB)                                                                                   \
     FS_LAUNCH("sort_scatter", (sort_scatter_kernel<RowPosReader, NB>), dim3(grid), dim3(kBlock), stream, in, m_max, \
               m_dev, shift, tile_hist, chunk_sums, totals, dst_k, dst_v, src.status)
@@ -362,7 +398,10 @@ fs_status radix_sort_pairs(uint32_t* keys_a, uint32_t* vals_a, uint32_t* keys_b,
             FS_DISPATCH_BITS(nbits, FS_COUNT_PAIRS)
 #undef FS_COUNT_PAIRS
             FS_LAUNCH("sort_scan", sort_scan_kernel, dim3((unsigned)chunks), dim3(scan_threads), stream,
-                      tile_hist, 1 << nbits, m_max, m_dev, chunk_sums, totals, scan_done);
+                      tile_hist, 1 << nbits, m_max, m_dev, chunk_sums, totals, scan_done, fused_scan ? 1 : 0);
+            if (!fused_scan)
+                FS_LAUNCH("sort_scan_chunks", sort_scan_chunks_kernel, dim3(((1u << nbits) + kBlock - 1) / kBlock),
+                          dim3(kBlock), stream, chunk_sums, 1 << nbits, m_max, m_dev, totals);
 #define FS_SCATTER_PAIRS(NB)                                                                                  \
     FS_LAUNCH("sort_scatter", (sort_scatter_kernel<PairReader, NB>), dim3(grid), dim3(kBlock), stream, in, m_max,   \
               m_dev, shift, tile_hist, chunk_sums, totals, dst_k, dst_v, (int32_t*)nullptr)
