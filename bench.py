@@ -51,6 +51,8 @@ def parse():
                          "faster on this workload (timed once before the warm-up)")
     ap.add_argument("--no-exchange", action="store_true", help="skip the untimed send / unbucketize / replica-store report")
     ap.add_argument("--no-also", action="store_true", help="skip c4 and the c5 planning pass of the default run")
+    ap.add_argument("--c5-chunk", type=int, default=0,
+                    help="ids per fs_plan_replication call of the c5 planning pass (0 = the whole sample in one call)")
     ap.add_argument("--cpu-tables", type=int, default=0, help="tables in the oracle's sample (0 = automatic)")
     ap.add_argument("--scale-rows", type=int, default=1, help="divide E by this (debugging only; reported)")
     return ap.parse_args()
@@ -529,9 +531,9 @@ def run_step_config(cfg, args, steps: int, warmup: int, full_report: bool):
 
 def run_c5_planning(args):
     """The planning configuration: 10^9 sampled ids (4 tables x 250 M, one segment per table) through
-    fs_plan_replication's histogram in calls of 2^26 ids, then the top-k under a 4 GB budget at 256 bytes
-    per row.  Ids are drawn on the GPU chunk by chunk (never resident as a whole); each call is timed with
-    HIP events on its stream while its chunk is resident."""
+    fs_plan_replication's histogram in ONE call (the ids, 8 GB, are drawn on the GPU and resident when the
+    timed region starts), then the top-k under a 4 GB budget at 256 bytes per row.  The call is timed with
+    HIP events on its stream; `--c5-chunk N` splits the pass into calls of at most N ids instead."""
     import torch
     import fs_inputs
     import paper_2301_02959_amd as fs
@@ -547,7 +549,6 @@ def run_c5_planning(args):
     cap = min(R, budget // bpr)
     sel = torch.zeros(cap, dtype=torch.int64, device=dev)
     nsel = torch.zeros(1, dtype=torch.int64, device=dev)
-    chunk = 1 << 26
 
     def ws_of(flags, n):
         size = ctypes.c_size_t(0)
@@ -558,30 +559,37 @@ def run_c5_planning(args):
         assert rc == 0, rc
         return torch.empty(max(int(size.value), 256), dtype=torch.uint8, device=dev)
 
-    ws_acc = ws_of(fs.FS_PLAN_ACCUMULATE, chunk)
-    ws_sel = ws_of(fs.FS_PLAN_SELECT, 0)
-    hist_ms, seen, calls, first = 0.0, 0, 0, True
     t_wall = time.time()
-    for t, ids in fs_inputs.make_profile_sample(cfg, per_table, dev, chunk=chunk):
-        m = ids.numel()
-        offsets = torch.zeros(T + 1, dtype=torch.int64, device=dev)
-        offsets[t + 1:] = m
-        if first:                                        # untimed: loads the kernels, on counters of its own
-            warm = torch.zeros(R, dtype=torch.int32, device=dev)
-            fs.fs_plan_replication(ids, offsets, T, 1, row_base, m, R, warm, fs.FS_PLAN_ACCUMULATE, dev_status=status,
+    parts = [ids for _, ids in fs_inputs.make_profile_sample(cfg, per_table, dev, chunk=per_table)]
+    all_ids = torch.cat(parts)
+    del parts
+    seen = all_ids.numel()
+    table_start = torch.arange(T + 1, dtype=torch.int64, device=dev) * per_table
+    chunk = args.c5_chunk if args.c5_chunk > 0 else seen
+    # the calls: [lo, hi) of the sample with the offsets of the tables inside it (one segment per table)
+    calls = []
+    for lo in range(0, seen, chunk):
+        hi = min(seen, lo + chunk)
+        calls.append((all_ids[lo:hi], (table_start.clamp(lo, hi) - lo).contiguous(), hi - lo))
+    ws_acc = ws_of(fs.FS_PLAN_ACCUMULATE, max(c[2] for c in calls))
+    ws_sel = ws_of(fs.FS_PLAN_SELECT, 0)
+
+    def accumulate(into):
+        for ids, offsets, m in calls:
+            fs.fs_plan_replication(ids, offsets, T, 1, row_base, m, R, into, fs.FS_PLAN_ACCUMULATE, dev_status=status,
                                    workspace=ws_acc)
-            del warm
-            first = False
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        fs.fs_plan_replication(ids, offsets, T, 1, row_base, m, R, counts, fs.FS_PLAN_ACCUMULATE, dev_status=status,
-                               workspace=ws_acc)
-        e1.record()
-        torch.cuda.synchronize()
-        hist_ms += e0.elapsed_time(e1)
-        seen += m
-        calls += 1
-        del ids
+
+    warm = torch.zeros(R, dtype=torch.int32, device=dev)   # untimed: loads the kernels, on counters of its own
+    accumulate(warm)
+    del warm
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    accumulate(counts)
+    e1.record()
+    torch.cuda.synchronize()
+    hist_ms = e0.elapsed_time(e1)
+    del all_ids
     sel_ms = []
     for _ in range(3):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -601,13 +609,13 @@ def run_c5_planning(args):
     total_ms = hist_ms + min(sel_ms)
     return {
         "config": {"workload": f"c5 planning: {seen} sampled ids over {T} tables x {cfg.E} rows, Zipf({cfg.alpha}), "
-                               f"histogram in {calls} calls of up to 2^26 ids, then top-k under {budget} bytes at {bpr} "
+                               f"histogram in {len(calls)} call(s) of up to {chunk} ids, then top-k under {budget} bytes at {bpr} "
                                f"bytes per row",
                    "ids": seen, "distinct_rows": distinct, "selected": k, "budget_rows": cap},
         "metric": "sampled ids/sec through fs_plan_replication (histogram, then top-k)", "unit": "ids/s",
         "value": round(seen / (total_ms * 1e-3), 1), "ms": round(total_ms, 3),
         "roofline": {"bound": "hbm", "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "calls": {"fs_plan_replication[ACCUMULATE]": {**frac_of_peak(hist_bytes, hist_ms), "launch_calls": calls},
+                     "calls": {"fs_plan_replication[ACCUMULATE]": {**frac_of_peak(hist_bytes, hist_ms), "launch_calls": len(calls)},
                                "fs_plan_replication[SELECT]": frac_of_peak(sel_bytes, min(sel_ms))}},
         "wall_s_with_id_generation": round(time.time() - t_wall, 1),
     }

@@ -67,6 +67,8 @@ constexpr int kHistBlock = 1024;          // 16 waves per span: a span per 256 t
 //          cold tail's one read-modify-write of a whole line per row dominates) 1.15, 1.11 and 1.45 ms.
 //          Counting the most popular rows in registers (no LDS add for them) changed nothing: the LDS
 //          is not what limits the kernel.
+typedef int64_t Id2 __attribute__((ext_vector_type(2)));
+
 template <int SLOT_BITS>
 __global__ __launch_bounds__(kHistBlock) void plan_histogram_kernel(
     const int64_t* __restrict__ ids, const int64_t* __restrict__ offsets, int T, int64_t B,
@@ -87,17 +89,13 @@ __global__ __launch_bounds__(kHistBlock) void plan_histogram_kernel(
         span_tables[1] = plan_table_of(offsets, T, B, end - 1);
     }
     __syncthreads();
-    const int t_lo = span_tables[0];
-    const int t_hi = span_tables[1];
+    const int t_lo = __builtin_amdgcn_readfirstlane(span_tables[0]);
+    const int t_hi = __builtin_amdgcn_readfirstlane(span_tables[1]);
     int32_t faults = 0;
-    auto count_one = [&](int64_t i, int64_t id) {
-        int t = t_lo;
-        while (t < t_hi && offsets[(int64_t)(t + 1) * B] <= i) ++t;
-        const int64_t first = row_base[t];
-        const int64_t rows_t = row_base[t + 1] - first;
-        if (id < 0 || id >= rows_t) { faults |= FS_DEV_BAD_ID; id = 0; }
-        if ((uint64_t)(first + id) >= (uint64_t)R) { faults |= FS_DEV_BAD_ID; return; }   // row_base does not fit R
-        const uint32_t g = (uint32_t)(first + id);
+    // Counts one row in the LDS table.  A row that finds both its slots taken goes to the global counter:
+    // the add is issued here and its old value handed back (`*went` = the row + 1), so that the caller can
+    // look at the answers of a whole batch of ids at once instead of waiting for each on its own.
+    auto count_row = [&](uint32_t g, uint32_t* went, uint32_t* old) {
         const uint32_t want = g + 1u;
         const uint32_t s1 = (g * 2654435761u) >> (32 - SLOT_BITS);
         uint32_t tag = tags[s1];
@@ -107,18 +105,72 @@ __global__ __launch_bounds__(kHistBlock) void plan_histogram_kernel(
         tag = tags[s2];
         if (tag == 0) tag = atomicCAS(&tags[s2], 0u, want);
         if (tag == 0 || tag == want) { atomicAdd(&hits[s2], 1u); return; }
-        add_saturating(counts + g, 1u, &faults);
+        *went = want;
+        *old = atomicAdd(counts + g, 1u);
     };
-    constexpr int kAhead = 8;                                    // ids in flight per thread (16: no faster)
-    int64_t i = base + threadIdx.x;
-    for (; i + (int64_t)(kAhead - 1) * kHistBlock < end; i += (int64_t)kAhead * kHistBlock) {
-        int64_t id[kAhead];
+    auto settle = [&](uint32_t went, uint32_t old) {             // the add wrapped: pin the counter at the maximum
+        if (went != 0 && old == 0xFFFFFFFFu) {
+            atomicExch(counts + (went - 1u), 0xFFFFFFFFu);
+            faults |= FS_DEV_COUNT_OVERFLOW;
+        }
+    };
+    // The span table by table (nearly always one): the table's first row and size are the same for all of
+    // its ids, so the loop over the ids loads nothing but the ids, two to a lane (16 bytes) where the
+    // address allows it.
+    for (int t = t_lo; t <= t_hi; ++t) {
+        int64_t lo = offsets[(int64_t)t * B];
+        int64_t hi = offsets[(int64_t)(t + 1) * B];
+        lo = lo > base ? lo : base;
+        hi = hi < end ? hi : end;
+        if (lo >= hi) continue;
+        const int64_t first = row_base[t];
+        const int64_t rows_t = row_base[t + 1] - first;
+        auto count_one = [&](int64_t id, uint32_t* went, uint32_t* old) {
+            *went = 0;
+            *old = 0;
+            if (id < 0 || id >= rows_t) { faults |= FS_DEV_BAD_ID; id = 0; }
+            if ((uint64_t)(first + id) >= (uint64_t)R) { faults |= FS_DEV_BAD_ID; return; }   // row_base does not fit R
+            count_row((uint32_t)(first + id), went, old);
+        };
+        if ((reinterpret_cast<uintptr_t>(ids + lo) & 15) != 0) {         // an odd first id: on its own
+            if (threadIdx.x == 0) {
+                uint32_t went, old;
+                count_one(load_stream(ids + lo), &went, &old);
+                settle(went, old);
+            }
+            ++lo;
+        }
+        const Id2* pairs = reinterpret_cast<const Id2*>(ids + lo);
+        const int64_t num_pairs = (hi - lo) >> 1;
+        constexpr int kAhead = 4;                                // pairs of ids in flight per thread
+        int64_t p = threadIdx.x;
+        for (; p + (int64_t)(kAhead - 1) * kHistBlock < num_pairs; p += (int64_t)kAhead * kHistBlock) {
+            Id2 id[kAhead];
+            uint32_t went[2 * kAhead], old[2 * kAhead];
 #pragma unroll
-        for (int q = 0; q < kAhead; ++q) id[q] = load_stream(ids + i + (int64_t)q * kHistBlock);
+            for (int q = 0; q < kAhead; ++q) id[q] = load_stream(pairs + p + (int64_t)q * kHistBlock);
 #pragma unroll
-        for (int q = 0; q < kAhead; ++q) count_one(i + (int64_t)q * kHistBlock, id[q]);
+            for (int q = 0; q < kAhead; ++q) {
+                count_one(id[q].x, &went[2 * q], &old[2 * q]);
+                count_one(id[q].y, &went[2 * q + 1], &old[2 * q + 1]);
+            }
+#pragma unroll
+            for (int q = 0; q < 2 * kAhead; ++q) settle(went[q], old[q]);
+        }
+        for (; p < num_pairs; p += kHistBlock) {
+            const Id2 id = load_stream(pairs + p);
+            uint32_t went[2], old[2];
+            count_one(id.x, &went[0], &old[0]);
+            count_one(id.y, &went[1], &old[1]);
+            settle(went[0], old[0]);
+            settle(went[1], old[1]);
+        }
+        if (((hi - lo) & 1) != 0 && threadIdx.x == kHistBlock - 1) {     // an odd last id
+            uint32_t went, old;
+            count_one(load_stream(ids + hi - 1), &went, &old);
+            settle(went, old);
+        }
     }
-    for (; i < end; i += kHistBlock) count_one(i, load_stream(ids + i));
     __syncthreads();
     // The flush: one saturating add per used slot.  A thread's adds are all issued before the first old
     // value is looked at: one after the other, each waiting for its answer, they are the longest stretch
@@ -152,10 +204,18 @@ __global__ __launch_bounds__(kHistBlock) void plan_histogram_kernel(
 }
 
 // Span length and table size for n ids: small batches keep the 32 k spans and the small table (many blocks
-// per CU); from two long spans per CU on, spans are as long as the large table serves well (128 k ids),
-// shortened so that their number is a multiple of the CU count where that is possible.
+// per CU).  From one 64 k span for each of the two blocks a CU holds, the large table, with spans of up to
+// 128 k ids, shortened so that their number is a multiple of the CU count where that is possible.  A popular
+// row is flushed once per span, so a planning pass over very many ids (from 2^27) takes spans of up to 512 k
+// ids, all of one length and a whole number of rounds over the chip's 512 resident blocks: 10^9 ids of
+// Zipf(1.3) in one call take 4.7 ms with 128 k spans, 4.1 ms with 512 k, 10 ms with 2 M.  A training batch of
+// a flatter law (72 M ids of Zipf(1.1) over 16 tables) does better with the shorter spans (1.13 ms at 96 k,
+// 1.25 ms at 144 k): the first rows to arrive keep the slots, and a fresh table serves the rows that repeat
+// within a stretch.
 constexpr int64_t kHistSpanSmall = 32768;
 constexpr int64_t kHistSpanLarge = 131072;
+constexpr int64_t kHistSpanHuge = 524288;
+constexpr int64_t kHistHugeFrom = (int64_t)1 << 27;
 constexpr int kHistBitsSmall = 12;
 constexpr int kHistBitsLarge = 13;
 constexpr int64_t kHistCus = 256;
@@ -164,10 +224,12 @@ static void hist_shape(int64_t n, int64_t* span, bool* large)
 {
     *large = n >= 2 * kHistCus * (kHistSpanLarge / 2);          // at least one 64 k span for every CU, twice over
     if (!*large) { *span = kHistSpanSmall; return; }
-    const int64_t rounds = (n + kHistCus * kHistSpanLarge - 1) / (kHistCus * kHistSpanLarge);   // spans per CU
-    int64_t s = (n + kHistCus * rounds - 1) / (kHistCus * rounds);
+    const int64_t longest = n >= kHistHugeFrom ? kHistSpanHuge : kHistSpanLarge;
+    const int64_t per_round = n >= kHistHugeFrom ? 2 * kHistCus : kHistCus;
+    const int64_t rounds = (n + per_round * longest - 1) / (per_round * longest);
+    int64_t s = (n + per_round * rounds - 1) / (per_round * rounds);
     s = (s + 8191) / 8192 * 8192;                                // whole rounds of 8 ids per thread
-    *span = s < kHistSpanLarge ? s : kHistSpanLarge;
+    *span = s < longest ? s : longest;
 }
 
 // ---- selection --------------------------------------------------------------

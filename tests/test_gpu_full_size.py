@@ -222,12 +222,13 @@ def test_c5_plan_one_billion_ids(G):
     cfg = fs_inputs.CONFIGS["c5"]
     R, T = cfg.R, cfg.T
     per_table = 250_000_000
-    counts = torch.zeros(R, dtype=torch.int32, device=dev)
+    counts = torch.zeros(R, dtype=torch.int32, device=dev)            # in calls of 2^26 ids
     ocounts = np.zeros(R, np.uint32)
     row_base = torch.arange(T + 1, dtype=torch.int64, device=dev) * cfg.E
     rb_h = row_base.cpu().numpy()
     st = torch.zeros(1, dtype=torch.int32, device=dev)
     seen = 0
+    parts = []
     for t, ids in fs_inputs.make_profile_sample(cfg, per_table, dev, chunk=1 << 26):
         m = ids.numel()
         offsets = torch.zeros(T + 1, dtype=torch.int64, device=dev)
@@ -236,6 +237,7 @@ def test_c5_plan_one_billion_ids(G):
         orc, ost, _ = oracle.plan_replication(ids.cpu().numpy(), offsets.cpu().numpy(), T, 1, rb_h, R, ocounts,
                                               oracle.PLAN_ACCUMULATE)
         assert orc == 0 and ost == 0
+        parts.append(ids)
         seen += m
         if (seen // m) % 4 == 0:
             _progress(f"[c5 plan] {seen} ids")
@@ -243,6 +245,15 @@ def test_c5_plan_one_billion_ids(G):
     assert int(st.item()) == 0 and seen == 4 * per_table
     assert np.array_equal(counts.cpu().numpy().view(np.uint32), ocounts)
     assert int(ocounts.astype(np.int64).sum()) == seen
+    # the same sample in ONE call (as bench.py runs the pass: spans of half a million ids, some across two tables)
+    all_ids = torch.cat(parts)
+    del parts
+    one = torch.zeros(R, dtype=torch.int32, device=dev)
+    offsets = torch.arange(T + 1, dtype=torch.int64, device=dev) * per_table
+    fs.fs_plan_replication(all_ids, offsets, T, 1, row_base, seen, R, one, fs.FS_PLAN_ACCUMULATE, dev_status=st)
+    torch.cuda.synchronize()
+    assert int(st.item()) == 0 and torch.equal(one, counts)
+    del all_ids, one
     budget, bpr = 4_000_000_000, 256
     cap = min(R, budget // bpr)
     sel = torch.zeros(cap, dtype=torch.int64, device=dev)

@@ -56,6 +56,42 @@ def test_histogram_matches(G, case):
     assert np.array_equal(hc, oc) and hc.sum() - base.sum() == n
 
 
+@pytest.mark.parametrize("shift,big", [(0, 1_300_001), (1, 1_300_001), (1, 40_000_001)])
+def test_histogram_odd_boundaries_and_unaligned_ids(G, shift, big):
+    """The histogram reads ids two at a time where it can: tables that start and end at odd positions, empty
+    tables between them, an ids array that starts 8 bytes past a 16-byte boundary, a large batch whose spans
+    cross tables, and ids out of range (counted as row 0 of their table, flagged) -- all as the oracle counts."""
+    import paper_2301_02959_amd as fs
+    rng = np.random.default_rng(11 + shift)
+    T, B = 7, 1
+    sizes = np.array([1, 0, 262_145, 3, 0, big, 77_777])                     # one segment per table (40 M: the large table)
+    E = np.array([5, 9, 40_000, 2, 6, 900_000, 123])
+    offsets = np.zeros(T + 1, np.int64)
+    np.cumsum(sizes, out=offsets[1:])
+    row_base = np.zeros(T + 1, np.int64)
+    np.cumsum(E, out=row_base[1:])
+    n, R = int(offsets[-1]), int(row_base[-1])
+    ids = np.concatenate([np.minimum(rng.pareto(1.1, m).astype(np.int64), e - 1) for m, e in zip(sizes, E)])
+    bad = rng.choice(n, 50, replace=False)
+    ids[bad[:25]] = -1 - rng.integers(0, 1000, 25)
+    ids[bad[25:]] = 10 ** 9 + rng.integers(0, 1000, 25)
+    base = rng.integers(0, 3, R).astype(np.uint32)
+    oc = base.copy()
+    orc, ost, _ = oracle.plan_replication(ids, offsets, T, B, row_base, R, oc, A)
+    assert orc == 0 and ost == oracle.BAD_ID
+    buf = torch.zeros(n + 2, dtype=torch.int64, device=G.DEV)
+    ids_d = buf[shift:shift + n]
+    assert ids_d.data_ptr() % 16 == 8 * shift
+    ids_d.copy_(torch.from_numpy(ids))
+    counts = torch.from_numpy(base.view(np.int32).copy()).to(G.DEV)
+    st = torch.zeros(1, dtype=torch.int32, device=G.DEV)
+    rc = fs.fs_plan_replication(ids_d, G.to_dev(offsets, torch.int64), T, B, G.to_dev(row_base, torch.int64), n, R, counts, A,
+                                dev_status=st, raise_on_error=False)
+    torch.cuda.synchronize()
+    assert rc == 0 and int(st.item()) == oracle.BAD_ID
+    assert np.array_equal(counts.cpu().numpy().view(np.uint32), oc)
+
+
 def test_histogram_zipf_profile_and_select(G):
     """c5's laws on a small table: profile, then choose under a budget, tag, and compare everything."""
     cfg = fs_inputs.CONFIGS["c5"].scaled(E=200_000, T=3)

@@ -97,6 +97,25 @@ def test_random_pipeline(G, seed):
         assert (rc, st, nu) == (orc, ost, onu)
         assert np.array_equal(u.cpu().numpy(), ou)
         assert np.array_equal(g.cpu().numpy().view(np.uint32), og.view(np.uint32)), (j0, j1)
+        # the shared sort and the entry points that take its pairs: the oracle's order, then the same bits
+        m = j1 - j0
+        srows = torch.zeros(max(m, 1), dtype=torch.int32, device=G.DEV)
+        spos = torch.zeros(max(m, 1), dtype=torch.int32, device=G.DEV)
+        assert fs.fs_sort_lookups(rows, pos, j0, j1, R, n, srows, spos, st_d) == 0
+        orc, ost, osr, osp = oracle.sort_lookups(orows, opos, j0, j1, R, n)
+        assert (orc, ost) == (0, 0)
+        assert np.array_equal(srows[:m].cpu().numpy().view(np.uint32), osr)
+        assert np.array_equal(spos[:m].cpu().numpy().view(np.uint32), osp)
+        us = torch.full((max(onu, 1),), -7, dtype=torch.int64, device=G.DEV)
+        gs = torch.full((max(onu, 1), D), float("nan"), dtype=torch.float32, device=G.DEV)
+        nus = torch.full((1,), -7, dtype=torch.int64, device=G.DEV)
+        assert fs.fs_seq_grad_bwd_sorted(grad_d, srows, spos, m, R, 0, us, gs, max(onu, 1), nus, st_d) == 0
+        assert int(nus.item()) == onu and np.array_equal(us[:onu].cpu().numpy(), ou)
+        assert np.array_equal(gs[:onu].cpu().numpy().view(np.uint32), og.view(np.uint32)), (j0, j1)
+        out_s = torch.full((n, D), 5.0, dtype=TDT[dt], device=G.DEV)
+        assert fs.fs_seq_gather_fwd_sorted(W_d, srows, spos, m, out_s, st_d) == 0
+        torch.cuda.synchronize()
+        assert np.array_equal(G.bits(out_s), ref.view(np.uint8).reshape(-1)), (j0, j1)
         if onu > 1:
             cap = int(rng.integers(1, onu))
             rc, st, u, g, nu = G.hip_bwd(grad_d, rows, pos, j0, j1, R, 0, cap)
