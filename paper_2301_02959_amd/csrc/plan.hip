@@ -50,32 +50,28 @@ __global__ __launch_bounds__(kBlock) void plan_check_offsets_kernel(
     if (ballot(bad) != 0 && lane_id() == 0) { report(status, FS_DEV_BAD_OFFSETS); atomicExch(ok_flag, 0); }
 }
 
+constexpr int kHistSlotBits = 13;
 constexpr int kHistBlock = 1024;          // 16 waves per span: a span per 256 threads leaves the chip idle
 
-// One block counts the ids of [blockIdx.x * span, + span) into an LDS table of 2^SLOT_BITS (row, count)
-// entries: a row takes the first of its two slots (two hashes of the row) that is free or already its
-// own; a row that finds both taken by other rows is added to the global counter at once.  At the end
-// the table is flushed with one saturating add per used slot.  The first row to claim a slot keeps it,
-// so a row lives in at most one slot and the counts stay exact.
-//   2^12 slots, spans of 32 k ids: small batches (many blocks, several per CU)
-//   2^13 slots (64 KB of LDS, two blocks per CU), spans of up to 128 k ids: large batches.  A popular
-//          row is flushed once per span, so longer spans mean fewer global updates for the head of the
-//          distribution; two blocks per CU let one block's flush (a stretch of nothing but global
-//          adds) run beside the other's counting.  Measured on 67 M ids of one Zipf(1.3) table
-//          (1.2 M distinct rows): 0.39 ms; with 2^14 slots and one block per CU 0.49 ms, with 32 k spans
-//          and 2^12 slots 0.56 ms; on 72 M ids of Zipf(1.1) over 16 tables (10.8 M distinct rows: the
-//          cold tail's one read-modify-write of a whole line per row dominates) 1.15, 1.11 and 1.45 ms.
-//          Counting the most popular rows in registers (no LDS add for them) changed nothing: the LDS
-//          is not what limits the kernel.
+// One block counts the ids of [blockIdx.x * span, + span) into an LDS table of 2^13 (row, count) entries
+// (64 KB: two blocks per CU, so that one block's flush, a stretch of nothing but global adds, runs beside
+// the other's counting): a row takes the first of its two slots (two hashes of the row) that is free or
+// already its own; a row that finds both taken by other rows is added to the global counter at once.  At
+// the end the table is flushed with one saturating add per used slot.  The first row to claim a slot keeps
+// it, so a row lives in at most one slot and the counts stay exact.
+// What the kernel costs is its global adds: the chip retires about 27 G of them a second wherever they land
+// (one table of 64 KB or 1 GB of counters, one XCD's or all, returning or not), and a span cannot need fewer
+// than it has distinct rows.  Measured: 2^12 slots instead of 2^13 on batches of 4 M to 16 M ids 3 to 13 %
+// slower (more rows find both slots taken); 2^14 slots and one block per CU on 67 M ids of Zipf(1.3) 0.49 ms
+// instead of 0.39 ms; counting the most popular rows in registers changed nothing (the LDS is not the limit).
 typedef int64_t Id2 __attribute__((ext_vector_type(2)));
 
-template <int SLOT_BITS>
 __global__ __launch_bounds__(kHistBlock) void plan_histogram_kernel(
     const int64_t* __restrict__ ids, const int64_t* __restrict__ offsets, int T, int64_t B,
     const int64_t* __restrict__ row_base, int64_t n, int64_t R, int64_t span, uint32_t* __restrict__ counts,
     const int32_t* __restrict__ ok_flag, int32_t* status)
 {
-    constexpr int kSlots = 1 << SLOT_BITS;
+    constexpr int kSlots = 1 << kHistSlotBits;
     __shared__ uint32_t tags[kSlots];          // row + 1, 0 = free
     __shared__ uint32_t hits[kSlots];
     __shared__ int span_tables[2];
@@ -97,11 +93,11 @@ __global__ __launch_bounds__(kHistBlock) void plan_histogram_kernel(
     // look at the answers of a whole batch of ids at once instead of waiting for each on its own.
     auto count_row = [&](uint32_t g, uint32_t* went, uint32_t* old) {
         const uint32_t want = g + 1u;
-        const uint32_t s1 = (g * 2654435761u) >> (32 - SLOT_BITS);
+        const uint32_t s1 = (g * 2654435761u) >> (32 - kHistSlotBits);
         uint32_t tag = tags[s1];
         if (tag == 0) tag = atomicCAS(&tags[s1], 0u, want);
         if (tag == 0 || tag == want) { atomicAdd(&hits[s1], 1u); return; }
-        const uint32_t s2 = ((g ^ (g >> 15)) * 2246822519u) >> (32 - SLOT_BITS);
+        const uint32_t s2 = ((g ^ (g >> 15)) * 2246822519u) >> (32 - kHistSlotBits);
         tag = tags[s2];
         if (tag == 0) tag = atomicCAS(&tags[s2], 0u, want);
         if (tag == 0 || tag == want) { atomicAdd(&hits[s2], 1u); return; }
@@ -203,33 +199,29 @@ __global__ __launch_bounds__(kHistBlock) void plan_histogram_kernel(
     }
 }
 
-// Span length and table size for n ids: small batches keep the 32 k spans and the small table (many blocks
-// per CU).  From one 64 k span for each of the two blocks a CU holds, the large table, with spans of up to
-// 128 k ids, shortened so that their number is a multiple of the CU count where that is possible.  A popular
-// row is flushed once per span, so a planning pass over very many ids (from 2^27) takes spans of up to 512 k
-// ids, all of one length and a whole number of rounds over the chip's 512 resident blocks: 10^9 ids of
-// Zipf(1.3) in one call take 4.7 ms with 128 k spans, 4.1 ms with 512 k, 10 ms with 2 M.  A training batch of
-// a flatter law (72 M ids of Zipf(1.1) over 16 tables) does better with the shorter spans (1.13 ms at 96 k,
-// 1.25 ms at 144 k): the first rows to arrive keep the slots, and a fresh table serves the rows that repeat
-// within a stretch.
+// Span length for n ids: batches keep 32 k spans (many blocks).  From one 64 k span for each of the two
+// blocks a CU holds, spans of up to 128 k ids, shortened so that their number is a multiple of the CU count
+// where that is possible.  A popular row is flushed once per span, so a planning pass over very many ids
+// (from 2^27) takes spans of up to 512 k ids, all of one length and a whole number of rounds over the chip's
+// 512 resident blocks: 10^9 ids of Zipf(1.3) in one call take 4.7 ms with 128 k spans, 4.1 ms with 512 k,
+// 10 ms with 2 M.  A training batch of a flatter law (72 M ids of Zipf(1.1) over 16 tables) does better with
+// the shorter spans (1.13 ms at 96 k, 1.25 ms at 144 k): the first rows to arrive keep the slots, and a fresh
+// table serves the rows that repeat within a stretch.
 constexpr int64_t kHistSpanSmall = 32768;
 constexpr int64_t kHistSpanLarge = 131072;
 constexpr int64_t kHistSpanHuge = 524288;
 constexpr int64_t kHistHugeFrom = (int64_t)1 << 27;
-constexpr int kHistBitsSmall = 12;
-constexpr int kHistBitsLarge = 13;
 constexpr int64_t kHistCus = 256;
 
-static void hist_shape(int64_t n, int64_t* span, bool* large)
+static int64_t hist_span(int64_t n)
 {
-    *large = n >= 2 * kHistCus * (kHistSpanLarge / 2);          // at least one 64 k span for every CU, twice over
-    if (!*large) { *span = kHistSpanSmall; return; }
+    if (n < 2 * kHistCus * (kHistSpanLarge / 2)) return kHistSpanSmall;   // under one 64 k span for every CU, twice over
     const int64_t longest = n >= kHistHugeFrom ? kHistSpanHuge : kHistSpanLarge;
     const int64_t per_round = n >= kHistHugeFrom ? 2 * kHistCus : kHistCus;
     const int64_t rounds = (n + per_round * longest - 1) / (per_round * longest);
     int64_t s = (n + per_round * rounds - 1) / (per_round * rounds);
     s = (s + 8191) / 8192 * 8192;                                // whole rounds of 8 ids per thread
-    *span = s < longest ? s : longest;
+    return s < longest ? s : longest;
 }
 
 // ---- selection --------------------------------------------------------------
@@ -354,6 +346,25 @@ __global__ __launch_bounds__(kBlock) void plan_emit_kernel(
 }
 
 __global__ void plan_set_flag_kernel(int32_t* flag) { *flag = 1; }
+
+// The same check by one block that also sets the flag itself (few segments: one launch instead of two).
+constexpr int64_t kCheckOneBlockMax = 8192;
+__global__ __launch_bounds__(kHistBlock) void plan_check_offsets_one_kernel(
+    const int64_t* __restrict__ offsets, int64_t S, int64_t n, int32_t* ok_flag, int32_t* status)
+{
+    __shared__ int any_bad;
+    if (threadIdx.x == 0) any_bad = 0;
+    __syncthreads();
+    bool bad = false;
+    for (int64_t s = threadIdx.x; s < S; s += kHistBlock) bad |= offsets[s] > offsets[s + 1];
+    if (threadIdx.x == 0) bad |= offsets[0] != 0 || offsets[S] != n;
+    if (ballot(bad) != 0 && lane_id() == 0) any_bad = 1;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        *ok_flag = any_bad ? 0 : 1;
+        if (any_bad) report(status, FS_DEV_BAD_OFFSETS);
+    }
+}
 
 // ---- tier planner -----------------------------------------------------------
 // After the same compaction and sort, rows stand in descending frequency order with
@@ -606,21 +617,20 @@ extern "C" fs_status fs_plan_replication(
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (acc) {
         const int64_t S = (int64_t)T * B;
-        FS_LAUNCH("plan_set_flag", plan_set_flag_kernel, dim3(1), dim3(1), s, ok_flag);
-        const unsigned grid = (unsigned)((S + kBlock - 1) / kBlock < 1024 ? (S + kBlock - 1) / kBlock : 1024);
-        FS_LAUNCH("plan_check_offsets", plan_check_offsets_kernel, dim3(grid), dim3(kBlock), s,
-                  offsets, S, n, ok_flag, dev_status);
+        if (S <= kCheckOneBlockMax) {
+            FS_LAUNCH("plan_check_offsets", plan_check_offsets_one_kernel, dim3(1), dim3(kHistBlock), s,
+                      offsets, S, n, ok_flag, dev_status);
+        } else {
+            FS_LAUNCH("plan_set_flag", plan_set_flag_kernel, dim3(1), dim3(1), s, ok_flag);
+            const unsigned grid = (unsigned)((S + kBlock - 1) / kBlock < 1024 ? (S + kBlock - 1) / kBlock : 1024);
+            FS_LAUNCH("plan_check_offsets", plan_check_offsets_kernel, dim3(grid), dim3(kBlock), s,
+                      offsets, S, n, ok_flag, dev_status);
+        }
         if (n > 0) {
-            int64_t span;
-            bool large;
-            hist_shape(n, &span, &large);
+            const int64_t span = hist_span(n);
             const int64_t blocks = (n + span - 1) / span;
-            if (large)
-                FS_LAUNCH("plan_histogram", plan_histogram_kernel<kHistBitsLarge>, dim3((unsigned)blocks), dim3(kHistBlock), s,
-                          ids, offsets, (int)T, (int64_t)B, row_base, n, R, span, counts, ok_flag, dev_status);
-            else
-                FS_LAUNCH("plan_histogram", plan_histogram_kernel<kHistBitsSmall>, dim3((unsigned)blocks), dim3(kHistBlock), s,
-                          ids, offsets, (int)T, (int64_t)B, row_base, n, R, span, counts, ok_flag, dev_status);
+            FS_LAUNCH("plan_histogram", plan_histogram_kernel, dim3((unsigned)blocks), dim3(kHistBlock), s,
+                      ids, offsets, (int)T, (int64_t)B, row_base, n, R, span, counts, ok_flag, dev_status);
         }
     }
     if (sel) {
