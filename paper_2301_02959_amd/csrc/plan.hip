@@ -227,6 +227,8 @@ static int64_t hist_span(int64_t n)
 // ---- selection --------------------------------------------------------------
 // Reads counts once: the candidates of a 8192-row tile are packed, in row order, at the tile's
 // own place in a staging buffer (keys/vals at [tile * 8192 + i]) and counted.
+// VEC: a lane loads four consecutive counters at once (counts 16-byte aligned); the packed order is the same.
+template <bool VEC>
 __global__ __launch_bounds__(kBlock) void plan_mark_kernel(
     const uint32_t* __restrict__ counts, int64_t R, int allow_zero, uint32_t* __restrict__ tile_count,
     uint32_t* __restrict__ stage_keys, uint32_t* __restrict__ stage_vals)
@@ -234,26 +236,58 @@ __global__ __launch_bounds__(kBlock) void plan_mark_kernel(
     __shared__ uint32_t wave_sum[kWavesPerBlock];
     constexpr int kItems = kSelTile / kBlock;
     constexpr int kSpan = kWave * kItems;                 // consecutive rows per wave
+    constexpr int kStep = VEC ? 4 : 1;                    // consecutive rows per lane and load
     const int w = wave_id();
     const int lane = lane_id();
     const int64_t tile_base = (int64_t)blockIdx.x * kSelTile;
     const int64_t base = tile_base + (int64_t)w * kSpan;
+    // item `it` of a lane is row base + row_of(it): with VEC, load it / 4 brings rows 4 * lane .. 4 * lane + 3 of a
+    // stretch of 256
+    auto row_of = [&](int it) { return VEC ? (it / 4) * (kWave * 4) + lane * 4 + (it & 3) : it * kWave + lane; };
     uint32_t cnt[kItems];
     uint32_t before[kItems];
     bool cand[kItems];
     uint32_t total = 0;
+    if constexpr (VEC) {
 #pragma unroll
-    for (int it = 0; it < kItems; ++it) {
-        const int64_t g = base + it * kWave + lane;
-        cnt[it] = g < R ? counts[g] : 0u;
+        for (int v = 0; v < kItems / 4; ++v) {
+            const int64_t g = base + row_of(4 * v);
+            u32x4 c = {0u, 0u, 0u, 0u};
+            if (g + 3 < R) {
+                c = *reinterpret_cast<const u32x4*>(counts + g);
+            } else {
+                if (g < R) c[0] = counts[g];
+                if (g + 1 < R) c[1] = counts[g + 1];
+                if (g + 2 < R) c[2] = counts[g + 2];
+            }
+            cnt[4 * v] = c[0]; cnt[4 * v + 1] = c[1]; cnt[4 * v + 2] = c[2]; cnt[4 * v + 3] = c[3];
+        }
+    } else {
+#pragma unroll
+        for (int it = 0; it < kItems; ++it) {
+            const int64_t g = base + row_of(it);
+            cnt[it] = g < R ? counts[g] : 0u;
+        }
     }
+    // Position of a candidate among the wave's: those of earlier stretches, those of lower lanes in its stretch
+    // (one ballot per item position), and the lane's own earlier items of the stretch.
 #pragma unroll
-    for (int it = 0; it < kItems; ++it) {
-        const int64_t g = base + it * kWave + lane;
-        cand[it] = g < R && (allow_zero || cnt[it] != 0);
-        const uint64_t b = ballot(cand[it]);
-        before[it] = total + (uint32_t)popc_below(b);
-        total += (uint32_t)__popcll(b);
+    for (int it0 = 0; it0 < kItems; it0 += kStep) {
+        uint32_t lower = 0, mine = 0, all = 0;
+#pragma unroll
+        for (int e = 0; e < kStep; ++e) {
+            const int it = it0 + e;
+            const int64_t g = base + row_of(it);
+            cand[it] = g < R && (allow_zero || cnt[it] != 0);
+            const uint64_t bal = ballot(cand[it]);
+            before[it] = mine;
+            lower += (uint32_t)popc_below(bal);
+            mine += cand[it] ? 1u : 0u;
+            all += (uint32_t)__popcll(bal);
+        }
+#pragma unroll
+        for (int e = 0; e < kStep; ++e) before[it0 + e] += total + lower;
+        total += all;
     }
     if (lane == 0) wave_sum[w] = total;
     __syncthreads();
@@ -266,11 +300,23 @@ __global__ __launch_bounds__(kBlock) void plan_mark_kernel(
 #pragma unroll
     for (int it = 0; it < kItems; ++it) {
         if (cand[it]) {
-            const int64_t g = base + it * kWave + lane;
+            const int64_t g = base + row_of(it);
             stage_keys[tile_base + off + before[it]] = ~cnt[it];
             stage_vals[tile_base + off + before[it]] = (uint32_t)g;
         }
     }
+}
+
+static fs_status launch_mark(const uint32_t* counts, int64_t R, int allow_zero, int64_t sel_tiles, uint32_t* tile_count,
+                             uint32_t* stage_keys, uint32_t* stage_vals, hipStream_t s)
+{
+    if ((reinterpret_cast<uintptr_t>(counts) & 15) == 0)
+        FS_LAUNCH("plan_mark", plan_mark_kernel<true>, dim3((unsigned)sel_tiles), dim3(kBlock), s,
+                  counts, R, allow_zero, tile_count, stage_keys, stage_vals);
+    else
+        FS_LAUNCH("plan_mark", plan_mark_kernel<false>, dim3((unsigned)sel_tiles), dim3(kBlock), s,
+                  counts, R, allow_zero, tile_count, stage_keys, stage_vals);
+    return FS_OK;
 }
 
 constexpr int kScanBlock = 1024;
@@ -635,8 +681,7 @@ extern "C" fs_status fs_plan_replication(
     }
     if (sel) {
         const int allow_zero = (flags & FS_PLAN_ALLOW_ZERO) ? 1 : 0;
-        FS_LAUNCH("plan_mark", plan_mark_kernel, dim3((unsigned)sel_tiles), dim3(kBlock), s,
-                  counts, R, allow_zero, tile_count, keys_b, vals_b);
+        if (fs_status rc = launch_mark(counts, R, allow_zero, sel_tiles, tile_count, keys_b, vals_b, s); rc != FS_OK) return rc;
         FS_LAUNCH("plan_scan", plan_scan_kernel, dim3(1), dim3(kScanBlock), s, tile_count, sel_tiles, num_cand);
         FS_LAUNCH("plan_move", plan_move_kernel, dim3((unsigned)sel_tiles), dim3(kBlock), s,
                   tile_count, sel_tiles, num_cand, keys_b, vals_b, keys_a, vals_a);
@@ -709,8 +754,7 @@ extern "C" fs_status fs_plan_tiers(
                   : (uint64_t)1 << 62;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
-    FS_LAUNCH("plan_mark", plan_mark_kernel, dim3((unsigned)sel_tiles), dim3(kBlock), s,
-              counts, R, 0, tile_count, keys_b, vals_b);
+    if (fs_status rc = launch_mark(counts, R, 0, sel_tiles, tile_count, keys_b, vals_b, s); rc != FS_OK) return rc;
     FS_LAUNCH("plan_scan", plan_scan_kernel, dim3(1), dim3(kScanBlock), s, tile_count, sel_tiles, num_cand);
     FS_LAUNCH("plan_move", plan_move_kernel, dim3((unsigned)sel_tiles), dim3(kBlock), s,
               tile_count, sel_tiles, num_cand, keys_b, vals_b, keys_a, vals_a);

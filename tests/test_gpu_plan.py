@@ -131,6 +131,33 @@ def test_select_ties_zeros_and_allow_zero(G, seed):
         assert rc == orc == 0 and np.array_equal(hsel, osel), (flags, cap)
 
 
+@pytest.mark.parametrize("shift", [0, 1, 2, 3])
+def test_select_with_counts_at_any_alignment(G, shift):
+    """The selection reads the counters four to a lane where their address allows it: counts arrays that start
+    0, 4, 8 and 12 bytes past a 16-byte boundary give the oracle's selection, whole and in order."""
+    import paper_2301_02959_amd as fs
+    rng = np.random.default_rng(40 + shift)
+    R = 50_003 - shift
+    counts = np.minimum(rng.pareto(1.2, R) * 3, 1e6).astype(np.uint32)
+    buf = torch.zeros(R + 8, dtype=torch.int32, device=G.DEV)
+    view = buf[shift:shift + R]
+    assert view.data_ptr() % 16 == 4 * shift
+    view.copy_(torch.from_numpy(counts.view(np.int32)))
+    nz = int((counts > 0).sum())
+    for flags, cap in ((S, 777), (S, nz + 5), (S | Z, R)):
+        orc, ost, osel = oracle.plan_replication(None, None, 1, 1, None, R, counts.copy(), flags, cap * 8, 8)
+        sel = torch.full((cap,), -7, dtype=torch.int64, device=G.DEV)
+        nsel = torch.full((1,), -7, dtype=torch.int64, device=G.DEV)
+        st = torch.zeros(1, dtype=torch.int32, device=G.DEV)
+        rc = fs.fs_plan_replication(None, None, 1, 1, None, 0, R, view, flags, cap * 8, 8, sel, nsel, None, st,
+                                    raise_on_error=False)
+        torch.cuda.synchronize()
+        k = int(nsel.item())
+        assert rc == orc == 0 and int(st.item()) == ost == 0 and k == len(osel)
+        assert np.array_equal(sel[:k].cpu().numpy(), osel), (flags, cap)
+    assert np.array_equal(view.cpu().numpy().view(np.uint32), counts)
+
+
 def test_saturation_faults_and_one_call_does_all(G):
     counts = np.array([2 ** 32 - 3, 0, 5, 0], np.uint32)
     orc, ost, _ = oracle.plan_replication([0, 0, 0, 0, 2], [0, 5], 1, 1, [0, 4], 4, counts.copy(), A)
