@@ -13,12 +13,9 @@
 //                     as broadcasts; a run that starts in the chunk goes to row_grads, the
 //                     piece that continues a run from the previous chunk goes to carry[chunk]
 //   bwd_singletons    runs of one lookup (most runs: the cold tail) are skipped by the walk and
-//                     converted here, fully parallel; the same launch folds the carries: the
-//                     first wave of a chunk whose last run spills over the chunk end (it sees
-//                     that from the keys it has read anyway) adds the carries of the following
-//                     chunks to that run's row_grads, left to right (a launch of its own cost
-//                     one wave per chunk a chain of dependent loads to find out that it had
-//                     nothing to do)
+//                     converted here, fully parallel
+//   bwd_fold          for every run that spills over a chunk end: row_grads += carry of
+//                     the following chunks, left to right
 // which is exactly the summation order stated in flexshard.h (chunk = FS_BWD_TILE).
 // variant 1 replaces carry + fold by fp32 atomic adds into pre-zeroed rows.
 // HBM-bound: grad_out is read once (random 16*units-byte rows), row_grads written once.
@@ -380,48 +377,6 @@ __device__ __forceinline__ void singles_batch(
     }
 }
 
-// The run that starts in `chunk` and goes on into the next chunk(s): its gradient so far (the part in its
-// own chunk, at run index u) plus the carries of the chunks it goes on into, left to right.  One wave.
-__device__ __forceinline__ void fold_spilling_run(
-    const uint32_t* __restrict__ keys, int64_t chunks, int64_t chunk, int64_t u,
-    float* __restrict__ row_grads, int D, int64_t cap, const float* __restrict__ carry)
-{
-    if (u >= cap) return;
-    const int64_t k1 = (chunk + 1) * kChunk;
-    const uint32_t key = keys[k1];
-    // The last chunk whose first lookup still belongs to the run.  Most spilling runs end in the
-    // very next chunk, so the search gallops from there (1, 2, 4 .. chunks ahead) and then bisects:
-    // no further load for a short run instead of log2(m) dependent ones.
-    int64_t lo = chunk + 1, step = 1;                                // chunk lo starts inside the run
-    bool go_on = chunk + 2 < chunks && keys[k1 + kChunk] == key;     // then (chunk + 2) * kChunk < m
-    while (go_on) {
-        lo += step;
-        step <<= 1;
-        go_on = lo + step < chunks && keys[(lo + step) * kChunk] == key;
-    }
-    int64_t hi = lo + step < chunks ? lo + step : chunks;            // chunk hi does not (or does not exist)
-    while (hi - lo > 1) {
-        const int64_t mid = lo + ((hi - lo) >> 1);
-        if (keys[mid * kChunk] == key) lo = mid; else hi = mid;
-    }
-    const int64_t last_chunk = lo;
-    constexpr int kAhead = 8;                    // carries in flight
-    for (int col = lane_id() * 4; col < D; col += kWave * 4) {
-        f32x4 acc = *reinterpret_cast<const f32x4*>(row_grads + u * D + col);
-        int64_t cc = chunk + 1;
-        for (; cc + kAhead <= last_chunk + 1; cc += kAhead) {
-            f32x4 part[kAhead];
-#pragma unroll
-            for (int j = 0; j < kAhead; ++j)
-                part[j] = *reinterpret_cast<const f32x4*>(carry + (cc + j) * D + col);
-#pragma unroll
-            for (int j = 0; j < kAhead; ++j) acc = acc + part[j];
-        }
-        for (; cc <= last_chunk; ++cc) acc = acc + *reinterpret_cast<const f32x4*>(carry + cc * D + col);
-        *reinterpret_cast<f32x4*>(row_grads + u * D + col) = acc;
-    }
-}
-
 // The singletons of a wave's share of one chunk, listed in LDS (position, run index, row), in order.
 // kSinglesSplit waves share a chunk: each reads all of its keys (run indices need the heads before
 // it) but lists only the singletons of its own quarter.  Shorter-lived waves with less to move each
@@ -431,20 +386,18 @@ __device__ __forceinline__ void fold_spilling_run(
 __device__ __forceinline__ bool list_singletons(
     const uint32_t* __restrict__ keys, const uint32_t* __restrict__ vals, int64_t m, int64_t chunks, uint32_t n,
     const uint32_t* __restrict__ block_base, const uint32_t* __restrict__ chunk_local,
-    uint32_t* s_pos, uint32_t* s_run, uint32_t* s_key, uint32_t* singles_out, uint32_t* runs_end, int64_t* spills)
+    uint32_t* s_pos, uint32_t* s_run, uint32_t* s_key, uint32_t* singles_out, uint32_t* runs_end)
 {
     const int lane = lane_id();
     const int64_t wave_global = (int64_t)blockIdx.x * kWavesPerBlock + wave_id();
     const int64_t chunk = wave_global / kSinglesSplit;
     const int part = (int)(wave_global % kSinglesSplit);
-    *spills = -1;
     if (chunk >= chunks) return false;
     const int64_t k0 = chunk * kChunk;
     const int64_t k1 = k0 + kChunk < m ? k0 + kChunk : m;
     const uint32_t first_run = runs_before(block_base, chunk_local, chunk, chunks);
 
     uint32_t heads_before = 0, singles = 0;
-    uint32_t chunk_head = kNoKey, chunk_before = kNoKey, chunk_last = kNoKey, chunk_next = kNoKey;
 #pragma unroll
     for (int q = 0; q < kChunk / kWave; ++q) {
         const int64_t k = k0 + q * kWave + lane;
@@ -465,15 +418,9 @@ __device__ __forceinline__ bool list_singletons(
         }
         heads_before += (uint32_t)__popcll(hb);
         singles += (uint32_t)__popcll(sb);
-        if (q == 0) { chunk_head = __shfl(key, 0); chunk_before = __shfl(prev, 0); }
-        if (q == kChunk / kWave - 1) { chunk_last = __shfl(key, kWave - 1); chunk_next = __shfl(next, kWave - 1); }
     }
     *singles_out = singles;
     *runs_end = first_run + heads_before;
-    // The chunk's last run goes on into the next chunk and started in this one: the chunk's first wave adds
-    // the later chunks' carries to it (fold_spilling_run).  A chunk that is not full is the last one.
-    if (part == 0 && k0 + kChunk < m && chunk_next == chunk_last && !(chunk_head == chunk_last && chunk_before == chunk_last))
-        *spills = chunk;
     if (singles == 0) return false;
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -584,8 +531,7 @@ __global__ __launch_bounds__(kBlock) void bwd_singletons_update_kernel(
     const u32x4* __restrict__ grad, const UpdateArgs a,
     const uint32_t* __restrict__ keys, const uint32_t* __restrict__ vals, int64_t m, int64_t chunks, uint32_t n,
     const uint32_t* __restrict__ block_base, const uint32_t* __restrict__ chunk_local,
-    int64_t* __restrict__ uniq_rows, int64_t cap, uint8_t* __restrict__ applied,
-    float* __restrict__ row_grads, const float* __restrict__ carry)
+    int64_t* __restrict__ uniq_rows, int64_t cap, uint8_t* __restrict__ applied)
 {
     constexpr int RPI = kWave / LG;
     constexpr int CNT = 2;                                           // rows a group keeps in flight (each brings a gradient row, a table
@@ -597,12 +543,9 @@ __global__ __launch_bounds__(kBlock) void bwd_singletons_update_kernel(
     __shared__ __attribute__((aligned(16))) float s_stage[kWavesPerBlock][kWave * 8];
     const int w = wave_id();
     uint32_t singles, runs_end;
-    int64_t spills;
-    const bool any = list_singletons(keys, vals, m, chunks, n, block_base, chunk_local, s_pos[w], s_run[w], s_key[w],
-                                     &singles, &runs_end, &spills);
-    if (spills >= 0 && blockIdx.y == 0)
-        fold_spilling_run(keys, chunks, spills, (int64_t)runs_end - 1, row_grads, a.D, cap, carry);
-    if (!any) return;                                                // wave-uniform; no block barrier below
+    if (!list_singletons(keys, vals, m, chunks, n, block_base, chunk_local, s_pos[w], s_run[w], s_key[w], &singles,
+                         &runs_end))
+        return;                                                      // wave-uniform; no block barrier below
     for (uint32_t s = 0; s < singles; s += CNT * RPI)
         singles_update_batch<CNT, LG, DT, OPT, EXACT>(grad, a, s_pos[w], s_run[w], s_key[w], s_stage[w], s, singles, cap,
                                                        uniq_rows, applied);
@@ -618,7 +561,7 @@ __global__ __launch_bounds__(kBlock) void bwd_singletons_kernel(
     const u32x4* __restrict__ grad, int units, int D,
     const uint32_t* __restrict__ keys, const uint32_t* __restrict__ vals, int64_t m, int64_t chunks, uint32_t n,
     const uint32_t* __restrict__ block_base, const uint32_t* __restrict__ chunk_local,
-    int64_t* __restrict__ uniq_rows, float* __restrict__ row_grads, int64_t cap, const float* __restrict__ carry)
+    int64_t* __restrict__ uniq_rows, float* __restrict__ row_grads, int64_t cap)
 {
     constexpr int RPI = kWave / LG;
     constexpr int UNR = 8;
@@ -629,12 +572,9 @@ __global__ __launch_bounds__(kBlock) void bwd_singletons_kernel(
     const int w = wave_id();
     const int lane = lane_id();
     uint32_t singles, runs_end;
-    int64_t spills;
-    const bool any = list_singletons(keys, vals, m, chunks, n, block_base, chunk_local, s_pos[w], s_run[w], s_key[w],
-                                     &singles, &runs_end, &spills);
-    if (spills >= 0 && blockIdx.y == 0 && carry != nullptr)      // (no carries in the atomic variant)
-        fold_spilling_run(keys, chunks, spills, (int64_t)runs_end - 1, row_grads, D, cap, carry);
-    if (!any) return;                                            // wave-uniform; no block barrier below
+    if (!list_singletons(keys, vals, m, chunks, n, block_base, chunk_local, s_pos[w], s_run[w], s_key[w], &singles,
+                         &runs_end))
+        return;                                                  // wave-uniform; no block barrier below
     const int c = blockIdx.y * LG + lane % LG;
     const bool all_fit = (int64_t)runs_end <= cap;
     // Full batches of UNR instructions, then ONE batch of exactly as many instructions as the rest
@@ -654,6 +594,62 @@ __global__ __launch_bounds__(kBlock) void bwd_singletons_kernel(
                                                        singles, c, all_fit, cap, uniq_rows, row_grads);
         }
 #undef FS_TAIL
+    }
+}
+
+// One wave per chunk; a wave whose chunk starts a spilling run (one that goes on into the next
+// chunk) adds the carries of the chunks the run goes on into, left to right.
+__global__ __launch_bounds__(kBlock) void bwd_fold_kernel(
+    const uint32_t* __restrict__ keys, int64_t m, int64_t chunks,
+    const uint32_t* __restrict__ block_base, const uint32_t* __restrict__ chunk_local,
+    float* __restrict__ row_grads, int D, int64_t cap, const float* __restrict__ carry)
+{
+    const int64_t chunk = (int64_t)blockIdx.x * kWavesPerBlock + wave_id();
+    const int64_t k0 = chunk * kChunk;
+    const int64_t k1 = k0 + kChunk;
+    if (k1 >= m) return;                                             // nothing follows this chunk
+    // Every index the decision needs, loaded in one round: a wave's time here is a chain of
+    // dependent loads, and there are as many waves as chunks.
+    const uint32_t key = keys[k1 - 1];
+    const uint32_t next = keys[k1];
+    const uint32_t head = keys[k0];
+    const uint32_t before = k0 > 0 ? keys[k0 - 1] : kNoKey;
+    const bool has_far = chunk + 2 < chunks;                         // then (chunk + 2) * kChunk < m
+    const uint32_t far = keys[has_far ? k1 + kChunk : k1];
+    const int64_t u = (int64_t)runs_before(block_base, chunk_local, chunk + 1, chunks) - 1;
+    if (next != key) return;                                         // the chunk's last run ends with it
+    if (head == key && before == key) return;                        // the run started in an earlier chunk
+    if (u >= cap) return;
+    // The last chunk whose first lookup still belongs to the run.  Most spilling runs end in the
+    // very next chunk, so the search gallops from there (1, 2, 4 .. chunks ahead) and then bisects:
+    // no further load for a short run instead of log2(m) dependent ones.
+    int64_t lo = chunk + 1, step = 1;                                // chunk lo starts inside the run
+    bool go_on = has_far && far == key;
+    while (go_on) {
+        lo += step;
+        step <<= 1;
+        go_on = lo + step < chunks && keys[(lo + step) * kChunk] == key;
+    }
+    int64_t hi = lo + step < chunks ? lo + step : chunks;            // chunk hi does not (or does not exist)
+    while (hi - lo > 1) {
+        const int64_t mid = lo + ((hi - lo) >> 1);
+        if (keys[mid * kChunk] == key) lo = mid; else hi = mid;
+    }
+    const int64_t last_chunk = lo;
+    constexpr int kAhead = 32;                   // carries in flight: the longest run's chain is latency-bound
+    for (int col = lane_id() * 4; col < D; col += kWave * 4) {
+        f32x4 acc = *reinterpret_cast<const f32x4*>(row_grads + u * D + col);
+        int64_t cc = chunk + 1;
+        for (; cc + kAhead <= last_chunk + 1; cc += kAhead) {
+            f32x4 part[kAhead];
+#pragma unroll
+            for (int j = 0; j < kAhead; ++j)
+                part[j] = *reinterpret_cast<const f32x4*>(carry + (cc + j) * D + col);
+#pragma unroll
+            for (int j = 0; j < kAhead; ++j) acc = acc + part[j];
+        }
+        for (; cc <= last_chunk; ++cc) acc = acc + *reinterpret_cast<const f32x4*>(carry + cc * D + col);
+        *reinterpret_cast<f32x4*>(row_grads + u * D + col) = acc;
     }
 }
 
@@ -699,7 +695,7 @@ template <int LG>
 static fs_status launch_singletons(fs_dtype dtype, const void* grad, int units, int D, const uint32_t* keys,
                                    const uint32_t* vals, int64_t m, int64_t chunks, uint32_t n, const uint32_t* block_base,
                                    const uint32_t* chunk_local, int64_t* uniq_rows, float* row_grads, int64_t cap,
-                                   const float* carry, hipStream_t stream)
+                                   hipStream_t stream)
 {
     const int64_t waves = chunks * kSinglesSplit;
     if ((waves + kWavesPerBlock - 1) / kWavesPerBlock > 0x7FFFFFFF) return FS_ERR_SIZE;
@@ -707,7 +703,7 @@ static fs_status launch_singletons(fs_dtype dtype, const void* grad, int units, 
     const u32x4* g = static_cast<const u32x4*>(grad);
 #define FS_SINGLE_LAUNCH(DT, EX)                                                                                   \
     FS_LAUNCH("bwd_singletons", (bwd_singletons_kernel<LG, DT, EX>), grid, dim3(kBlock), stream, g, units, D, keys,     \
-              vals, m, chunks, n, block_base, chunk_local, uniq_rows, row_grads, cap, carry)
+              vals, m, chunks, n, block_base, chunk_local, uniq_rows, row_grads, cap)
     const bool exact = units == LG && LG >= 16;
     if (dtype == FS_F32) { if (exact) FS_SINGLE_LAUNCH(FS_F32, (LG >= 16)); else FS_SINGLE_LAUNCH(FS_F32, false); }
     else if (dtype == FS_F16) { if (exact) FS_SINGLE_LAUNCH(FS_F16, (LG >= 16)); else FS_SINGLE_LAUNCH(FS_F16, false); }
@@ -721,8 +717,7 @@ template <int LG, int DT>
 static fs_status launch_singletons_update_opt(int optimizer, const void* grad, const UpdateArgs& a, const uint32_t* keys,
                                               const uint32_t* vals, int64_t m, int64_t chunks, uint32_t n,
                                               const uint32_t* block_base, const uint32_t* chunk_local, int64_t* uniq_rows,
-                                              int64_t cap, uint8_t* applied, float* row_grads, const float* carry,
-                                              hipStream_t stream)
+                                              int64_t cap, uint8_t* applied, hipStream_t stream)
 {
     const int64_t waves = chunks * kSinglesSplit;
     if ((waves + kWavesPerBlock - 1) / kWavesPerBlock > 0x7FFFFFFF) return FS_ERR_SIZE;
@@ -730,7 +725,7 @@ static fs_status launch_singletons_update_opt(int optimizer, const void* grad, c
     const u32x4* g = static_cast<const u32x4*>(grad);
 #define FS_SU_LAUNCH(OPT, EX)                                                                                      \
     FS_LAUNCH("bwd_singletons_update", (bwd_singletons_update_kernel<LG, DT, OPT, EX>), grid, dim3(kBlock), stream, g, a, \
-              keys, vals, m, chunks, n, block_base, chunk_local, uniq_rows, cap, applied, row_grads, carry)
+              keys, vals, m, chunks, n, block_base, chunk_local, uniq_rows, cap, applied)
     const bool exact = a.units == LG;
     if (optimizer == FS_OPT_SGD) { if (exact) FS_SU_LAUNCH(FS_OPT_SGD, true); else FS_SU_LAUNCH(FS_OPT_SGD, false); }
     else if (optimizer == FS_OPT_ADAGRAD) { if (exact) FS_SU_LAUNCH(FS_OPT_ADAGRAD, true); else FS_SU_LAUNCH(FS_OPT_ADAGRAD, false); }
@@ -743,17 +738,16 @@ template <int LG>
 static fs_status launch_singletons_update(fs_dtype dtype, int optimizer, const void* grad, const UpdateArgs& a,
                                           const uint32_t* keys, const uint32_t* vals, int64_t m, int64_t chunks, uint32_t n,
                                           const uint32_t* block_base, const uint32_t* chunk_local, int64_t* uniq_rows,
-                                          int64_t cap, uint8_t* applied, float* row_grads, const float* carry,
-                                          hipStream_t stream)
+                                          int64_t cap, uint8_t* applied, hipStream_t stream)
 {
     if (dtype == FS_F32)
         return launch_singletons_update_opt<LG, FS_F32>(optimizer, grad, a, keys, vals, m, chunks, n, block_base, chunk_local,
-                                                        uniq_rows, cap, applied, row_grads, carry, stream);
+                                                        uniq_rows, cap, applied, stream);
     if (dtype == FS_F16)
         return launch_singletons_update_opt<LG, FS_F16>(optimizer, grad, a, keys, vals, m, chunks, n, block_base, chunk_local,
-                                                        uniq_rows, cap, applied, row_grads, carry, stream);
+                                                        uniq_rows, cap, applied, stream);
     return launch_singletons_update_opt<LG, FS_BF16>(optimizer, grad, a, keys, vals, m, chunks, n, block_base, chunk_local,
-                                                     uniq_rows, cap, applied, row_grads, carry, stream);
+                                                     uniq_rows, cap, applied, stream);
 }
 
 // Everything after the sort: (keys, vals) are the lookups in (row, position) order.
@@ -791,7 +785,7 @@ static fs_status bwd_after_sort(const void* grad_out, int64_t n, int D, fs_dtype
     if (update != nullptr) {                     // rows looked up once are updated in place, the others flagged for the step below
 #define FS_SINGLE_UPDATE(LG)                                                                                    \
     rc = launch_singletons_update<LG>(dtype, optimizer, grad_out, *update, keys, vals, m, chunks, (uint32_t)n,    \
-                                      w.block_base, w.chunk_local, uniq_rows, cap_unique, applied, row_grads, w.carry, s)
+                                      w.block_base, w.chunk_local, uniq_rows, cap_unique, applied, s)
         if (units <= 1) FS_SINGLE_UPDATE(1);         // the group sizes of fs_sparse_update: the row-wise rule's sum of
         else if (units <= 2) FS_SINGLE_UPDATE(2);    // squares is taken over the group, and both must round alike
         else if (units <= 4) FS_SINGLE_UPDATE(4);
@@ -801,6 +795,8 @@ static fs_status bwd_after_sort(const void* grad_out, int64_t n, int D, fs_dtype
         else FS_SINGLE_UPDATE(64);
 #undef FS_SINGLE_UPDATE
         if (rc != FS_OK) return rc;
+        FS_LAUNCH("bwd_fold", bwd_fold_kernel, dim3(wave_grid), dim3(kBlock), s,
+                  keys, m, chunks, w.block_base, w.chunk_local, row_grads, D, cap_unique, w.carry);
         UpdateArgs rest = *update;               // the optimizer step on the rows whose gradient is in row_grads
         rest.uniq_rows = uniq_rows; rest.row_grads = row_grads; rest.cap = cap_unique; rest.num_unique = num_unique;
         rest.skip = applied;
@@ -808,7 +804,7 @@ static fs_status bwd_after_sort(const void* grad_out, int64_t n, int D, fs_dtype
     }
 #define FS_SINGLE(LG)                                                                                           \
     rc = launch_singletons<LG>(dtype, grad_out, units, D, keys, vals, m, chunks, (uint32_t)n, w.block_base,       \
-                               w.chunk_local, uniq_rows, row_grads, cap_unique, variant == 0 ? w.carry : nullptr, s)
+                               w.chunk_local, uniq_rows, row_grads, cap_unique, s)
     if (units <= 1) FS_SINGLE(1);
     else if (units <= 2) FS_SINGLE(2);
     else if (units <= 4) FS_SINGLE(4);
@@ -817,7 +813,11 @@ static fs_status bwd_after_sort(const void* grad_out, int64_t n, int D, fs_dtype
     else if (units <= 32) FS_SINGLE(32);
     else FS_SINGLE(64);
 #undef FS_SINGLE
-    return rc;
+    if (rc != FS_OK) return rc;
+    if (variant == 0)
+        FS_LAUNCH("bwd_fold", bwd_fold_kernel, dim3(wave_grid), dim3(kBlock), s,
+                  keys, m, chunks, w.block_base, w.chunk_local, row_grads, D, cap_unique, w.carry);
+    return FS_OK;
 }
 
 static BwdScratch take_bwd_scratch(Carver& ws, int64_t m, int D, int variant)
