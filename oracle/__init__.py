@@ -159,6 +159,46 @@ def seq_gather_fwd_replica(weights: np.ndarray, store: np.ndarray, slot_of_row, 
     return rc, status.value
 
 
+NO_SLOT = 0x3FFFFFFF
+
+
+def replica_tag_slots(placement: np.ndarray, slot_of_row) -> Tuple[int, int]:
+    """Owner bits of every tier-0 entry of `placement` (uint32, in place) = the row's slot, NO_SLOT if none."""
+    assert placement.dtype == np.uint32 and placement.flags.c_contiguous
+    slots = np.ascontiguousarray(slot_of_row, dtype=np.int32)
+    status = ctypes.c_int32(0)
+    rc = lib().oracle_replica_tag_slots(_p(placement), ctypes.c_int64(placement.shape[0]), _p(slots), ctypes.byref(status))
+    return rc, status.value
+
+
+def lookup_slots(placement: np.ndarray, rows, j0: int, j1: int):
+    """Returns (rc, status, out_slots[len(rows)] int32): the slot each lookup's placement entry carries over [j0, j1),
+    -1 where it has none; entries outside the range keep the sentinel -7."""
+    rows = _i64(rows)
+    pl = np.ascontiguousarray(placement, dtype=np.uint32)
+    out = np.full(rows.shape[0], -7, dtype=np.int32)
+    status = ctypes.c_int32(0)
+    rc = lib().oracle_lookup_slots(_p(pl), ctypes.c_int64(pl.shape[0]), _p(rows), ctypes.c_int64(j0), ctypes.c_int64(j1),
+                                   _p(out), ctypes.byref(status))
+    return rc, status.value, out
+
+
+def seq_gather_fwd_slots(weights: np.ndarray, store: np.ndarray, rows, slots, pos, j0: int, j1: int,
+                         out: np.ndarray, dtype: Optional[int] = None) -> Tuple[int, int]:
+    """seq_gather_fwd with lookup j read from store[slots[j]] where slots[j] >= 0.  Returns (rc, status)."""
+    code = _dtype_code(weights, dtype)
+    rows = _i64(rows)
+    pos = np.ascontiguousarray(pos, dtype=np.int32)
+    slots = np.ascontiguousarray(slots, dtype=np.int32)
+    R, D = weights.shape
+    status = ctypes.c_int32(0)
+    rc = lib().oracle_seq_gather_fwd_slots(
+        _p(weights), ctypes.c_int64(R), ctypes.c_int32(D), ctypes.c_int(code), _p(store),
+        ctypes.c_int64(store.shape[0]), _p(rows), _p(slots), _p(pos), ctypes.c_int64(j0), ctypes.c_int64(j1),
+        _p(out), ctypes.c_int64(out.shape[0]), ctypes.byref(status))
+    return rc, status.value
+
+
 def seq_grad_bwd(grad_out: np.ndarray, rows, pos, j0: int, j1: int, R: int, tile: int = BWD_TILE,
                  cap_unique: Optional[int] = None, dtype: Optional[int] = None, want64: bool = True):
     """Returns (rc, status, uniq_rows[n_u], row_grads[n_u, D] f32, row_grads64 or None, n_u)."""

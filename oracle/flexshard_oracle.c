@@ -260,6 +260,74 @@ int oracle_seq_gather_fwd_replica(
     return OK;
 }
 
+/*
+ * Replica slots handed over by the router (Section 3.1: a replicated row has
+ * no owner to name, every GPU holds it; Section 4.3: the replicated rows are
+ * the few most popular ones).  The owner bits of a tier-0 placement entry are
+ * free, so they carry the row's slot in the replica store, NO_SLOT if it has
+ * none; the router, which reads the entry of every lookup anyway, can then
+ * hand each lookup's slot to the gather.
+ */
+#define NO_SLOT 0x3FFFFFFFu
+
+/* placement[r] of every tier-0 row r: owner bits = slot_of_row[r], or NO_SLOT. */
+int oracle_replica_tag_slots(uint32_t* placement, int64_t R, const int32_t* slot_of_row, int32_t* status)
+{
+    if (!placement || !slot_of_row) return ERR_NULL;
+    if (R < 1) return ERR_SIZE;
+    for (int64_t r = 0; r < R; ++r) {
+        if ((placement[r] >> 30) != 0) continue;
+        int32_t s = slot_of_row[r];
+        if (s >= 0 && (uint32_t)s >= NO_SLOT) { flag(status, DEV_BAD_ID); s = -1; }   /* no such slot number */
+        placement[r] = s >= 0 ? (uint32_t)s : NO_SLOT;
+    }
+    return OK;
+}
+
+/* out_slots[j] = the slot the placement entry of rows[j] carries, -1 if none (or not tier 0). */
+int oracle_lookup_slots(
+    const uint32_t* placement, int64_t R, const int64_t* rows, int64_t j0, int64_t j1,
+    int32_t* out_slots, int32_t* status)
+{
+    if (R < 1 || j0 < 0 || j0 > j1) return ERR_SIZE;
+    if (j1 > j0 && (!placement || !rows || !out_slots)) return ERR_NULL;
+    for (int64_t j = j0; j < j1; ++j) {
+        int64_t r = rows[j];
+        out_slots[j] = -1;
+        if (r < 0 || r >= R) { flag(status, DEV_BAD_ID); continue; }
+        uint32_t e = placement[r];
+        if ((e >> 30) == 0 && (e & 0x3FFFFFFFu) != NO_SLOT) out_slots[j] = (int32_t)(e & 0x3FFFFFFFu);
+    }
+    return OK;
+}
+
+/* The gather with each lookup's slot given: slots[j] >= 0 reads store[slots[j]], else weights[rows[j]]. */
+int oracle_seq_gather_fwd_slots(
+    const void* weights, int64_t R, int32_t D, int dtype,
+    const void* store, int64_t k, const int64_t* rows, const int32_t* slots,
+    const int32_t* pos, int64_t j0, int64_t j1,
+    void* out, int64_t n, int32_t* status)
+{
+    int es = elem_size(dtype);
+    if (!es) return ERR_DTYPE;
+    if (R < 1 || n < 0 || D < 1 || j0 < 0 || j0 > j1 || k < 0) return ERR_SIZE;
+    if (j1 > j0 && (!weights || !rows || !pos || !out || !slots || (k > 0 && !store))) return ERR_NULL;
+    size_t row_bytes = (size_t)D * (size_t)es;
+    if (row_bytes % 16 != 0) return ERR_ALIGN;
+    for (int64_t j = j0; j < j1; ++j) {
+        int64_t r = rows[j];
+        int64_t p = pos[j];
+        if (r < 0 || r >= R || p < 0 || p >= n) { flag(status, DEV_BAD_ID); continue; }
+        int32_t s = slots[j];
+        const char* from;
+        if (s < 0) from = (const char*)weights + (size_t)r * row_bytes;
+        else if (s < k) from = (const char*)store + (size_t)s * row_bytes;
+        else { flag(status, DEV_BAD_ID); continue; }
+        memcpy((char*)out + (size_t)p * row_bytes, from, row_bytes);
+    }
+    return OK;
+}
+
 /* IEEE binary16 -> binary32, written out from the format definition. */
 static float half_to_float(uint16_t h)
 {

@@ -25,6 +25,10 @@ int oracle_seq_unbucketize(const void*, int32_t, int, const int32_t*, int64_t, i
 int oracle_replica_build(const void*, int64_t, int32_t, int, const int64_t*, int64_t, void*, int32_t*, int32_t*);
 int oracle_seq_gather_fwd_replica(const void*, int64_t, int32_t, int, const void*, int64_t, const int32_t*,
                                   const int64_t*, const int32_t*, int64_t, int64_t, void*, int64_t, int32_t*);
+int oracle_replica_tag_slots(uint32_t*, int64_t, const int32_t*, int32_t*);
+int oracle_lookup_slots(const uint32_t*, int64_t, const int64_t*, int64_t, int64_t, int32_t*, int32_t*);
+int oracle_seq_gather_fwd_slots(const void*, int64_t, int32_t, int, const void*, int64_t, const int64_t*, const int32_t*,
+                                const int32_t*, int64_t, int64_t, void*, int64_t, int32_t*);
 int oracle_seq_grad_bwd(const void*, int64_t, int32_t, int, const int64_t*, const int32_t*, int64_t, int64_t, int64_t,
                         int32_t, int64_t*, float*, double*, int64_t, int64_t*, int32_t*);
 int oracle_plan_replication(const int64_t*, const int64_t*, int32_t, int32_t, const int64_t*, int64_t, int64_t,
@@ -107,6 +111,16 @@ static void route_and_gather(void)
     float* out3 = malloc(6 * 4 * sizeof(float));
     CHECK(oracle_seq_gather_fwd_replica(w, 6, 4, 0, store, 3, slots, rows_want, pos_want, 0, 6, out3, 6, &st) == 0);
     CHECK(st == 0 && out3[3 * 4 + 1] == 77.0f && out3[4 * 4 + 1] == 31.0f);
+    /* the slots handed over in the placement: all six rows replicated, rows 4 and 1 have a slot */
+    HEAP(uint32_t, tagged, 9u, 9u, 9u, 9u, 9u, 0x80000001u);
+    CHECK(oracle_replica_tag_slots(tagged, 6, slots, &st) == 0 && st == 0);
+    CHECK(tagged[4] == 0u && tagged[1] == 1u && tagged[0] == 0x3FFFFFFFu && tagged[5] == 0x80000001u);
+    int32_t* lslots = malloc(6 * sizeof(int32_t));
+    CHECK(oracle_lookup_slots(tagged, 6, rows_want, 0, 6, lslots, &st) == 0 && st == 0);
+    float* out4 = malloc(6 * 4 * sizeof(float));
+    CHECK(oracle_seq_gather_fwd_slots(w, 6, 4, 0, store, 3, rows_want, lslots, pos_want, 0, 6, out4, 6, &st) == 0 && st == 0);
+    CHECK(memcmp(out3, out4, 24 * sizeof(float)) == 0);               /* what the gather with the slot map wrote (row 5 is not tier 0, and has no slot) */
+    free(tagged); free(lslots); free(out4);
     /* a row and a position out of range are skipped and flagged */
     HEAP(int64_t, bad_rows, 9, 1);
     HEAP(int32_t, bad_pos, 0, 6);

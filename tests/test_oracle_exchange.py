@@ -124,3 +124,63 @@ def test_replica_faults_and_empty():
     out = np.full((2, 4), -1, np.float32)
     rc, st = oracle.seq_gather_fwd_replica(W, store, bad, [1, 4], np.array([0, 1], np.int32), 0, 2, out)
     assert (rc, st) == (0, oracle.BAD_ID) and np.all(out[0] == -1) and np.array_equal(out[1], W[4])
+
+
+def test_slots_travel_in_the_placement_of_replicated_rows():
+    """The slot hand-over: a tier-0 entry's owner bits become the row's slot (NO_SLOT without one), other tiers
+    stay as they are; reading a lookup's slot back is a take through the tagged placement; and the gather with
+    the slots given writes what the gather with the slot map writes -- which, with a store built from the same
+    table, is numpy.take."""
+    from helpers import entry, random_placement
+    rng = np.random.default_rng(5)
+    R, D, k, n = 400, 8, 37, 900
+    W, code = _table(rng, R, D, "f32")
+    pl = random_placement(rng, R, 8, 4, p=(0.5, 0.2, 0.3))
+    before = pl.copy()
+    sel = np.concatenate([rng.permutation(R)[:k - 2], [-3, R + 9]]).astype(np.int64)     # two faulty selections
+    store = np.zeros((k, D), np.float32)
+    rc, st, slot_of_row = oracle.replica_build(W, sel, store)
+    assert rc == 0 and st == oracle.BAD_ID
+    assert oracle.replica_tag_slots(pl, slot_of_row) == (0, 0)
+    tier = before >> 30
+    assert np.array_equal(pl[tier != 0], before[tier != 0])                              # other tiers untouched
+    want = np.where(slot_of_row >= 0, slot_of_row, oracle.NO_SLOT).astype(np.uint32)
+    assert np.array_equal(pl[tier == 0], want[tier == 0]) and np.all(pl[tier == 0] >> 30 == 0)
+    # a lookup's slot: its row's, if the row is replicated here and has one
+    rows = rng.integers(0, R, n)
+    rows[:5] = sel[:5]
+    rc, st, got = oracle.lookup_slots(pl, rows, 100, 850)
+    exp = np.where((tier[rows] == 0) & (slot_of_row[rows] >= 0), slot_of_row[rows], -1)
+    assert (rc, st) == (0, 0) and np.array_equal(got[100:850], exp[100:850]) and np.all(got[:100] == -7) and np.all(got[850:] == -7)
+    rc, st, all_slots = oracle.lookup_slots(pl, rows, 0, n)
+    # the gather with slots: a marked store tells where each row came from
+    pos = rng.permutation(n).astype(np.int32)
+    mark = store + 1000.0
+    out = np.zeros((n, D), np.float32)
+    assert oracle.seq_gather_fwd_slots(W, mark, rows, all_slots, pos, 0, n, out) == (0, 0)
+    ref = np.zeros((n, D), np.float32)
+    ref[pos] = np.where((all_slots >= 0)[:, None], mark[np.maximum(all_slots, 0)], W[rows])
+    assert np.array_equal(out, ref) and (all_slots >= 0).sum() > 20
+    # with the store the table's own rows: the plain lookup, bit for bit, also over a sub-range
+    out2 = np.full((n, D), 5.0, np.float32)
+    assert oracle.seq_gather_fwd_slots(W, store, rows, all_slots, pos, 200, 700, out2) == (0, 0)
+    ref2 = np.full((n, D), 5.0, np.float32)
+    ref2[pos[200:700]] = W[rows[200:700]]
+    assert np.array_equal(out2, ref2)
+
+
+def test_slot_faults():
+    from helpers import entry
+    W = np.arange(40, dtype=np.float32).reshape(10, 4)
+    store = W[:3] + 100
+    # a slot number that the owner bits cannot hold, a row outside the table, a slot beyond the store
+    pl = np.array([entry(0, 7), entry(0, 7), entry(2, 1)], np.uint32)
+    assert oracle.replica_tag_slots(pl, [oracle.NO_SLOT, 2, 0]) == (0, oracle.BAD_ID)
+    assert pl.tolist() == [oracle.NO_SLOT, 2, entry(2, 1)]
+    rc, st, s = oracle.lookup_slots(pl, [1, 3, -1, 0, 2], 0, 5)
+    assert (rc, st) == (0, oracle.BAD_ID) and s.tolist() == [2, -1, -1, -1, -1]
+    out = np.zeros((4, 4), np.float32)
+    rc, st = oracle.seq_gather_fwd_slots(W, store, [4, 5, 6, 11], [1, 3, -1, 0], np.array([0, 1, 2, 3], np.int32), 0, 4, out)
+    assert (rc, st) == (0, oracle.BAD_ID)
+    assert np.array_equal(out, np.stack([store[1], np.zeros(4), W[6], np.zeros(4)]).astype(np.float32))
+    assert oracle.replica_tag_slots(pl, [0, 0, 0])[0] == 0 and oracle.lookup_slots(pl, [0], 1, 0)[0] == 2

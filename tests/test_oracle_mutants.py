@@ -47,6 +47,11 @@ MUTANTS = {
     "replica_last_slot_wins": ("if (slot_of_row[r] < 0) slot_of_row[r] = (int32_t)s;", "slot_of_row[r] = (int32_t)s;"),
     "replica_store_ignored": ("else if (s < k) from = (const char*)store + (size_t)s * row_bytes;", "else if (s < k) from = (const char*)weights + (size_t)r * row_bytes;"),
     "replica_slot_is_row": ("else if (s < k) from = (const char*)store + (size_t)s * row_bytes;", "else if (s < k) from = (const char*)store + (size_t)(r % k) * row_bytes;"),
+    "slots_tag_other_tiers": ("if ((placement[r] >> 30) != 0) continue;\n        int32_t s = slot_of_row[r];", "int32_t s = slot_of_row[r];"),
+    "slots_untagged_row_keeps_owner": ("placement[r] = s >= 0 ? (uint32_t)s : NO_SLOT;", "if (s >= 0) placement[r] = (uint32_t)s;"),
+    "slots_read_from_any_tier": ("if ((e >> 30) == 0 && (e & 0x3FFFFFFFu) != NO_SLOT) out_slots[j]", "if ((e & 0x3FFFFFFFu) != NO_SLOT) out_slots[j]"),
+    "slots_gather_ignores_slot": ("int32_t s = slots[j];\n        const char* from;\n        if (s < 0) from", "int32_t s = -1;\n        const char* from;\n        if (s < 0) from"),
+    "slots_gather_indexed_by_pos": ("int32_t s = slots[j];\n        const char* from;", "int32_t s = slots[p % (j1 - j0)];\n        const char* from;"),
     "tiers_dynamic_saving_doubled": ("const wide_t mem = static_term - U * B * c;", "const wide_t mem = static_term - 2 * U * B * c;"),
     "tiers_saved_without_dynamic": ("saved -= static_term - U * B * (wide_t)cand[i].count;", "saved -= static_term - U * (wide_t)cand[i].count;"),
     "tiers_static_without_shard": ("const wide_t static_term = (dp * U - 1) * S;", "const wide_t static_term = (dp * U) * S;"),
@@ -178,6 +183,10 @@ def pins(o):
     out_r = np.zeros((6, 8), np.float32)
     assert o.seq_gather_fwd_replica(Wt, mark, slots, look, np.arange(6, dtype=np.int32), 0, 6, out_r) == (0, 0)
     assert np.array_equal(out_r, np.stack([mark[1], Wt[5], mark[3], mark[0], mark[4], Wt[6]]))
+    # slots handed over in the placement: tagging, reading back, the gather that takes them
+    import test_oracle_exchange as tx
+    tx.test_slots_travel_in_the_placement_of_replicated_rows()
+    tx.test_slot_faults()
     # tier planner: hand cases, closed forms, the whole-curve brute force
     import test_oracle_tiers as tt
     tt.test_three_tier_hand_case()
