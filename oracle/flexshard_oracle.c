@@ -318,10 +318,10 @@ int oracle_seq_gather_fwd_slots(
         int64_t r = rows[j];
         int64_t p = pos[j];
         if (r < 0 || r >= R || p < 0 || p >= n) { flag(status, DEV_BAD_ID); continue; }
-        int32_t s = slots[j];
+        int32_t slot = slots[j];
         const char* from;
-        if (s < 0) from = (const char*)weights + (size_t)r * row_bytes;
-        else if (s < k) from = (const char*)store + (size_t)s * row_bytes;
+        if (slot < 0) from = (const char*)weights + (size_t)r * row_bytes;
+        else if (slot < k) from = (const char*)store + (size_t)slot * row_bytes;
         else { flag(status, DEV_BAD_ID); continue; }
         memcpy((char*)out + (size_t)p * row_bytes, from, row_bytes);
     }

@@ -50,8 +50,8 @@ MUTANTS = {
     "slots_tag_other_tiers": ("if ((placement[r] >> 30) != 0) continue;\n        int32_t s = slot_of_row[r];", "int32_t s = slot_of_row[r];"),
     "slots_untagged_row_keeps_owner": ("placement[r] = s >= 0 ? (uint32_t)s : NO_SLOT;", "if (s >= 0) placement[r] = (uint32_t)s;"),
     "slots_read_from_any_tier": ("if ((e >> 30) == 0 && (e & 0x3FFFFFFFu) != NO_SLOT) out_slots[j]", "if ((e & 0x3FFFFFFFu) != NO_SLOT) out_slots[j]"),
-    "slots_gather_ignores_slot": ("int32_t s = slots[j];\n        const char* from;\n        if (s < 0) from", "int32_t s = -1;\n        const char* from;\n        if (s < 0) from"),
-    "slots_gather_indexed_by_pos": ("int32_t s = slots[j];\n        const char* from;", "int32_t s = slots[p % (j1 - j0)];\n        const char* from;"),
+    "slots_gather_ignores_slot": ("int32_t slot = slots[j];", "int32_t slot = -1;"),
+    "slots_gather_indexed_by_pos": ("int32_t slot = slots[j];", "int32_t slot = slots[p % (j1 - j0)];"),
     "tiers_dynamic_saving_doubled": ("const wide_t mem = static_term - U * B * c;", "const wide_t mem = static_term - 2 * U * B * c;"),
     "tiers_saved_without_dynamic": ("saved -= static_term - U * B * (wide_t)cand[i].count;", "saved -= static_term - U * (wide_t)cand[i].count;"),
     "tiers_static_without_shard": ("const wide_t static_term = (dp * U - 1) * S;", "const wide_t static_term = (dp * U) * S;"),
