@@ -429,12 +429,29 @@ def run_step_config(cfg, args, steps: int, warmup: int, full_report: bool):
         send = torch.empty(n, D, dtype=cfg.torch_dtype, device=dev)
         store = torch.empty(budget_rows, D, dtype=cfg.torch_dtype, device=dev)
         slots = torch.empty(R, dtype=torch.int32, device=dev)
+        # ... and through the slot hand-over: the placement's tier-0 entries carry the replica slots
+        # (fs_replica_tag_slots), the router hands each lookup's slot on (fs_route_bucketize_slots) and the gather
+        # reads it beside the row and the position (fs_seq_gather_fwd_slots) instead of looking the row up in the
+        # slot map
+        placement_tagged = placement.clone()
+        out_slots = torch.empty(n, dtype=torch.int32, device=dev)
+
+        def q_route_slots(size):
+            rc = L.fs_route_bucketize_slots(z, z, ctypes.c_int32(T), ctypes.c_int32(B), z, z, ctypes.c_int64(n),
+                                            ctypes.c_int32(U), ctypes.c_int32(W), ctypes.c_int32(self_b), z, z, z, z, z, z,
+                                            ctypes.byref(size), z, z)
+            assert rc == 0, rc
+        ws_route_slots = ws_for(q_route_slots)
 
         def xstep():
             fs.fs_replica_build(weights, sel_rows, budget_rows, num_selected, store, slots, status)
             fs.fs_seq_gather_send(weights, out_rows, 0, n, send, status)
             fs.fs_seq_unbucketize(send, out_pos, 0, n, out, status)
             fs.fs_seq_gather_fwd_replica(weights, store, budget_rows, slots, out_rows, out_pos, 0, n, out, status)
+            fs.fs_replica_tag_slots(placement_tagged, slots, status)
+            fs.fs_route_bucketize_slots(ids, offsets, T, B, row_base, placement_tagged, n, U, W, self_b, bucket_offsets,
+                                        out_rows, out_pos, out_slots, tier_counts, status, workspace=ws_route_slots)
+            fs.fs_seq_gather_fwd_slots(weights, store, budget_rows, out_rows, out_slots, out_pos, 0, n, out, status)
 
         for _ in range(2):
             xstep()
@@ -449,10 +466,12 @@ def run_step_config(cfg, args, steps: int, warmup: int, full_report: bool):
         assert int(status.item()) == 0, f"device status {int(status.item())}"
         xalg = {"gather_send": n * row_bytes + n_u * row_bytes + n * 8,
                 "unbucketize": 2 * n * row_bytes + n * 4,
-                "gather_replica": n * row_bytes + n_u * row_bytes + n * 16}
+                "gather_replica": n * row_bytes + n_u * row_bytes + n * 16,
+                "gather_slots": n * row_bytes + n_u * row_bytes + n * 16}
         result["exchange_path"] = {
             "replica_rows": k_sel,
-            "kernels": {k: {"ms": round(v, 4),
+            "lookups_with_a_slot": int((out_slots >= 0).sum().item()),
+            "kernels": {(k + " (with slots)" if k.startswith("route_") else k): {"ms": round(v, 4),
                             **({"GBps": round(xalg[k] / (v * 1e-3) / 1e9, 1),
                                 "frac": round(xalg[k] / (v * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)} if k in xalg else {})}
                         for k, v in sorted(xrec.items())}}

@@ -77,7 +77,9 @@ enum {
  *                       2 sharded over all U GPUs        ("RW")
  *                       3 invalid
  *   bits 29..0   owner  tier 2: bucket in [0, U); tier 1: index in [0, W)
- *                       inside the requester's group; tier 0: ignored.
+ *                       inside the requester's group; tier 0: ignored by
+ *                       fs_route_bucketize; fs_route_bucketize_slots reads
+ *                       the row's replica slot there (FS_OWNER_MASK: none).
  */
 #define FS_TIER_SHIFT 30
 #define FS_OWNER_MASK 0x3FFFFFFFu
@@ -241,6 +243,54 @@ fs_status fs_seq_gather_fwd_replica(
     const void* store, int64_t k, const int32_t* slot_of_row,
     const int64_t* rows, const int32_t* pos, int64_t j0, int64_t j1,
     void* out, int64_t n, void* stream, int32_t* dev_status);
+
+/*
+ * Replica slots handed over by the router (Section 3.1: a replicated row has no
+ * owner to name, every GPU holds it; Section 4.3: the replicated rows are the
+ * few most popular ones, which most lookups ask for).  The owner bits of a
+ * tier-0 placement entry are free, so they can carry the row's slot in the
+ * replica store; the router reads the entry of every lookup anyway and can hand
+ * each lookup's slot to the gather, which then needs no load of the slot map in
+ * front of the load of the row.
+ *
+ * fs_replica_tag_slots -- for every row r in [0, R) whose placement entry is
+ *   tier 0: owner bits = slot_of_row[r] if that is >= 0, else FS_OWNER_MASK
+ *   ("no slot").  Entries of the other tiers are left as they are.
+ *   slot_of_row is what fs_replica_build wrote.
+ *   Data faults: a slot >= FS_OWNER_MASK cannot be carried: "no slot" is
+ *   written (FS_DEV_BAD_ID).  Host faults: NULL; R < 1 (FS_ERR_SIZE).
+ *
+ * fs_route_bucketize_slots -- fs_route_bucketize (same arguments, same outputs,
+ *   same faults), and in addition out_slots[j], j in [0, n): the slot that the
+ *   placement entry of out_rows[j] carries if that entry is tier 0 and its
+ *   owner bits are not FS_OWNER_MASK, else -1.  Meant for a placement whose
+ *   tier-0 entries were written by fs_replica_tag_slots (fs_route_bucketize
+ *   itself ignores those bits).  The workspace is larger by 4 n bytes; ask with
+ *   workspace == NULL.
+ *
+ * fs_seq_gather_fwd_slots -- fs_seq_gather_fwd, except that lookup j with
+ *   slots[j] = s >= 0 is read from store[s, :] instead of weights[rows[j], :]
+ *   (slots is indexed like rows and pos).  With a store built from the same
+ *   weights and slots from fs_route_bucketize_slots the output bits are those
+ *   of fs_seq_gather_fwd.  A slot >= k skips that lookup (FS_DEV_BAD_ID); other
+ *   faults as fs_seq_gather_fwd_replica.
+ */
+fs_status fs_replica_tag_slots(
+    uint32_t* placement, int64_t R, const int32_t* slot_of_row, void* stream, int32_t* dev_status);
+
+fs_status fs_route_bucketize_slots(
+    const int64_t* ids, const int64_t* offsets, int32_t T, int32_t B,
+    const int64_t* row_base, const uint32_t* placement,
+    int64_t n, int32_t U, int32_t W, int32_t self,
+    int64_t* bucket_offsets, int64_t* out_rows, int32_t* out_pos, int32_t* out_slots,
+    int64_t* tier_counts,
+    void* workspace, size_t* workspace_bytes /* host */,
+    void* stream, int32_t* dev_status);
+
+fs_status fs_seq_gather_fwd_slots(
+    const void* weights, int64_t R, int32_t D, fs_dtype dtype,
+    const void* store, int64_t k, const int64_t* rows, const int32_t* slots, const int32_t* pos,
+    int64_t j0, int64_t j1, void* out, int64_t n, void* stream, int32_t* dev_status);
 
 /*
  * fs_seq_grad_bwd -- backward of the sequence lookup (Section 3.2 metrics 4-6:

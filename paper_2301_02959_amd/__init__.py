@@ -34,6 +34,7 @@ STATUS_NAMES = {0: "FS_OK", 1: "FS_ERR_NULL", 2: "FS_ERR_SIZE", 3: "FS_ERR_DTYPE
 EXPORTS = ["fs_route_bucketize", "fs_route_bucketize_noalloc", "fs_seq_gather_fwd", "fs_seq_grad_bwd", "fs_plan_replication",
            "fs_sort_lookups", "fs_seq_grad_bwd_sorted", "fs_seq_gather_fwd_sorted", "fs_seq_grad_bwd_update",
            "fs_seq_gather_send", "fs_seq_unbucketize", "fs_replica_build", "fs_seq_gather_fwd_replica", "fs_plan_tiers",
+           "fs_replica_tag_slots", "fs_route_bucketize_slots", "fs_seq_gather_fwd_slots",
            "fs_cost_model", "fs_tier_traffic", "fs_sparse_update", "fs_util_copy", "fs_util_read_write_mix", "fs_version", "fs_bwd_tile", "fs_prof_begin", "fs_prof_only", "fs_prof_end"]
 
 _DTYPES = {torch.float32: FS_F32, torch.float16: FS_F16, torch.bfloat16: FS_BF16}
@@ -59,6 +60,7 @@ def lib() -> ctypes.CDLL:
         for name in ("fs_sort_lookups", "fs_seq_grad_bwd_sorted", "fs_seq_gather_fwd_sorted", "fs_seq_grad_bwd_update",
                      "fs_route_bucketize", "fs_route_bucketize_noalloc", "fs_seq_gather_fwd", "fs_seq_grad_bwd", "fs_plan_replication",
                      "fs_seq_gather_send", "fs_seq_unbucketize", "fs_replica_build",
+                     "fs_replica_tag_slots", "fs_route_bucketize_slots", "fs_seq_gather_fwd_slots",
                      "fs_seq_gather_fwd_replica", "fs_plan_tiers", "fs_cost_model", "fs_tier_traffic", "fs_sparse_update", "fs_prof_begin", "fs_prof_only",
                      "fs_util_copy", "fs_util_read_write_mix"):
             getattr(_lib, name).restype = ctypes.c_int
@@ -210,6 +212,49 @@ def fs_seq_gather_fwd_replica(weights, store, k: int, slot_of_row, rows, pos, j0
         _ptr(slot_of_row, _I32), _ptr(rows, _I64), _ptr(pos, _I32), ctypes.c_int64(j0), ctypes.c_int64(j1), _ptr(out, _ROWS),
         ctypes.c_int64(n), _stream(), _ptr(dev_status, _I32))
     return _check("fs_seq_gather_fwd_replica", code, raise_on_error)
+
+
+def fs_replica_tag_slots(placement, slot_of_row, dev_status=None, raise_on_error: bool = True,
+                         R: Optional[int] = None) -> int:
+    R = placement.shape[0] if R is None else R
+    code = lib().fs_replica_tag_slots(_ptr(placement, _U32), ctypes.c_int64(R), _ptr(slot_of_row, _I32), _stream(),
+                                      _ptr(dev_status, _I32))
+    return _check("fs_replica_tag_slots", code, raise_on_error)
+
+
+def fs_route_bucketize_slots(ids, offsets, T: int, B: int, row_base, placement, n: int, U: int, W: int, self_: int,
+                             bucket_offsets, out_rows, out_pos, out_slots, tier_counts=None, dev_status=None,
+                             workspace: Optional[torch.Tensor] = None, raise_on_error: bool = True) -> int:
+    L = lib()
+
+    def call(ws_ptr, ws_size_ref):
+        return L.fs_route_bucketize_slots(
+            _ptr(ids, _I64), _ptr(offsets, _I64), ctypes.c_int32(T), ctypes.c_int32(B), _ptr(row_base, _I64), _ptr(placement, _U32),
+            ctypes.c_int64(n), ctypes.c_int32(U), ctypes.c_int32(W), ctypes.c_int32(self_),
+            _ptr(bucket_offsets, _I64), _ptr(out_rows, _I64), _ptr(out_pos, _I32), _ptr(out_slots, _I32), _ptr(tier_counts, _I64),
+            ws_ptr, ws_size_ref, _stream(), _ptr(dev_status, _I32))
+
+    if workspace is None:
+        workspace, size, code = _workspace(call, offsets.device)
+        if code != 0:
+            return _check("fs_route_bucketize_slots", code, raise_on_error)
+    else:
+        size = ctypes.c_size_t(workspace.numel())
+    return _check("fs_route_bucketize_slots", call(_ptr(workspace), ctypes.byref(size)), raise_on_error)
+
+
+def fs_seq_gather_fwd_slots(weights, store, k: int, rows, slots, pos, j0: int, j1: int, out,
+                            dev_status=None, raise_on_error: bool = True, R: Optional[int] = None,
+                            D: Optional[int] = None, dtype: Optional[int] = None, n: Optional[int] = None) -> int:
+    R = weights.shape[0] if R is None else R
+    D = weights.shape[1] if D is None else D
+    n = out.shape[0] if n is None else n
+    dtype = _DTYPES[weights.dtype] if dtype is None else dtype
+    code = lib().fs_seq_gather_fwd_slots(
+        _ptr(weights, _ROWS), ctypes.c_int64(R), ctypes.c_int32(D), ctypes.c_int(dtype), _ptr(store, _ROWS), ctypes.c_int64(k),
+        _ptr(rows, _I64), _ptr(slots, _I32), _ptr(pos, _I32), ctypes.c_int64(j0), ctypes.c_int64(j1), _ptr(out, _ROWS),
+        ctypes.c_int64(n), _stream(), _ptr(dev_status, _I32))
+    return _check("fs_seq_gather_fwd_slots", code, raise_on_error)
 
 
 def fs_seq_grad_bwd(grad_out, rows, pos, j0: int, j1: int, R: int, variant: int,

@@ -83,7 +83,9 @@ __device__ __forceinline__ void gather_wave(int units, u32x4* __restrict__ out,
 //   (fs_seq_unbucketize, out[pos[j]] = recv[j], has a kernel of its own further down)
 //   kReplica:  as kBoth, but a row with slot_of_row[row] >= 0 is read from store[slot]
 //   kSorted:   as kBoth with the lookups as 32-bit (row, position) pairs (fs_seq_gather_fwd_sorted)
-enum GatherMode { kBoth = 0, kToSend = 1, kReplica = 3, kSorted = 4 };
+//   kSlots:    as kReplica with the slot of lookup j given in slots[j], read beside its row and position
+//              (fs_seq_gather_fwd_slots): no load of the slot map in front of the row's
+enum GatherMode { kBoth = 0, kToSend = 1, kReplica = 3, kSorted = 4, kSlots = 5 };
 
 struct GatherArgs {
     const u32x4* weights;
@@ -98,8 +100,9 @@ struct GatherArgs {
     int64_t n;
     int32_t* status;
     int stripe;                      // workgroups per XCD stripe (1: tiles in launch order)
-    const u32x4* store;              // kReplica only
-    const int32_t* slot_of_row;
+    const u32x4* store;              // kReplica and kSlots
+    const int32_t* slot_of_row;      // kReplica: [R]
+    const int32_t* slots;            // kSlots: [m], one per lookup
     int64_t k;
 };
 
@@ -136,8 +139,14 @@ __global__ __launch_bounds__(kBlock) void gather_rows_kernel(const GatherArgs a)
         my_ok = ((uint64_t)my_row < (uint64_t)a.R && (uint32_t)my_pos < (uint32_t)a.n) ? 1 : 0;
         if (!my_ok) { report(a.status, FS_DEV_BAD_ID); my_row = 0; my_pos = 0; }
     }
+    int32_t my_slot = -1;
+    if (MODE == kSlots && jj < m) my_slot = load_stream(a.slots + jj);
     const int64_t stride = EXACT ? LG : a.units;
     const u32x4* my_src = a.weights + my_row * stride;
+    if (MODE == kSlots && my_ok && my_slot >= 0) {
+        if (my_slot < a.k) my_src = a.store + (int64_t)my_slot * stride;
+        else { report(a.status, FS_DEV_BAD_ID); my_ok = 0; my_src = a.weights; my_pos = 0; }
+    }
     if (MODE == kReplica && my_ok) {
         const int32_t slot = a.slot_of_row[my_row];      // cacheable: popular rows repeat
         if (slot >= 0) {
@@ -238,6 +247,21 @@ __global__ __launch_bounds__(kBlock) void replica_clear_kernel(int32_t* __restri
 {
     const int64_t step = (int64_t)gridDim.x * kBlock;
     for (int64_t r = (int64_t)blockIdx.x * kBlock + threadIdx.x; r < R; r += step) slot_of_row[r] = -1;
+}
+
+// The owner bits of every tier-0 placement entry = the row's slot, FS_OWNER_MASK if it has none.
+__global__ __launch_bounds__(kBlock) void replica_tag_slots_kernel(
+    uint32_t* __restrict__ placement, int64_t R, const int32_t* __restrict__ slot_of_row, int32_t* status)
+{
+    const int64_t step = (int64_t)gridDim.x * kBlock;
+    int32_t faults = 0;
+    for (int64_t r = (int64_t)blockIdx.x * kBlock + threadIdx.x; r < R; r += step) {
+        if ((placement[r] >> FS_TIER_SHIFT) != FS_TIER_GLOBAL) continue;
+        int32_t slot = slot_of_row[r];
+        if (slot >= 0 && (uint32_t)slot >= FS_OWNER_MASK) { faults |= FS_DEV_BAD_ID; slot = -1; }   // no such slot number
+        placement[r] = slot >= 0 ? (uint32_t)slot : FS_OWNER_MASK;
+    }
+    if (ballot(faults != 0) != 0 && lane_id() == 0) report(status, FS_DEV_BAD_ID);
 }
 
 // slot_of_row[sel_rows[s]] = the smallest s that names the row (as unsigned, -1 is the largest value)
@@ -358,6 +382,41 @@ extern "C" fs_status fs_seq_gather_fwd_replica(
     a.out = static_cast<u32x4*>(out); a.n = n; a.status = dev_status;
     a.store = static_cast<const u32x4*>(store); a.slot_of_row = slot_of_row; a.k = k;
     return launch_gather<kReplica>(a, "gather_replica", static_cast<hipStream_t>(stream));
+}
+
+extern "C" fs_status fs_seq_gather_fwd_slots(
+    const void* weights, int64_t R, int32_t D, fs_dtype dtype,
+    const void* store, int64_t k, const int64_t* rows, const int32_t* slots, const int32_t* pos,
+    int64_t j0, int64_t j1, void* out, int64_t n, void* stream, int32_t* dev_status)
+{
+    using namespace fs;
+    GatherArgs a = {};
+    const fs_status st = check_rows(weights, out, D, dtype, &a);
+    if (st == FS_ERR_DTYPE) return st;
+    if (R < 1 || n < 0 || n >= (1LL << 31) || D < 1 || j0 < 0 || j0 > j1 || k < 0 || k >= (1LL << 31))
+        return FS_ERR_SIZE;
+    if (j1 == j0) return FS_OK;
+    if (!weights || !rows || !pos || !out || !slots || (k > 0 && !store)) return FS_ERR_NULL;
+    if (st != FS_OK) return st;
+    if (reinterpret_cast<uintptr_t>(store) & 15) return FS_ERR_ALIGN;
+    a.weights = static_cast<const u32x4*>(weights); a.R = R;
+    a.rows = rows + j0; a.pos = pos + j0; a.slots = slots + j0; a.m = j1 - j0;
+    a.out = static_cast<u32x4*>(out); a.n = n; a.status = dev_status;
+    a.store = static_cast<const u32x4*>(store); a.k = k;
+    return launch_gather<kSlots>(a, "gather_slots", static_cast<hipStream_t>(stream));
+}
+
+extern "C" fs_status fs_replica_tag_slots(
+    uint32_t* placement, int64_t R, const int32_t* slot_of_row, void* stream, int32_t* dev_status)
+{
+    using namespace fs;
+    if (!placement || !slot_of_row) return FS_ERR_NULL;
+    if (R < 1) return FS_ERR_SIZE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int64_t grid = (R + kBlock - 1) / kBlock;
+    FS_LAUNCH("replica_tag_slots", replica_tag_slots_kernel, dim3((unsigned)(grid < 16384 ? grid : 16384)), dim3(kBlock), s,
+              placement, R, slot_of_row, dev_status);
+    return FS_OK;
 }
 
 extern "C" fs_status fs_seq_gather_fwd_sorted(

@@ -55,7 +55,7 @@ __global__ __launch_bounds__(kBlock) void route_remap_kernel(
     const int64_t* __restrict__ ids, const int64_t* __restrict__ offsets, int T, int64_t B,
     const int64_t* __restrict__ row_base, const uint32_t* __restrict__ placement,
     int64_t n, int U, int W, int self, int dest_bits,
-    uint16_t* __restrict__ dest_out, uint32_t* __restrict__ g_out,
+    uint16_t* __restrict__ dest_out, uint32_t* __restrict__ g_out, int32_t* __restrict__ slot_out /* or null */,
     uint32_t* __restrict__ tile_hist /* [U + 3][tiles]: buckets, then the three tiers */, int64_t tiles,
     int32_t* status)
 {
@@ -145,6 +145,9 @@ __global__ __launch_bounds__(kBlock) void route_remap_kernel(
             }
             dest_out[i] = (uint16_t)dest;
             g_out[i] = (uint32_t)g[it];
+            // a replicated row's entry names no owner: its owner bits carry the row's replica slot, if it has one
+            if (slot_out != nullptr)
+                slot_out[i] = (tier == FS_TIER_GLOBAL && owner != FS_OWNER_MASK) ? (int32_t)owner : -1;
         }
         // one LDS add per distinct bucket per wave
         const uint64_t same = match_bits(dest, dest_bits, valid);
@@ -192,7 +195,8 @@ __global__ __launch_bounds__(kBlock) void route_scatter_kernel(
     const uint16_t* __restrict__ dest_in, const uint32_t* __restrict__ g_in, int64_t n, int U, int dest_bits,
     const uint32_t* __restrict__ tile_hist /* scanned */, int64_t tiles, const uint32_t* __restrict__ totals,
     int64_t* __restrict__ out_rows, int32_t* __restrict__ out_pos,
-    int64_t* __restrict__ bucket_offsets, int64_t* __restrict__ tier_counts)
+    int64_t* __restrict__ bucket_offsets, int64_t* __restrict__ tier_counts,
+    const int32_t* __restrict__ slot_in /* or null */, int32_t* __restrict__ out_slots)
 {
     extern __shared__ uint32_t lds[];
     uint32_t* bucket_base = lds;                                        // [U] first output index of the tile in bucket b
@@ -240,12 +244,14 @@ __global__ __launch_bounds__(kBlock) void route_scatter_kernel(
     uint32_t dest[kRouteItems];
     uint32_t rank[kRouteItems];
     uint32_t g[kRouteItems];
+    int32_t slot[kRouteItems];
 #pragma unroll
     for (int it = 0; it < kRouteItems; ++it) {
         const int64_t i = base + (int64_t)w * kRouteWaveSpan + it * kWave + lane;
         const bool valid = i < n;
         dest[it] = valid ? dest_in[i] : 0;
         g[it] = valid ? g_in[i] : 0;
+        slot[it] = (valid && slot_in != nullptr) ? slot_in[i] : -1;
     }
 #pragma unroll
     for (int it = 0; it < kRouteItems; ++it) {
@@ -279,6 +285,7 @@ __global__ __launch_bounds__(kBlock) void route_scatter_kernel(
             const uint32_t j = bucket_base[dest[it]] + my_hist[dest[it]] + rank[it];
             out_rows[j] = (int64_t)g[it];
             out_pos[j] = (int32_t)i;
+            if (slot_in != nullptr) out_slots[j] = slot[it];
         }
     }
 }
@@ -303,7 +310,8 @@ static fs_status route_run(
     int64_t n, int32_t U, int32_t W, int32_t self,
     int64_t* bucket_offsets, int64_t* out_rows, int32_t* out_pos,
     int64_t* tier_counts,
-    void* workspace, size_t* workspace_bytes, void* stream, int32_t* dev_status)
+    void* workspace, size_t* workspace_bytes, void* stream, int32_t* dev_status,
+    bool with_slots = false, int32_t* out_slots = nullptr)
 {
     if (!workspace_bytes) return FS_ERR_NULL;
     if (n < 0 || n >= (1LL << 31) || T < 1 || B < 1 || (int64_t)T * B >= (1LL << 31)) return FS_ERR_SIZE;
@@ -315,10 +323,11 @@ static fs_status route_run(
     uint32_t* tile_hist = ws.take<uint32_t>(((size_t)U + 3) * (size_t)tiles);
     uint32_t* g_tmp = ws.take<uint32_t>((size_t)n);
     uint16_t* dest_tmp = ws.take<uint16_t>((size_t)n);
+    int32_t* slot_tmp = with_slots ? ws.take<int32_t>((size_t)n) : nullptr;
     if (!workspace) { *workspace_bytes = ws.used; return FS_OK; }
     if (*workspace_bytes < ws.used || (reinterpret_cast<uintptr_t>(workspace) & 255)) return FS_ERR_WORKSPACE;
     if (!offsets || !row_base || !placement || !bucket_offsets) return FS_ERR_NULL;
-    if (n > 0 && (!ids || !out_rows || !out_pos)) return FS_ERR_NULL;
+    if (n > 0 && (!ids || !out_rows || !out_pos || (with_slots && !out_slots))) return FS_ERR_NULL;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int64_t S = (int64_t)T * B;
@@ -335,13 +344,13 @@ static fs_status route_run(
         FS_LAUNCH_SMEM("route_remap", route_remap_kernel, dim3((unsigned)tiles), dim3(kBlock),
                        (size_t)U * sizeof(uint32_t), s,
                        ids, offsets, (int)T, (int64_t)B, row_base, placement, n, (int)U, (int)W, (int)self,
-                       dest_bits, dest_tmp, g_tmp, tile_hist, tiles, dev_status);
+                       dest_bits, dest_tmp, g_tmp, slot_tmp, tile_hist, tiles, dev_status);
         FS_LAUNCH("route_scan", route_scan_kernel, dim3((unsigned)U + 3), dim3(kRouteScanBlock), s, tile_hist, tiles, totals);
         const unsigned scatter_grid = (unsigned)xcd_striped_grid(tiles, kRouteStripe);
         FS_LAUNCH_SMEM("route_scatter", route_scatter_kernel, dim3(scatter_grid), dim3(kBlock),
                        (size_t)U * sizeof(uint32_t) + (size_t)kWavesPerBlock * U * sizeof(uint16_t), s,
                        dest_tmp, g_tmp, n, (int)U, dest_bits, tile_hist, tiles, totals, out_rows, out_pos,
-                       bucket_offsets, tier_counts);
+                       bucket_offsets, tier_counts, (const int32_t*)slot_tmp, out_slots);
     }
     return FS_OK;
 }
@@ -380,6 +389,18 @@ extern "C" fs_status fs_route_bucketize(
 {
     return fs::route_run(ids, offsets, T, B, row_base, placement, n, U, W, self, bucket_offsets, out_rows, out_pos,
                          tier_counts, workspace, workspace_bytes, stream, dev_status);
+}
+
+extern "C" fs_status fs_route_bucketize_slots(
+    const int64_t* ids, const int64_t* offsets, int32_t T, int32_t B,
+    const int64_t* row_base, const uint32_t* placement,
+    int64_t n, int32_t U, int32_t W, int32_t self,
+    int64_t* bucket_offsets, int64_t* out_rows, int32_t* out_pos, int32_t* out_slots,
+    int64_t* tier_counts,
+    void* workspace, size_t* workspace_bytes, void* stream, int32_t* dev_status)
+{
+    return fs::route_run(ids, offsets, T, B, row_base, placement, n, U, W, self, bucket_offsets, out_rows, out_pos,
+                         tier_counts, workspace, workspace_bytes, stream, dev_status, true, out_slots);
 }
 
 extern "C" fs_status fs_route_bucketize_noalloc(

@@ -212,3 +212,106 @@ def test_c1_plan_replica_route_exchange_end_to_end(G):
     torch.cuda.synchronize()
     assert int(st.item()) == 0 and int(tc[0]) > 0
     assert torch.equal(out, Wt[b["ids"]])
+
+
+@pytest.mark.parametrize("dt,D,U,W", [("f32", 8, 8, 4), ("bf16", 256, 64, 8), ("f16", 72, 24, 24)])
+def test_slots_from_the_router_bit_exact(G, dt, D, U, W):
+    """The slot hand-over: fs_replica_tag_slots writes what the oracle writes into the placement;
+    fs_route_bucketize_slots gives fs_route_bucketize's outputs plus the oracle's slot of every lookup;
+    fs_seq_gather_fwd_slots with those slots writes the oracle's bits, which are the plain gather's when the
+    store holds the table's own rows, and the store's when it does not."""
+    import paper_2301_02959_amd as fs
+    from helpers import random_jagged, random_placement
+    rng = np.random.default_rng(D + U)
+    tdt = TDT[dt]
+    code = G.oracle_dtype(dt)
+    T, B, E, k = 3, 40, 5000, 900
+    R = T * E
+    ids, offsets, row_base, n = random_jagged(rng, T, B, E, 200)
+    ids = np.minimum(rng.pareto(0.9, n).astype(np.int64) * 3, E - 1)            # skewed: the popular rows repeat
+    pl = random_placement(rng, R, U, W, p=(0.4, 0.2, 0.4))
+    Wt = torch.randn(R, D, generator=torch.Generator().manual_seed(D)).to(tdt)
+    Wn = fs_inputs.as_numpy_bits(Wt)
+    # the store: the k most looked-up rows, whatever their tier (only tier-0 rows will be served from it)
+    g_all = row_base[np.repeat(np.arange(T * B), np.diff(offsets)) // B] + ids
+    sel = np.argsort(-np.bincount(g_all, minlength=R), kind="stable")[:k].astype(np.int64)
+    W_d, sel_d, pl_d = Wt.to(G.DEV), G.to_dev(sel, torch.int64), G.placement_dev(pl)
+    st = _status(G)
+    store = torch.zeros(k, D, dtype=tdt, device=G.DEV)
+    slot_of_row = torch.zeros(R, dtype=torch.int32, device=G.DEV)
+    assert fs.fs_replica_build(W_d, sel_d, k, None, store, slot_of_row, st) == 0
+    assert fs.fs_replica_tag_slots(pl_d, slot_of_row, st) == 0
+    ref_store = np.zeros_like(Wn[:k])
+    rc, ost, ref_slot_of_row = oracle.replica_build(Wn, sel, ref_store, dtype=code)
+    pl_tagged = pl.copy()
+    assert oracle.replica_tag_slots(pl_tagged, ref_slot_of_row) == (0, 0)
+    torch.cuda.synchronize()
+    assert int(st.item()) == 0 and np.array_equal(pl_d.cpu().numpy().view(np.uint32), pl_tagged)
+    # the router
+    self_ = U - 1
+    ids_d, off_d, rb_d = G.to_dev(ids, torch.int64), G.to_dev(offsets, torch.int64), G.to_dev(row_base, torch.int64)
+    bo = torch.zeros(U + 1, dtype=torch.int64, device=G.DEV)
+    rows = torch.zeros(n, dtype=torch.int64, device=G.DEV)
+    pos = torch.zeros(n, dtype=torch.int32, device=G.DEV)
+    slots = torch.full((n,), -7, dtype=torch.int32, device=G.DEV)
+    tc = torch.zeros(3, dtype=torch.int64, device=G.DEV)
+    assert fs.fs_route_bucketize_slots(ids_d, off_d, T, B, rb_d, pl_d, n, U, W, self_, bo, rows, pos, slots, tc, st) == 0
+    orc, ost, obo, orows, opos, otc = oracle.route_bucketize(ids, offsets, T, B, row_base, pl_tagged, U, W, self_)
+    rc2, st2, oslots = oracle.lookup_slots(pl_tagged, orows, 0, n)
+    torch.cuda.synchronize()
+    assert (orc, ost, rc2, st2) == (0, 0, 0, 0) and int(st.item()) == 0
+    assert np.array_equal(bo.cpu().numpy(), obo) and np.array_equal(tc.cpu().numpy(), otc)
+    assert np.array_equal(rows.cpu().numpy(), orows) and np.array_equal(pos.cpu().numpy(), opos)
+    assert np.array_equal(slots.cpu().numpy(), oslots) and (oslots >= 0).sum() > n // 10
+    # the gather that takes the slots: a marked store shows which lookups it served
+    mark = (store.float() + 1000.0).to(tdt)
+    mark_n = fs_inputs.as_numpy_bits(mark)
+    for j0, j1, src_d, src_n in ((0, n, mark, mark_n), (n // 7, n - 5, store, ref_store)):
+        out = torch.full((n, D), 7.0, dtype=tdt, device=G.DEV)
+        assert fs.fs_seq_gather_fwd_slots(W_d, src_d, k, rows, slots, pos, j0, j1, out, st) == 0
+        ref = fs_inputs.as_numpy_bits(torch.full((n, D), 7.0, dtype=tdt)).copy()
+        assert oracle.seq_gather_fwd_slots(Wn, src_n, orows, oslots, opos, j0, j1, ref, dtype=code) == (0, 0)
+        torch.cuda.synchronize()
+        assert int(st.item()) == 0 and np.array_equal(G.bits(out), ref.view(np.uint8).reshape(-1))
+    direct = torch.full((n, D), 7.0, dtype=tdt, device=G.DEV)
+    assert fs.fs_seq_gather_fwd(W_d, rows, pos, n // 7, n - 5, direct, st) == 0
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.uint8), direct.view(torch.uint8))       # the store's rows are the table's
+
+
+def test_slot_faults(G):
+    import paper_2301_02959_amd as fs
+    from helpers import entry
+    Wt = torch.arange(10 * 4, dtype=torch.float32).reshape(10, 4).to(G.DEV)
+    store = Wt[:3] + 100
+    st = _status(G)
+    # a slot number that the owner bits cannot hold; entries of other tiers stay
+    pl = G.placement_dev(np.array([entry(0, 7), entry(0, 7), entry(2, 1)], np.uint32))
+    assert fs.fs_replica_tag_slots(pl, G.to_dev([oracle.NO_SLOT, 2, 0], torch.int32), st) == 0
+    torch.cuda.synchronize()
+    assert int(st.item()) == oracle.BAD_ID and pl.cpu().numpy().view(np.uint32).tolist() == [oracle.NO_SLOT, 2, entry(2, 1)]
+    # a slot beyond the store and a row outside the table skip the lookup
+    st.zero_()
+    out = torch.zeros(4, 4, device=G.DEV)
+    rows, slots, pos = G.to_dev([4, 5, 6, 11], torch.int64), G.to_dev([1, 3, -1, 0], torch.int32), G.to_dev([0, 1, 2, 3], torch.int32)
+    assert fs.fs_seq_gather_fwd_slots(Wt, store, 3, rows, slots, pos, 0, 4, out, st) == 0
+    torch.cuda.synchronize()
+    assert int(st.item()) == oracle.BAD_ID
+    assert torch.equal(out, torch.stack([store[1], torch.zeros(4, device=G.DEV), Wt[6], torch.zeros(4, device=G.DEV)]))
+    # host faults
+    assert fs.fs_replica_tag_slots(None, slots, st, raise_on_error=False, R=3) == 1
+    assert fs.fs_replica_tag_slots(pl, slots, st, raise_on_error=False, R=0) == 2
+    assert fs.fs_seq_gather_fwd_slots(Wt, store, 3, rows, None, pos, 0, 4, out, st, raise_on_error=False) == 1
+    assert fs.fs_seq_gather_fwd_slots(Wt, store, -1, rows, slots, pos, 0, 4, out, st, raise_on_error=False) == 2
+    assert fs.fs_seq_gather_fwd_slots(Wt, store, 3, rows, slots, pos, 3, 2, out, st, raise_on_error=False) == 2
+    z64 = torch.zeros(4, dtype=torch.int64, device=G.DEV)
+    off = G.to_dev([0, 4], torch.int64)
+    rb = G.to_dev([0, 3], torch.int64)
+    bo = torch.zeros(2, dtype=torch.int64, device=G.DEV)
+    assert fs.fs_route_bucketize_slots(z64, off, 1, 1, rb, pl, 4, 1, 1, 0, bo, z64.clone(), pos.clone(), None, None, st,
+                                       raise_on_error=False) == 1
+    # an empty batch: offsets written, nothing else
+    off0 = G.to_dev([0, 0], torch.int64)
+    assert fs.fs_route_bucketize_slots(None, off0, 1, 1, rb, pl, 0, 1, 1, 0, bo, None, None, None, None, st) == 0
+    torch.cuda.synchronize()
+    assert bo.tolist() == [0, 0]
