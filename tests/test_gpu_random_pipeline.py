@@ -70,6 +70,22 @@ def test_random_pipeline(G, seed):
     assert (rc, st) == (orc, ost) == (0, 0)
     assert np.array_equal(bo.cpu().numpy(), obo) and np.array_equal(tc.cpu().numpy(), otc)
     assert np.array_equal(rows.cpu().numpy(), orows) and np.array_equal(pos.cpu().numpy(), opos)
+    # ---- the router that also hands over the slot a replicated row's placement entry carries
+    bo_s = torch.zeros(c["U"] + 1, dtype=torch.int64, device=G.DEV)
+    rows_s = torch.zeros(max(n, 1), dtype=torch.int64, device=G.DEV)
+    pos_s = torch.zeros(max(n, 1), dtype=torch.int32, device=G.DEV)
+    slots_s = torch.full((max(n, 1),), -7, dtype=torch.int32, device=G.DEV)
+    tc_s = torch.zeros(3, dtype=torch.int64, device=G.DEV)
+    st_s = torch.zeros(1, dtype=torch.int32, device=G.DEV)
+    assert fs.fs_route_bucketize_slots(G.to_dev(c["ids"], torch.int64), G.to_dev(c["offsets"], torch.int64), c["T"], c["B"],
+                                       G.to_dev(c["row_base"], torch.int64), G.placement_dev(c["placement"]), n, c["U"], c["W"],
+                                       c["self_"], bo_s, rows_s, pos_s, slots_s, tc_s, st_s) == 0
+    orc, ost, oslots = oracle.lookup_slots(c["placement"], orows, 0, n)
+    torch.cuda.synchronize()
+    assert (orc, ost) == (0, 0) and int(st_s.item()) == 0
+    assert np.array_equal(bo_s.cpu().numpy(), obo) and np.array_equal(tc_s.cpu().numpy(), otc)
+    assert np.array_equal(rows_s[:n].cpu().numpy(), orows) and np.array_equal(pos_s[:n].cpu().numpy(), opos)
+    assert np.array_equal(slots_s[:n].cpu().numpy(), oslots)
     if n == 0:
         return
     # ---- ranges: everything, one bucket, an arbitrary slice, an empty range
