@@ -50,20 +50,27 @@ __global__ __launch_bounds__(kBlock) void plan_check_offsets_kernel(
     if (ballot(bad) != 0 && lane_id() == 0) { report(status, FS_DEV_BAD_OFFSETS); atomicExch(ok_flag, 0); }
 }
 
-constexpr int kHistSlotBits = 13;
+constexpr int kHistSlotBits = 14;
+constexpr uint32_t kHistMul1 = 2654435761u, kHistMul1Inv = 0x0e8b2f51u;    // odd multipliers: bijections of 32-bit words,
+constexpr uint32_t kHistMul2 = 2246822519u, kHistMul2Inv = 0xb6c92f47u;    // undone by their inverses mod 2^32
 constexpr int kHistBlock = 1024;          // 16 waves per span: a span per 256 threads leaves the chip idle
 
-// One block counts the ids of [blockIdx.x * span, + span) into an LDS table of 2^13 (row, count) entries
+// One block counts the ids of [blockIdx.x * span, + span) into an LDS table of 2^14 entries of 32 bits
 // (64 KB: two blocks per CU, so that one block's flush, a stretch of nothing but global adds, runs beside
-// the other's counting): a row takes the first of its two slots (two hashes of the row) that is free or
-// already its own; a row that finds both taken by other rows is added to the global counter at once.  At
-// the end the table is flushed with one saturating add per used slot.  The first row to claim a slot keeps
-// it, so a row lives in at most one slot and the counts stay exact.
+// the other's counting).  A row takes the first of its two slots (two hashes of the row) that is free or
+// already its own; a row that finds both taken by other rows is added to the global counter at once.  An
+// entry does not hold the row: the slot is the top 14 bits of a hash that is a bijection of 32-bit words,
+// so the other 18 bits (plus one, so that a used entry is never zero, and one bit for which hash it was)
+// name the row, and the 12 bits above them count it; a count that wraps sends its 4096 to the global
+// counter at once.  At the end the table is flushed with one saturating add per used slot.  The first row
+// to claim a slot keeps it, so the counts stay exact.
 // What the kernel costs is its global adds: the chip retires about 27 G of them a second wherever they land
 // (one table of 64 KB or 1 GB of counters, one XCD's or all, returning or not), and a span cannot need fewer
-// than it has distinct rows.  Measured: 2^12 slots instead of 2^13 on batches of 4 M to 16 M ids 3 to 13 %
-// slower (more rows find both slots taken); 2^14 slots and one block per CU on 67 M ids of Zipf(1.3) 0.49 ms
-// instead of 0.39 ms; counting the most popular rows in registers changed nothing (the LDS is not the limit).
+// than it has distinct rows.  Measured: (row, count) pairs of 64 bits, half as many entries in the same LDS:
+// 7 % slower on 10^9 ids of Zipf(1.3), 6 to 8 % on batches of 16 M and 72 M ids, 7 % FASTER on 67 M ids of
+// Zipf(1.3) in one round of 512 blocks (fewer entries to flush when all blocks flush together); a quarter
+// as many entries 3 to 13 % slower again; 2^14 pairs and one block per CU 0.49 ms instead of 0.39 ms on
+// those 67 M ids; counting the most popular rows in registers changed nothing (the LDS is not the limit).
 typedef int64_t Id2 __attribute__((ext_vector_type(2)));
 
 __global__ __launch_bounds__(kHistBlock) void plan_histogram_kernel(
@@ -72,14 +79,17 @@ __global__ __launch_bounds__(kHistBlock) void plan_histogram_kernel(
     const int32_t* __restrict__ ok_flag, int32_t* status)
 {
     constexpr int kSlots = 1 << kHistSlotBits;
-    __shared__ uint32_t tags[kSlots];          // row + 1, 0 = free
-    __shared__ uint32_t hits[kSlots];
+    constexpr int kRestBits = 32 - kHistSlotBits;                   // bits of a row's hash that its slot does not give
+    constexpr int kCountShift = kRestBits + 2;                      // entry: [count | which hash | rest + 1]
+    constexpr uint32_t kTagMask = (1u << kCountShift) - 1u;
+    constexpr uint32_t kCountMax = (1u << (32 - kCountShift)) - 1u;
+    __shared__ uint32_t table[kSlots];         // 0 = free
     __shared__ int span_tables[2];
     if (*ok_flag == 0) return;                 // bad offsets: count nothing
     const int64_t base = (int64_t)blockIdx.x * span;
     const int64_t end = base + span < n ? base + span : n;
     if (base >= end) return;
-    for (int s = threadIdx.x; s < kSlots; s += kHistBlock) { tags[s] = 0; hits[s] = 0; }
+    for (int s = threadIdx.x; s < kSlots; s += kHistBlock) table[s] = 0;
     if (threadIdx.x == 0) {
         span_tables[0] = plan_table_of(offsets, T, B, base);
         span_tables[1] = plan_table_of(offsets, T, B, end - 1);
@@ -88,24 +98,37 @@ __global__ __launch_bounds__(kHistBlock) void plan_histogram_kernel(
     const int t_lo = __builtin_amdgcn_readfirstlane(span_tables[0]);
     const int t_hi = __builtin_amdgcn_readfirstlane(span_tables[1]);
     int32_t faults = 0;
-    // Counts one row in the LDS table.  A row that finds both its slots taken goes to the global counter:
-    // the add is issued here and its old value handed back (`*went` = the row + 1), so that the caller can
-    // look at the answers of a whole batch of ids at once instead of waiting for each on its own.
-    auto count_row = [&](uint32_t g, uint32_t* went, uint32_t* old) {
-        const uint32_t want = g + 1u;
-        const uint32_t s1 = (g * 2654435761u) >> (32 - kHistSlotBits);
-        uint32_t tag = tags[s1];
-        if (tag == 0) tag = atomicCAS(&tags[s1], 0u, want);
-        if (tag == 0 || tag == want) { atomicAdd(&hits[s1], 1u); return; }
-        const uint32_t s2 = ((g ^ (g >> 15)) * 2246822519u) >> (32 - kHistSlotBits);
-        tag = tags[s2];
-        if (tag == 0) tag = atomicCAS(&tags[s2], 0u, want);
-        if (tag == 0 || tag == want) { atomicAdd(&hits[s2], 1u); return; }
-        *went = want;
-        *old = atomicAdd(counts + g, 1u);
+    // Counts one row in the LDS table.  At most one global add comes of it: of 1 for a row that finds both
+    // its slots taken, of a full count field for a row whose count in the table has just wrapped to zero.  The
+    // add is issued here and its old value handed back (`*went` = the row + 1, `*amount`), so that the caller
+    // can look at the answers of a whole batch of ids at once instead of waiting for each on its own.
+    auto count_row = [&](uint32_t g, uint32_t* went, uint32_t* amount, uint32_t* old) {
+        const uint32_t h1 = g * kHistMul1;
+        const uint32_t s1 = h1 >> kRestBits;
+        const uint32_t tag1 = (h1 & ((1u << kRestBits) - 1u)) + 1u;
+        uint32_t e = table[s1];
+        if (e == 0) e = atomicCAS(&table[s1], 0u, tag1);
+        uint32_t* mine = nullptr;
+        if (e == 0 || (e & kTagMask) == tag1) mine = &table[s1];
+        else {
+            const uint32_t h2 = (g ^ (g >> 15)) * kHistMul2;
+            const uint32_t s2 = h2 >> kRestBits;
+            const uint32_t tag2 = ((h2 & ((1u << kRestBits) - 1u)) + 1u) | (1u << (kRestBits + 1));
+            e = table[s2];
+            if (e == 0) e = atomicCAS(&table[s2], 0u, tag2);
+            if (e == 0 || (e & kTagMask) == tag2) mine = &table[s2];
+        }
+        if (mine != nullptr) {
+            // the count is the entry's top field: a carry out of it is lost, the tag below it stays whole
+            const uint32_t before = atomicAdd(mine, 1u << kCountShift);
+            if ((before >> kCountShift) != kCountMax) return;
+            *amount = kCountMax + 1u;                               // wrapped to zero: that many counts go to memory now
+        }
+        *went = g + 1u;
+        *old = atomicAdd(counts + g, *amount);
     };
-    auto settle = [&](uint32_t went, uint32_t old) {             // the add wrapped: pin the counter at the maximum
-        if (went != 0 && old == 0xFFFFFFFFu) {
+    auto settle = [&](uint32_t went, uint32_t amount, uint32_t old) {   // the add wrapped: pin the counter at the maximum
+        if (went != 0 && old > 0xFFFFFFFFu - amount) {
             atomicExch(counts + (went - 1u), 0xFFFFFFFFu);
             faults |= FS_DEV_COUNT_OVERFLOW;
         }
@@ -121,18 +144,19 @@ __global__ __launch_bounds__(kHistBlock) void plan_histogram_kernel(
         if (lo >= hi) continue;
         const int64_t first = row_base[t];
         const int64_t rows_t = row_base[t + 1] - first;
-        auto count_one = [&](int64_t id, uint32_t* went, uint32_t* old) {
+        auto count_one = [&](int64_t id, uint32_t* went, uint32_t* amount, uint32_t* old) {
             *went = 0;
+            *amount = 1u;
             *old = 0;
             if (id < 0 || id >= rows_t) { faults |= FS_DEV_BAD_ID; id = 0; }
             if ((uint64_t)(first + id) >= (uint64_t)R) { faults |= FS_DEV_BAD_ID; return; }   // row_base does not fit R
-            count_row((uint32_t)(first + id), went, old);
+            count_row((uint32_t)(first + id), went, amount, old);
         };
         if ((reinterpret_cast<uintptr_t>(ids + lo) & 15) != 0) {         // an odd first id: on its own
             if (threadIdx.x == 0) {
-                uint32_t went, old;
-                count_one(load_stream(ids + lo), &went, &old);
-                settle(went, old);
+                uint32_t went, amount, old;
+                count_one(load_stream(ids + lo), &went, &amount, &old);
+                settle(went, amount, old);
             }
             ++lo;
         }
@@ -142,29 +166,29 @@ __global__ __launch_bounds__(kHistBlock) void plan_histogram_kernel(
         int64_t p = threadIdx.x;
         for (; p + (int64_t)(kAhead - 1) * kHistBlock < num_pairs; p += (int64_t)kAhead * kHistBlock) {
             Id2 id[kAhead];
-            uint32_t went[2 * kAhead], old[2 * kAhead];
+            uint32_t went[2 * kAhead], amount[2 * kAhead], old[2 * kAhead];
 #pragma unroll
             for (int q = 0; q < kAhead; ++q) id[q] = load_stream(pairs + p + (int64_t)q * kHistBlock);
 #pragma unroll
             for (int q = 0; q < kAhead; ++q) {
-                count_one(id[q].x, &went[2 * q], &old[2 * q]);
-                count_one(id[q].y, &went[2 * q + 1], &old[2 * q + 1]);
+                count_one(id[q].x, &went[2 * q], &amount[2 * q], &old[2 * q]);
+                count_one(id[q].y, &went[2 * q + 1], &amount[2 * q + 1], &old[2 * q + 1]);
             }
 #pragma unroll
-            for (int q = 0; q < 2 * kAhead; ++q) settle(went[q], old[q]);
+            for (int q = 0; q < 2 * kAhead; ++q) settle(went[q], amount[q], old[q]);
         }
         for (; p < num_pairs; p += kHistBlock) {
             const Id2 id = load_stream(pairs + p);
-            uint32_t went[2], old[2];
-            count_one(id.x, &went[0], &old[0]);
-            count_one(id.y, &went[1], &old[1]);
-            settle(went[0], old[0]);
-            settle(went[1], old[1]);
+            uint32_t went[2], amount[2], old[2];
+            count_one(id.x, &went[0], &amount[0], &old[0]);
+            count_one(id.y, &went[1], &amount[1], &old[1]);
+            settle(went[0], amount[0], old[0]);
+            settle(went[1], amount[1], old[1]);
         }
         if (((hi - lo) & 1) != 0 && threadIdx.x == kHistBlock - 1) {     // an odd last id
-            uint32_t went, old;
-            count_one(load_stream(ids + hi - 1), &went, &old);
-            settle(went, old);
+            uint32_t went, amount, old;
+            count_one(load_stream(ids + hi - 1), &went, &amount, &old);
+            settle(went, amount, old);
         }
     }
     __syncthreads();
@@ -179,8 +203,18 @@ __global__ __launch_bounds__(kHistBlock) void plan_histogram_kernel(
 #pragma unroll
         for (int q = 0; q < kBatch; ++q) {
             const int s = (s0 + q) * kHistBlock + threadIdx.x;
-            tag[q] = tags[s];
-            add[q] = hits[s];
+            const uint32_t e = table[s];
+            add[q] = e >> kCountShift;
+            // the row back from its slot and the rest of its hash: both hashes are bijections of 32-bit words
+            const uint32_t h = ((uint32_t)s << kRestBits) | ((e & ((1u << (kRestBits + 1)) - 1u)) - 1u);
+            uint32_t g;
+            if ((e >> (kRestBits + 1)) & 1u) {
+                const uint32_t y = h * kHistMul2Inv;
+                g = y ^ (y >> 15) ^ (y >> 30);
+            } else {
+                g = h * kHistMul1Inv;
+            }
+            tag[q] = e != 0 ? g + 1u : 0u;
         }
 #pragma unroll
         for (int q = 0; q < kBatch; ++q)

@@ -158,6 +158,27 @@ def test_select_with_counts_at_any_alignment(G, shift):
     assert np.array_equal(view.cpu().numpy().view(np.uint32), counts)
 
 
+def test_histogram_counts_beyond_a_table_entry_and_saturation_in_pieces(G):
+    """A row met more often in one span than an entry of the kernel's LDS table can count (4096) reaches the
+    global counter in pieces: the total is exact, and a counter that saturates on one of the pieces stays at
+    the maximum and raises the flag, as the oracle's does."""
+    rng = np.random.default_rng(77)
+    R = 1000
+    ids = np.concatenate([np.full(100_000, 7), np.full(10_000, 8), np.full(4096, 9), np.full(4097, 10), np.full(8192, 11),
+                          rng.integers(0, R, 50_000)]).astype(np.int64)
+    ids = ids[rng.permutation(len(ids))]
+    offsets = np.array([0, len(ids)], np.int64)
+    base = np.zeros(R, np.uint32)
+    base[7] = 2 ** 32 - 5000                       # saturates part of the way
+    base[8] = 2 ** 32 - 1 - 10_000 - int((ids == 8).sum() - 10_000)     # ends exactly at the maximum: no fault
+    base[11] = 123
+    oc = base.copy()
+    orc, ost, _ = oracle.plan_replication(ids, offsets, 1, 1, [0, R], R, oc, A)
+    rc, st, hc, _, _ = hip_plan(G, ids, offsets, 1, 1, [0, R], R, base, A)
+    assert rc == orc == 0 and st == ost == oracle.COUNT_OVERFLOW
+    assert np.array_equal(hc, oc) and hc[7] == 2 ** 32 - 1 and hc[8] == 2 ** 32 - 1 and hc[9] >= 4096 and hc[10] >= 4097
+
+
 def test_saturation_faults_and_one_call_does_all(G):
     counts = np.array([2 ** 32 - 3, 0, 5, 0], np.uint32)
     orc, ost, _ = oracle.plan_replication([0, 0, 0, 0, 2], [0, 5], 1, 1, [0, 4], 4, counts.copy(), A)
