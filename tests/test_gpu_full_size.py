@@ -83,13 +83,24 @@ def _run_config(G, cfg, check_atomic=True, bwd_rows_sample=None, exchange=True):
     assert orc == 0 and ost == 0
     assert np.array_equal(bo.cpu().numpy(), obo) and np.array_equal(tc.cpu().numpy(), otc)
     assert np.array_equal(rows.cpu().numpy(), orows) and np.array_equal(pos.cpu().numpy(), opos)
-    del ids_h, pl_h
+    del ids_h
+
+    # ---- the shared sort (what bench.py's step runs): the oracle's (row, pos) order, pair for pair
+    _progress(f"[{cfg.name}] sort of the lookups against the oracle's")
+    st_t = torch.zeros(1, dtype=torch.int32, device=dev)
+    srows = torch.zeros(n, dtype=torch.int32, device=dev)
+    spos = torch.zeros(n, dtype=torch.int32, device=dev)
+    fs.fs_sort_lookups(rows, pos, 0, n, R, n, srows, spos, st_t)
+    orc, ost, osr, osp = oracle.sort_lookups(orows, opos, 0, n, R, n)
+    torch.cuda.synchronize()
+    assert (orc, ost) == (0, 0) and int(st_t.item()) == 0
+    assert np.array_equal(srows.cpu().numpy().view(np.uint32), osr) and np.array_equal(spos.cpu().numpy().view(np.uint32), osp)
+    del osr, osp
 
     # ---- gather over all buckets
     _progress(f"[{cfg.name}] gather")
     weights = fs_inputs.make_table(cfg, dev)
     out = torch.empty(n, D, dtype=cfg.torch_dtype, device=dev)
-    st_t = torch.zeros(1, dtype=torch.int32, device=dev)
     fs.fs_seq_gather_fwd(weights, rows, pos, 0, n, out, st_t)
     torch.cuda.synchronize()
     assert int(st_t.item()) == 0
@@ -111,6 +122,17 @@ def _run_config(G, cfg, check_atomic=True, bwd_rows_sample=None, exchange=True):
     assert oracle.seq_gather_fwd(w_s, np.arange(len(samp)), np.arange(len(samp), dtype=np.int32), 0, len(samp), ref,
                                  dtype=G.oracle_dtype(cfg.dtype)) == (0, 0)
     assert np.array_equal(fs_inputs.as_numpy_bits(out[samp_t]).view(np.uint8), ref.view(np.uint8))
+    ibits_ = torch.int16 if cfg.dtype != "f32" else torch.int32
+    # ---- the gather in row order (the other order bench.py's step may take): the same bits
+    if torch.cuda.mem_get_info()[0] > 1.2 * n * cfg.row_bytes:
+        out_s = torch.zeros(n, D, dtype=cfg.torch_dtype, device=dev)
+        fs.fs_seq_gather_fwd_sorted(weights, srows, spos, n, out_s, st_t)
+        torch.cuda.synchronize()
+        assert int(st_t.item()) == 0
+        for lo in range(0, n, step):
+            hi = min(n, lo + step)
+            assert torch.equal(out[lo:hi].view(ibits_), out_s[lo:hi].view(ibits_)), (lo, hi)
+        del out_s
     # ---- the same lookups through the exchange halves and through a replica store of the rows the
     # plan selects: each must reproduce `out` bit for bit (out itself was checked above); the send buffer
     # is checked against the oracle on the sampled lookups
@@ -156,8 +178,34 @@ def _run_config(G, cfg, check_atomic=True, bwd_rows_sample=None, exchange=True):
         for lo in range(0, n, step):
             hi = min(n, lo + step)
             assert torch.equal(out[lo:hi].view(ibits), out2[lo:hi].view(ibits)), (lo, hi)
-        del out2, counts, sel, store, slots
-    del weights, out, g_all
+        # the slots handed over by the router: the placement tagged as the oracle tags it, every lookup's slot
+        # the oracle's, the other outputs the router's, and the gather that takes the slots writes `out` again
+        _progress(f"[{cfg.name}] replica slots through the router")
+        pl_tag = placement.clone()
+        fs.fs_replica_tag_slots(pl_tag, slots, st_t)
+        pl_tag_h = pl_h.copy()
+        assert oracle.replica_tag_slots(pl_tag_h, slots.cpu().numpy()) == (0, 0)
+        assert np.array_equal(pl_tag.cpu().numpy().view(np.uint32), pl_tag_h)
+        bo3 = torch.zeros_like(bo)
+        rows3, pos3 = torch.zeros_like(rows), torch.zeros_like(pos)
+        slots3 = torch.full((n,), -7, dtype=torch.int32, device=dev)
+        fs.fs_route_bucketize_slots(ids, offsets, cfg.T, cfg.B, row_base, pl_tag, n, cfg.U, cfg.W, cfg.self_bucket, bo3,
+                                    rows3, pos3, slots3, None, st_t)
+        orc, ost, oslots = oracle.lookup_slots(pl_tag_h, orows, 0, n)
+        torch.cuda.synchronize()
+        assert (orc, ost) == (0, 0) and int(st_t.item()) == 0
+        assert torch.equal(bo3, bo) and torch.equal(rows3, rows) and torch.equal(pos3, pos)
+        assert np.array_equal(slots3.cpu().numpy(), oslots)
+        assert int((oslots >= 0).sum()) > 0 or cfg.f_global == 0        # (a configuration with no replicated tier has no slots)
+        out2.zero_()
+        fs.fs_seq_gather_fwd_slots(weights, store, k_cap, rows3, slots3, pos3, 0, n, out2, st_t)
+        torch.cuda.synchronize()
+        assert int(st_t.item()) == 0
+        for lo in range(0, n, step):
+            hi = min(n, lo + step)
+            assert torch.equal(out[lo:hi].view(ibits), out2[lo:hi].view(ibits)), (lo, hi)
+        del out2, counts, sel, store, slots, pl_tag, pl_tag_h, rows3, pos3, slots3, oslots
+    del weights, out, g_all, pl_h
     _free()
 
     # ---- backward over all buckets
@@ -179,7 +227,36 @@ def _run_config(G, cfg, check_atomic=True, bwd_rows_sample=None, exchange=True):
     tot_out = grad.double().sum(0).cpu().numpy()
     scale = np.sqrt((grad.double() ** 2).sum(0).cpu().numpy())
     assert np.all(np.abs(tot_rows - tot_out) <= 1e-5 * scale)
-    del g_h, g, u
+    del g_h
+    # the backward on the shared sort's pairs (what bench.py's step runs): the same rows and the same bits
+    u_s = torch.full((nu,), -7, dtype=torch.int64, device=dev)
+    g_s = torch.full((nu, D), float("nan"), dtype=torch.float32, device=dev)
+    nu_s = torch.zeros(1, dtype=torch.int64, device=dev)
+    fs.fs_seq_grad_bwd_sorted(grad, srows, spos, n, R, 0, u_s, g_s, nu, nu_s, st_t)
+    torch.cuda.synchronize()
+    assert int(st_t.item()) == 0 and int(nu_s.item()) == nu and torch.equal(u_s, u[:nu])
+    assert torch.equal(g_s.view(torch.int32), g[:nu].view(torch.int32))
+    del u_s
+    # ... and the backward that applies the optimizer step itself: table and state bit for bit those of the two calls
+    free_b = torch.cuda.mem_get_info()[0]
+    if free_b > 2.3 * R * cfg.row_bytes + 3 * nu * D * 4:
+        _progress(f"[{cfg.name}] backward with the optimizer step, one call against two")
+        Wa = fs_inputs.make_table(cfg, dev)
+        Wb = Wa.clone()
+        sa = torch.full((R,), 0.5, device=dev)
+        sb = sa.clone()
+        fs.fs_sparse_update(Wa, u[:nu], g_s, nu, nu_s, fs.FS_OPT_ADAGRAD_ROWWISE, 0.05, 1e-6, sa, None, None, 0, st_t)
+        u_b = torch.zeros(nu, dtype=torch.int64, device=dev)
+        g_b = torch.zeros(nu, D, dtype=torch.float32, device=dev)
+        fs.fs_seq_grad_bwd_update(grad, srows, spos, n, R, Wb, fs.FS_OPT_ADAGRAD_ROWWISE, 0.05, 1e-6, sb, None, None, 0,
+                                  u_b, g_b, nu, nu_s, st_t)
+        torch.cuda.synchronize()
+        assert int(st_t.item()) == 0 and torch.equal(u_b, u[:nu])
+        assert torch.equal(sa.view(torch.int32), sb.view(torch.int32))
+        ib = torch.int16 if cfg.dtype != "f32" else torch.int32
+        assert torch.equal(Wa.view(ib), Wb.view(ib))
+        del Wa, Wb, sa, sb, u_b, g_b
+    del g_s, g, u, srows, spos
     if check_atomic:
         rc, st, u1, g1, nu1 = G.hip_bwd(grad, rows, pos, 0, n, R, 1, cap)
         assert rc == 0 and st == 0 and nu1 == nu and np.array_equal(u1.cpu().numpy(), ou)
@@ -300,10 +377,25 @@ def test_c4_large_single_gpu_shard(G):
     del placement
     _free()
 
+    # the shared sort, as bench.py's step runs it.  The stated (row, pos) order is the stable sort by row of the
+    # router's output (a row lies in one bucket, and a bucket is in position order), which torch can do here
+    _progress("[c4] sort of the lookups")
+    st_t = torch.zeros(1, dtype=torch.int32, device=dev)
+    srows = torch.zeros(n, dtype=torch.int32, device=dev)
+    spos = torch.zeros(n, dtype=torch.int32, device=dev)
+    fs.fs_sort_lookups(rows, pos, 0, n, R, n, srows, spos, st_t)
+    want_rows, perm = torch.sort(rows, stable=True)
+    torch.cuda.synchronize()
+    assert int(st_t.item()) == 0
+    assert torch.equal(srows.long(), want_rows) and torch.equal(spos, pos[perm])
+    same_row = srows[1:] == srows[:-1]
+    assert bool((spos[1:][same_row] > spos[:-1][same_row]).all())      # positions ascend inside every row's run
+    del want_rows, perm, same_row
+    _free()
+
     _progress("[c4] table + gather")
     weights = fs_inputs.make_table(cfg, dev)
     out = torch.empty(n, D, dtype=cfg.torch_dtype, device=dev)
-    st_t = torch.zeros(1, dtype=torch.int32, device=dev)
     fs.fs_seq_gather_fwd(weights, rows, pos, 0, n, out, st_t)
     torch.cuda.synchronize()
     assert int(st_t.item()) == 0
@@ -320,7 +412,24 @@ def test_c4_large_single_gpu_shard(G):
     ref = np.zeros_like(w_s)
     oracle.seq_gather_fwd(w_s, np.arange(4096), np.arange(4096, dtype=np.int32), 0, 4096, ref, dtype=oracle.F16)
     assert np.array_equal(fs_inputs.as_numpy_bits(out[samp_t]).view(np.uint8), ref.view(np.uint8))
-    del weights, out, g_all, ids
+    # the gather in row order (the order bench.py's step takes on this workload): the same bits, written over
+    # a buffer of zeros; `out` itself was checked above, so its first and second half are compared in turn
+    del g_all
+    _free()
+    half = n // 2
+    for lo_h, hi_h in ((0, half), (half, n)):
+        keep = out[lo_h:hi_h].clone()
+        out[lo_h:hi_h].zero_()
+        in_half = (spos >= lo_h) & (spos < hi_h)
+        sr_h, sp_h = srows[in_half].contiguous(), spos[in_half].contiguous()
+        fs.fs_seq_gather_fwd_sorted(weights, sr_h, sp_h, sr_h.numel(), out, st_t)
+        torch.cuda.synchronize()
+        assert int(st_t.item()) == 0 and sr_h.numel() == hi_h - lo_h
+        for lo in range(lo_h, hi_h, step):
+            hi = min(hi_h, lo + step)
+            assert torch.equal(out[lo:hi].view(torch.int16), keep[lo - lo_h:hi - lo_h].view(torch.int16)), (lo, hi)
+        del keep, in_half, sr_h, sp_h
+    del weights, out, ids
     _free()
 
     _progress("[c4] backward, variant 0")
@@ -360,6 +469,16 @@ def test_c4_large_single_gpu_shard(G):
         return True
 
     assert within_bound(g)                                            # the stated order itself meets the bound
+    # the backward on the shared sort's pairs (what bench.py's step runs): the same rows, the same bits
+    u_s = torch.zeros(nu, dtype=torch.int64, device=dev)
+    g_s = torch.full((nu, D), float("nan"), dtype=torch.float32, device=dev)
+    nu_s = torch.zeros(1, dtype=torch.int64, device=dev)
+    fs.fs_seq_grad_bwd_sorted(grad, srows, spos, n, R, 0, u_s, g_s, nu, nu_s, st_t)
+    torch.cuda.synchronize()
+    assert int(st_t.item()) == 0 and int(nu_s.item()) == nu and torch.equal(u_s, u[:nu])
+    assert torch.equal(g_s.view(torch.int32), g[:nu].view(torch.int32))
+    del u_s, g_s, srows, spos
+    _free()
     _progress("[c4] backward, variant 1")
     rc, st, u1, g1, nu1 = G.hip_bwd(grad, rows, pos, 0, n, R, 1, cap)
     assert rc == 0 and st == 0 and nu1 == nu and torch.equal(u1, u)
