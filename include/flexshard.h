@@ -408,7 +408,8 @@ fs_status fs_seq_gather_fwd_sorted(
  * bad offsets (FS_DEV_BAD_OFFSETS) count nothing.
  * Host faults: NULL; n, R, T, B as above; budget_bytes < 0 or
  * bytes_per_row < 1 (FS_ERR_SIZE); unknown flag bits, TAG without SELECT
- * (FS_ERR_CONFIG).
+ * (FS_ERR_CONFIG); with ACCUMULATE, ids not 8-byte or counts not 4-byte
+ * aligned (FS_ERR_ALIGN).
  */
 #define FS_PLAN_ACCUMULATE 1
 #define FS_PLAN_SELECT 2

@@ -689,6 +689,7 @@ extern "C" fs_status fs_plan_replication(
     if (*workspace_bytes < ws.used || (reinterpret_cast<uintptr_t>(workspace) & 255)) return FS_ERR_WORKSPACE;
     if (!counts) return FS_ERR_NULL;
     if (acc && (!offsets || !row_base || (n > 0 && !ids))) return FS_ERR_NULL;
+    if (acc && ((reinterpret_cast<uintptr_t>(ids) & 7) || (reinterpret_cast<uintptr_t>(counts) & 3))) return FS_ERR_ALIGN;   // natural alignment: ids are read two at a time
     if (sel && !num_selected) return FS_ERR_NULL;
     if ((flags & FS_PLAN_TAG) && !placement) return FS_ERR_NULL;
     const int64_t cap = sel ? budget_bytes / bytes_per_row : 0;

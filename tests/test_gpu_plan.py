@@ -221,3 +221,29 @@ def test_histogram_row_base_beyond_R_drops_the_lookup(G):
     want = np.zeros(R, dtype=np.uint32)
     want[[1, 2, 3, 4]] = 1                                        # table 0
     assert np.array_equal(got, want)                              # 58 + 5 .. 58 + 8 are all >= 60: dropped
+
+
+def test_histogram_rejects_ids_off_their_natural_alignment(G):
+    """The histogram reads ids two at a time after stepping to a 16-byte boundary, which takes 8-byte aligned
+    ids: an ids pointer that is not is a host fault, and nothing is launched."""
+    import ctypes
+    import paper_2301_02959_amd as fs
+    dev = G.DEV
+    ids = torch.zeros(64, dtype=torch.int64, device=dev)
+    off = torch.tensor([0, 8], dtype=torch.int64, device=dev)
+    rb = torch.tensor([0, 10], dtype=torch.int64, device=dev)
+    counts = torch.zeros(16, dtype=torch.int32, device=dev)
+    ws = torch.zeros(1 << 20, dtype=torch.uint8, device=dev)
+    L = fs.lib()
+    P = lambda t, add=0: ctypes.c_void_p(t.data_ptr() + add)
+    z = ctypes.c_void_p(0)
+
+    def call(ids_ptr, counts_ptr):
+        size = ctypes.c_size_t(ws.numel())
+        return L.fs_plan_replication(ids_ptr, P(off), ctypes.c_int32(1), ctypes.c_int32(1), P(rb), ctypes.c_int64(8),
+                                     ctypes.c_int64(10), counts_ptr, ctypes.c_int32(A), ctypes.c_int64(0), ctypes.c_int64(1),
+                                     z, z, z, P(ws), ctypes.byref(size), z, z)
+    assert call(P(ids, 4), P(counts)) == 4 and call(P(ids), P(counts, 2)) == 4
+    assert call(P(ids, 8), P(counts, 4)) == 0                           # 8 mod 16 and 4 mod 16 are fine
+    torch.cuda.synchronize()
+    assert int(counts.sum().item()) == 8
