@@ -102,6 +102,34 @@ def test_two_billion_lookups():
     del bucket_start, counts
     torch.cuda.empty_cache()
 
+    # ---------------------------------------------------------------- the shared sort
+    _progress("[max] sort of the lookups")
+    srows = torch.empty(n, dtype=torch.int32, device=dev)
+    spos = torch.empty(n, dtype=torch.int32, device=dev)
+    assert fs.fs_sort_lookups(rows, pos, 0, n, R, n, srows, spos, st) == 0
+    torch.cuda.synchronize()
+    assert int(st.item()) == 0
+    _progress("[max] sort: properties")
+    per_row = torch.zeros(R, dtype=torch.int64, device=dev)
+    for lo in range(0, n, step):
+        hi = min(n, lo + step)
+        r, p = srows[lo:hi].long(), spos[lo:hi].long()
+        g = ids[p] + torch.where(p >= first_of_table1, E, 0)
+        assert torch.equal(r, g), lo                                              # every pair is a lookup of the batch
+        per_row += torch.bincount(r, minlength=R)
+        if hi - lo > 1:
+            up = (r[1:] > r[:-1]) | ((r[1:] == r[:-1]) & (p[1:] > p[:-1]))         # (row, pos) strictly ascending,
+            assert bool(up.all()), lo                                             # so no lookup appears twice
+        if lo > 0:
+            r0, p0 = int(srows[lo - 1]), int(spos[lo - 1])
+            assert (int(srows[lo]), int(spos[lo])) > (r0, p0)
+    for lo in range(0, n, step):                                                  # ... and every lookup once: the rows' counts
+        hi = min(n, lo + step)
+        per_row -= torch.bincount(rows[lo:hi], minlength=R)
+    assert not bool(per_row.any())
+    del per_row
+    torch.cuda.empty_cache()
+
     # ---------------------------------------------------------------- gather (16-byte rows)
     _progress("[max] gather")
     weights = torch.randn(R, D, device=dev, generator=gen)
@@ -117,7 +145,23 @@ def test_two_billion_lookups():
         g = ids[lo:hi] + torch.where(torch.arange(lo, hi, device=dev) >= first_of_table1, E, 0)
         ref = torch.index_select(w_bits, 0, g)
         assert not bool((out_bits[lo:hi] != ref).any()), lo
-    del out, weights, ids, w_bits, out_bits, ref
+    del ref
+    # the gather in row order over the same lookups: the same bits (checked a half of the output at a time
+    # against the copy the first gather wrote, so that no second output buffer is needed)
+    _progress("[max] gather in row order")
+    half = n // 2
+    for lo_h, hi_h in ((0, half), (half, n)):
+        keep = out_bits[lo_h:hi_h].clone()
+        out[lo_h:hi_h].zero_()
+        inside = (spos >= lo_h) & (spos < hi_h)
+        sr_h, sp_h = srows[inside].contiguous(), spos[inside].contiguous()
+        del inside
+        assert sr_h.numel() == hi_h - lo_h
+        assert fs.fs_seq_gather_fwd_sorted(weights, sr_h, sp_h, sr_h.numel(), out, st) == 0
+        torch.cuda.synchronize()
+        assert int(st.item()) == 0 and torch.equal(out_bits[lo_h:hi_h], keep), lo_h
+        del keep, sr_h, sp_h
+    del out, weights, ids, w_bits, out_bits
     torch.cuda.empty_cache()
 
     # ---------------------------------------------------------------- backward, integer-valued gradients
@@ -142,6 +186,15 @@ def test_two_billion_lookups():
     assert k == present.numel() and torch.equal(uniq[:k], present)
     assert int(want.abs().max()) < (1 << 24)                                       # every sum is an exact fp32 integer
     assert torch.equal(rg[:k].long(), want[present]) and torch.equal(rg[:k], rg[:k].round())
+    # the backward on the shared sort's pairs: the same rows, the same bits
+    _progress("[max] backward on the sorted pairs")
+    del want, seen
+    uniq_s = torch.empty(R, dtype=torch.int64, device=dev)
+    rg_s = torch.empty(R, D, dtype=torch.float32, device=dev)
+    assert fs.fs_seq_grad_bwd_sorted(grad, srows, spos, n, R, 0, uniq_s, rg_s, R, nu, st) == 0
+    torch.cuda.synchronize()
+    assert int(st.item()) == 0 and int(nu.item()) == k
+    assert torch.equal(uniq_s[:k], uniq[:k]) and torch.equal(rg_s[:k].view(torch.int32), rg[:k].view(torch.int32))
     _progress("[max] done")
 
 
